@@ -1,0 +1,307 @@
+"""fp64 CPU oracle for warm-started iterative GP marginal-likelihood optimisation.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, dense, obviously-correct
+definition of what the GPU hot path computes.  Only tests, the smoke check and
+the benchmark's cpu_baseline leg may import it; the product path never does,
+and nothing here imports the product package or its HIP library.
+
+Everything is NumPy/SciPy in float64.  Inputs that arrive as float32 are upcast
+exactly, so input rounding is never charged as an error of either side.
+
+Notation follows the paper (Section 2):
+    theta = (ell_1..ell_d, a, sigma)      lengthscales, signal scale, noise scale
+    K     = k(x, x; ell, a)               n x n kernel matrix
+    H     = K + sigma^2 I                 coefficient matrix
+    B     = [y, z_1..z_s]                 right-hand sides, column 0 is y
+    V     = [v_y, v_1..v_s] = H^{-1} B    solutions
+
+Readings where the paper is silent (it names the Matern-3/2 kernel with
+per-dimension lengthscales and a scalar signal scale in Section 4, prints no
+formula, and never mentions the squared exponential):
+    r^2_ij   = sum_k (x_ik - x_jk)^2 / ell_k^2        by explicit differences
+    SE-ARD   : K_ij = a^2 exp(-r^2_ij / 2)
+    Matern32 : K_ij = a^2 (1 + sqrt(3) r_ij) exp(-sqrt(3) r_ij)
+    the signal scale a is an amplitude (K is proportional to a^2);
+    the noise parameter is sigma with H = K + sigma^2 I (Section 2);
+    gradients are with respect to the constrained (ell, a, sigma).
+
+Pin status: every function below is pinned by tests/test_oracle_pins.py against
+something other than itself (scikit-learn / SciPy library routines, hand values,
+closed forms, finite differences, brute force).  The only unpinned quantity is
+the warm-vs-cold iteration *count* (the paper gives it only as stripped figures):
+"parity unpinned" for iteration numbers; the solutions themselves are pinned.
+"""
+from __future__ import annotations
+
+import numpy as np
+import scipy.linalg as sla
+
+SE = "se"
+MATERN32 = "matern32"
+_SQRT3 = np.sqrt(3.0)
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a), dtype=np.float64)
+
+
+# --------------------------------------------------------------------------
+# Kernel matrix and its derivatives (Section 2: k(x, x; vartheta); Section 4
+# names the Matern-3/2 ARD kernel with a scalar signal scale)
+# --------------------------------------------------------------------------
+def scaled_sqdist(Xa, Xb, ell):
+    """r^2_ij = sum_k (xa_ik - xb_jk)^2 / ell_k^2 by explicit differences."""
+    Xa, Xb, ell = _f64(Xa), _f64(Xb), _f64(ell)
+    r2 = np.zeros((Xa.shape[0], Xb.shape[0]))
+    for k in range(Xa.shape[1]):
+        diff = (Xa[:, k][:, None] - Xb[:, k][None, :]) / ell[k]
+        r2 += diff * diff
+    return r2
+
+
+def kernel_from_sqdist(r2, a, kind):
+    if kind == SE:
+        return a * a * np.exp(-0.5 * r2)
+    if kind == MATERN32:
+        r = np.sqrt(r2)
+        return a * a * (1.0 + _SQRT3 * r) * np.exp(-_SQRT3 * r)
+    raise ValueError(f"unknown kernel kind {kind!r}")
+
+
+def kernel_cross(Xa, Xb, ell, a, kind):
+    """k(Xa, Xb): pairwise evaluations, |Xa| x |Xb| (Section 2)."""
+    return kernel_from_sqdist(scaled_sqdist(Xa, Xb, ell), float(a), kind)
+
+
+def kernel_matrix(X, ell, a, kind):
+    """K = k(x, x; vartheta), n x n (Section 2)."""
+    return kernel_cross(X, X, ell, a, kind)
+
+
+def coefficient_matrix(X, ell, a, sigma, kind):
+    """H_theta = k(x, x) + sigma^2 I (Section 2)."""
+    K = kernel_matrix(X, ell, a, kind)
+    K[np.diag_indices_from(K)] += float(sigma) ** 2
+    return K
+
+
+def dK_dell(X, ell, a, kind, k):
+    """dK/d ell_k, n x n.
+
+    SE      : K_ij * D_ijk / ell_k^3                 with D_ijk = (x_ik - x_jk)^2
+    Matern32: 3 a^2 exp(-sqrt(3) r_ij) D_ijk / ell_k^3
+    (the Matern form has r cancelled, so coincident points give 0, not 0/0).
+    """
+    X, ell = _f64(X), _f64(ell)
+    a = float(a)
+    r2 = scaled_sqdist(X, X, ell)
+    D = (X[:, k][:, None] - X[:, k][None, :]) ** 2
+    if kind == SE:
+        return a * a * np.exp(-0.5 * r2) * D / ell[k] ** 3
+    if kind == MATERN32:
+        return 3.0 * a * a * np.exp(-_SQRT3 * np.sqrt(r2)) * D / ell[k] ** 3
+    raise ValueError(kind)
+
+
+def dK_da(X, ell, a, kind):
+    """dK/da = 2 K / a (K is proportional to a^2)."""
+    return 2.0 * kernel_matrix(X, ell, a, kind) / float(a)
+
+
+# --------------------------------------------------------------------------
+# Dense products and Cholesky solves (Section 2, the tractable-n route)
+# --------------------------------------------------------------------------
+def kmv_dense(X, ell, a, kind, V, sigma=None):
+    """K V, or (K + sigma^2 I) V when sigma is given.  Dense fp64 matmul."""
+    V = _f64(V)
+    out = kernel_matrix(X, ell, a, kind) @ V
+    if sigma is not None:
+        out = out + float(sigma) ** 2 * V
+    return out
+
+
+def kmv_rows(X, ell, a, kind, V, rows, sigma=None, col_block=32768):
+    """Exact rows (K V)[rows, :] against all n columns, never forming K.
+
+    For n too large for a dense K: O(len(rows) * n * (d + t)) work, column
+    blocks bound the memory.  Same definition as kmv_dense.
+    """
+    X, V = _f64(X), _f64(V)
+    rows = np.asarray(rows, dtype=np.int64)
+    Xr = X[rows]
+    out = np.zeros((rows.size, V.shape[1]))
+    for c0 in range(0, X.shape[0], col_block):
+        c1 = min(c0 + col_block, X.shape[0])
+        out += kernel_cross(Xr, X[c0:c1], ell, a, kind) @ V[c0:c1]
+    if sigma is not None:
+        out += float(sigma) ** 2 * V[rows]
+    return out
+
+
+def chol_solve(H, B):
+    """V* = H^{-1} B via Cholesky and two triangular solves (Section 2)."""
+    c, low = sla.cho_factor(_f64(H), lower=True)
+    return sla.cho_solve((c, low), _f64(B))
+
+
+# --------------------------------------------------------------------------
+# Log marginal likelihood and its exact gradient (Section 2, the equations
+# for L(theta) and grad L(theta))
+# --------------------------------------------------------------------------
+def mll(X, y, ell, a, sigma, kind):
+    """L = -1/2 y^T H^{-1} y - 1/2 log det H - n/2 log 2 pi."""
+    y = _f64(y).reshape(-1)
+    H = coefficient_matrix(X, ell, a, sigma, kind)
+    L = sla.cholesky(H, lower=True)
+    w = sla.solve_triangular(L, y, lower=True)
+    logdet = 2.0 * np.sum(np.log(np.diag(L)))
+    return -0.5 * (w @ w) - 0.5 * logdet - 0.5 * y.size * np.log(2.0 * np.pi)
+
+
+def dH_list(X, ell, a, sigma, kind):
+    """Yield dH/d theta_k for theta = (ell_1..ell_d, a, sigma), each n x n."""
+    X = _f64(X)
+    n, d = X.shape
+    for k in range(d):
+        yield dK_dell(X, ell, a, kind, k)
+    yield dK_da(X, ell, a, kind)
+    yield 2.0 * float(sigma) * np.eye(n)
+
+
+def mll_grad_exact(X, y, ell, a, sigma, kind):
+    """grad L = 1/2 (H^{-1}y)^T dH (H^{-1}y) - 1/2 tr(H^{-1} dH), d+2 entries."""
+    y = _f64(y).reshape(-1)
+    H = coefficient_matrix(X, ell, a, sigma, kind)
+    Hinv = chol_solve(H, np.eye(H.shape[0]))
+    alpha = Hinv @ y
+    g = []
+    for dH in dH_list(X, ell, a, sigma, kind):
+        g.append(0.5 * alpha @ (dH @ alpha) - 0.5 * np.sum(Hinv * dH))
+    return np.array(g)
+
+
+# --------------------------------------------------------------------------
+# Hutchinson gradient estimator (Section 2.1, "Gradient Estimator" and
+# "Linear System Solver": trace estimator substituted into grad L)
+# --------------------------------------------------------------------------
+def mll_grad_hutchinson(X, ell, a, sigma, kind, B, V=None):
+    """Stochastic gradient with probes Z = B[:, 1:], y = B[:, 0].
+
+    g_k = 1/2 v_y^T dH_k v_y - 1/(2s) sum_j v_j^T dH_k z_j
+    using z_j^T H^{-1} dH_k z_j = v_j^T dH_k z_j (H symmetric), 1/s as in the
+    trace-estimator equation.  V = H^{-1} B from Cholesky when not given; when
+    given (for example an iterative solver's output) the same formula is
+    evaluated at that V.
+    """
+    B = _f64(B)
+    if V is None:
+        V = chol_solve(coefficient_matrix(X, ell, a, sigma, kind), B)
+    V = _f64(V)
+    s = B.shape[1] - 1
+    vy, Vz, Z = V[:, 0], V[:, 1:], B[:, 1:]
+    g = []
+    for dH in dH_list(X, ell, a, sigma, kind):
+        quad = 0.5 * vy @ (dH @ vy)
+        tr = 0.0
+        if s > 0:
+            tr = np.sum(Vz * (dH @ Z)) / s
+        g.append(quad - 0.5 * tr)
+    return np.array(g)
+
+
+# --------------------------------------------------------------------------
+# Batched conjugate gradients, no preconditioner (Section 2.1 "Linear System
+# Solver", Appendix B stopping rule)
+# --------------------------------------------------------------------------
+def cg_batched(matvec, B, X0=None, tol=0.01, max_iters=1000):
+    """One independent Hestenes-Stiefel CG per column, run in lock step.
+
+    matvec(P) returns H P for an n x t block.  Per column c the iteration stops
+    ("freezes") once the recursively updated residual satisfies
+    ||r_c|| / ||b_c|| < tol_c (strict); the solve ends when every column is
+    frozen or after max_iters products.  A column with b_c = 0 has solution 0.
+
+    Returns (V, iters, relres) with iters = number of matvecs inside the loop
+    (the warm start's initial-residual product is not counted) and relres the
+    final recursive relative residuals.
+    """
+    B = _f64(B)
+    n, t = B.shape
+    tol = np.broadcast_to(np.asarray(tol, dtype=np.float64), (t,)).copy()
+    bnorm = np.sqrt(np.sum(B * B, axis=0))
+    if X0 is None:
+        X = np.zeros_like(B)
+        R = B.copy()
+    else:
+        X = _f64(X0).copy()
+        R = B - matvec(X)
+    zero_rhs = bnorm == 0.0
+    X[:, zero_rhs] = 0.0
+    R[:, zero_rhs] = 0.0
+    safe = np.where(zero_rhs, 1.0, bnorm)
+    rho = np.sum(R * R, axis=0)
+    relres = np.sqrt(rho) / safe
+    frozen = zero_rhs | (relres < tol)
+    P = R.copy()
+    iters = 0
+    while not frozen.all() and iters < max_iters:
+        AP = matvec(P)
+        iters += 1
+        gamma = np.sum(P * AP, axis=0)
+        live = ~frozen
+        alpha = np.zeros(t)
+        alpha[live] = rho[live] / gamma[live]
+        X += alpha * P
+        R -= alpha * AP
+        rho_new = np.where(live, np.sum(R * R, axis=0), rho)
+        relres = np.sqrt(rho_new) / safe
+        beta = np.zeros(t)
+        beta[live] = rho_new[live] / rho[live]
+        rho = rho_new
+        frozen = frozen | (relres < tol)
+        P = R + beta * P
+    return X, iters, relres
+
+
+def dense_matvec(H):
+    H = _f64(H)
+    return lambda P: H @ P
+
+
+# --------------------------------------------------------------------------
+# Positivity transform and Adam, as used by the outer loop (Section 4 and
+# Appendix B: softplus constraints, Adam with learning rate 0.1)
+# --------------------------------------------------------------------------
+def softplus(raw):
+    raw = _f64(raw)
+    return np.logaddexp(0.0, raw)
+
+
+def softplus_inverse(theta):
+    theta = _f64(theta)
+    return theta + np.log(-np.expm1(-theta))
+
+
+def softplus_grad(raw):
+    """d softplus(raw) / d raw = 1 / (1 + exp(-raw))."""
+    raw = _f64(raw)
+    return 1.0 / (1.0 + np.exp(-raw))
+
+
+def adam_ascent(raw0, grad_fn, steps, lr=0.1, b1=0.9, b2=0.999, eps=1e-8):
+    """Bias-corrected Adam maximising L over raw = softplus^{-1}(theta).
+
+    grad_fn(theta) returns dL/dtheta (constrained); the chain rule through the
+    softplus is applied here.  Returns the list of theta after every step.
+    """
+    raw = _f64(raw0).copy()
+    m = np.zeros_like(raw)
+    v = np.zeros_like(raw)
+    trace = []
+    for it in range(1, steps + 1):
+        g = grad_fn(softplus(raw)) * softplus_grad(raw)
+        m = b1 * m + (1 - b1) * g
+        v = b2 * v + (1 - b2) * g * g
+        raw = raw + lr * (m / (1 - b1 ** it)) / (np.sqrt(v / (1 - b2 ** it)) + eps)
+        trace.append(softplus(raw))
+    return trace

@@ -1,0 +1,336 @@
+"""Pins for the CPU oracle: every oracle function is checked against something
+other than itself (library routines, hand values, closed forms, finite
+differences, brute force).  No GPU, no HIP library.
+
+Each check is chosen so a plausible slip (dropped 1/2, wrong sign, wrong power of
+the lengthscale, amplitude-vs-variance, sigma-vs-sigma^2, 1/s missing, a
+transposed operand) makes at least one of them fail; test_planted_mistakes_are_caught
+demonstrates that on mutated copies of the formulas.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.linalg as sla
+import scipy.stats as st
+from scipy.spatial.distance import cdist
+from sklearn.gaussian_process.kernels import RBF, Matern
+
+from oracle import gp_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+KINDS = [orc.SE, orc.MATERN32]
+
+
+def _problem(n, d, seed, s=4):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n, d))
+    ell = rng.uniform(0.6, 1.8, size=d)
+    a = 1.3
+    sigma = 0.7
+    y = rng.standard_normal(n)
+    Z = rng.standard_normal((n, s))
+    return X, ell, a, sigma, y, Z
+
+
+# ---------------------------------------------------------------- kernel matrix
+def test_kernel_hand_values():
+    """n = 2, d = 1 values worked by hand (file header gives the arithmetic)."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "kernel_hand_values.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) >= 4
+    for kind, x0, x1, ell, a, expect in rows:
+        X = np.array([[float(x0)], [float(x1)]])
+        K = orc.kernel_matrix(X, [float(ell)], float(a), kind)
+        assert K[0, 1] == pytest.approx(float(expect), rel=1e-12)
+        assert K[1, 0] == pytest.approx(float(expect), rel=1e-12)
+        assert K[0, 0] == pytest.approx(float(a) ** 2, rel=1e-15)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_kernel_matches_sklearn(kind):
+    """ARD kernels agree with scikit-learn's independent implementations."""
+    X, ell, a, _, _, _ = _problem(40, 5, 1)
+    ref = (RBF(length_scale=ell) if kind == orc.SE else Matern(length_scale=ell, nu=1.5))(X)
+    K = orc.kernel_matrix(X, ell, a, kind)
+    np.testing.assert_allclose(K, a * a * ref, rtol=1e-12, atol=1e-14)
+
+
+def test_sqdist_matches_scipy_cdist():
+    X, ell, *_ = _problem(30, 7, 2)
+    np.testing.assert_allclose(orc.scaled_sqdist(X, X, ell), cdist(X / ell, X / ell, "sqeuclidean"),
+                               rtol=1e-11, atol=1e-12)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_kernel_invariants(kind):
+    X, ell, a, _, _, _ = _problem(60, 4, 3)
+    X[7] = X[3]                                   # a duplicated row
+    K = orc.kernel_matrix(X, ell, a, kind)
+    assert np.array_equal(K, K.T)
+    np.testing.assert_allclose(np.diag(K), a * a, rtol=1e-15)
+    assert K[7, 3] == pytest.approx(a * a, rel=1e-15)
+    assert (K > 0).all() and (K <= a * a * (1 + 1e-15)).all()
+    assert np.linalg.eigvalsh(K).min() > -1e-10 * K.shape[0]
+    # ell -> infinity: K -> a^2 11^T
+    Kinf = orc.kernel_matrix(X, np.full(4, 1e9), a, kind)
+    np.testing.assert_allclose(Kinf, a * a, rtol=1e-12)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_kernel_derivatives_by_finite_differences(kind):
+    X, ell, a, _, _, _ = _problem(12, 3, 4)
+    X[5] = X[2]                                   # coincident pair: derivative must be finite
+    h = 1e-6
+    for k in range(3):
+        e = np.zeros(3)
+        e[k] = h
+        fd = (orc.kernel_matrix(X, ell + e, a, kind) - orc.kernel_matrix(X, ell - e, a, kind)) / (2 * h)
+        dK = orc.dK_dell(X, ell, a, kind, k)
+        assert np.isfinite(dK).all() and dK[5, 2] == 0.0
+        np.testing.assert_allclose(dK, fd, rtol=1e-6, atol=1e-8)
+    fd = (orc.kernel_matrix(X, ell, a + h, kind) - orc.kernel_matrix(X, ell, a - h, kind)) / (2 * h)
+    np.testing.assert_allclose(orc.dK_da(X, ell, a, kind), fd, rtol=1e-7, atol=1e-9)
+
+
+# ---------------------------------------------------------------- products
+@pytest.mark.parametrize("kind", KINDS)
+def test_kmv_rows_equals_brute_force(kind):
+    X, ell, a, sigma, _, _ = _problem(50, 3, 5)
+    rng = np.random.default_rng(0)
+    V = rng.standard_normal((50, 3))
+    rows = np.array([0, 7, 49, 7])
+    got = orc.kmv_rows(X, ell, a, kind, V, rows, sigma=sigma, col_block=16)
+    for out_row, i in zip(got, rows):
+        for c in range(3):
+            acc = 0.0
+            for j in range(50):
+                r2 = sum(((X[i, k] - X[j, k]) / ell[k]) ** 2 for k in range(3))
+                if kind == orc.SE:
+                    kij = a * a * math.exp(-0.5 * r2)
+                else:
+                    r = math.sqrt(r2)
+                    kij = a * a * (1 + math.sqrt(3) * r) * math.exp(-math.sqrt(3) * r)
+                acc += kij * V[j, c]
+            acc += sigma ** 2 * V[i, c]
+            assert out_row[c] == pytest.approx(acc, rel=1e-11, abs=1e-12)
+    dense = orc.kmv_dense(X, ell, a, kind, V, sigma=sigma)
+    np.testing.assert_allclose(got, dense[rows], rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_kmv_closed_form_infinite_lengthscale(kind):
+    """ell -> inf: K V = a^2 1 (1^T V)."""
+    X, _, a, _, _, _ = _problem(33, 2, 6)
+    V = np.random.default_rng(1).standard_normal((33, 5))
+    got = orc.kmv_dense(X, np.full(2, 1e9), a, kind, V)
+    np.testing.assert_allclose(got, a * a * np.ones((33, 1)) * V.sum(axis=0), rtol=1e-10)
+
+
+# ---------------------------------------------------------------- MLL and exact gradient
+@pytest.mark.parametrize("kind", KINDS)
+def test_mll_matches_scipy_logpdf(kind):
+    X, ell, a, sigma, y, _ = _problem(25, 3, 7)
+    H = a * a * (RBF(ell) if kind == orc.SE else Matern(ell, nu=1.5))(X) + sigma ** 2 * np.eye(25)
+    ref = st.multivariate_normal(mean=np.zeros(25), cov=H).logpdf(y)
+    assert orc.mll(X, y, ell, a, sigma, kind) == pytest.approx(ref, rel=1e-11)
+
+
+def _fd_grad(X, y, ell, a, sigma, kind, h=1e-5):
+    theta = np.concatenate([ell, [a, sigma]])
+    g = np.zeros_like(theta)
+    d = len(ell)
+    for k in range(theta.size):
+        tp, tm = theta.copy(), theta.copy()
+        tp[k] += h
+        tm[k] -= h
+        g[k] = (orc.mll(X, y, tp[:d], tp[d], tp[d + 1], kind)
+                - orc.mll(X, y, tm[:d], tm[d], tm[d + 1], kind)) / (2 * h)
+    return g
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_exact_gradient_vs_central_differences(kind):
+    X, ell, a, sigma, y, _ = _problem(24, 3, 8)
+    X[9] = X[4]
+    g = orc.mll_grad_exact(X, y, ell, a, sigma, kind)
+    fd = _fd_grad(X, y, ell, a, sigma, kind)
+    assert g.shape == (5,)
+    np.testing.assert_allclose(g, fd, rtol=2e-6, atol=1e-7)
+
+
+# ---------------------------------------------------------------- Hutchinson estimator
+@pytest.mark.parametrize("kind", KINDS)
+def test_hutchinson_exact_when_probe_covariance_is_identity(kind):
+    """s = n, Z = sqrt(n) I gives (1/s) sum z z^T = I, so the estimator is the exact gradient."""
+    n = 20
+    X, ell, a, sigma, y, _ = _problem(n, 2, 9)
+    B = np.concatenate([y[:, None], np.sqrt(n) * np.eye(n)], axis=1)
+    g = orc.mll_grad_hutchinson(X, ell, a, sigma, kind, B)
+    np.testing.assert_allclose(g, orc.mll_grad_exact(X, y, ell, a, sigma, kind), rtol=1e-9, atol=1e-11)
+    # and against finite differences of the closed-form MLL directly
+    np.testing.assert_allclose(g, _fd_grad(X, y, ell, a, sigma, kind), rtol=2e-6, atol=1e-7)
+
+
+def test_hutchinson_is_unbiased():
+    n, s = 16, 8
+    X, ell, a, sigma, y, _ = _problem(n, 2, 10)
+    exact = orc.mll_grad_exact(X, y, ell, a, sigma, orc.MATERN32)
+    rng = np.random.default_rng(123)
+    samples = []
+    for _ in range(400):
+        B = np.concatenate([y[:, None], rng.standard_normal((n, s))], axis=1)
+        samples.append(orc.mll_grad_hutchinson(X, ell, a, sigma, orc.MATERN32, B))
+    samples = np.array(samples)
+    se = samples.std(axis=0, ddof=1) / np.sqrt(len(samples))
+    assert (np.abs(samples.mean(axis=0) - exact) < 4.0 * se + 1e-12).all()
+
+
+def test_hutchinson_at_given_V_noise_component_identity():
+    """dL/dsigma from the estimator is the pure vector identity
+    sigma (v_y^T v_y - (1/s) sum_j v_j^T z_j), for any V."""
+    X, ell, a, sigma, y, Z = _problem(18, 3, 11)
+    B = np.concatenate([y[:, None], Z], axis=1)
+    V = np.random.default_rng(5).standard_normal(B.shape)
+    g = orc.mll_grad_hutchinson(X, ell, a, sigma, orc.SE, B, V=V)
+    s = Z.shape[1]
+    assert g[-1] == pytest.approx(sigma * (V[:, 0] @ V[:, 0] - np.sum(V[:, 1:] * Z) / s), rel=1e-12)
+    # dL/da through one K-product: (2/a) [1/2 v_y^T K v_y - 1/(2s) sum v_j^T K z_j]
+    K = a * a * RBF(ell)(X)
+    ga = (2 / a) * (0.5 * V[:, 0] @ K @ V[:, 0] - np.sum(V[:, 1:] * (K @ Z)) / (2 * s))
+    assert g[-2] == pytest.approx(ga, rel=1e-11)
+
+
+# ---------------------------------------------------------------- probes (Lemma 2)
+@pytest.mark.parametrize("law,fourth", [("gaussian", 3.0), ("rademacher", 1.0)])
+def test_probe_generator_lemma2(law, fourth):
+    """E ||((1/s) sum z z^T - I) c||^2 = (E z^4 + n - 2) / s for unit c (Appendix A, Lemma 2)."""
+    from paper_2405_18328_amd.inputs import draw_probes
+    n, s, reps = 12, 6, 6000
+    rng = np.random.default_rng(77)
+    c = rng.standard_normal(n)
+    c /= np.linalg.norm(c)
+    vals = np.empty(reps)
+    for i in range(reps):
+        Z = draw_probes(rng, n, s, law)
+        vals[i] = np.sum((Z @ (Z.T @ c) / s - c) ** 2)
+    expect = (fourth + n - 2) / s
+    assert abs(vals.mean() - expect) < 4.0 * vals.std(ddof=1) / np.sqrt(reps)
+
+
+# ---------------------------------------------------------------- CG
+@pytest.mark.parametrize("kind", KINDS)
+def test_cg_reaches_cholesky_solution_within_n_iterations(kind):
+    n = 24
+    X, ell, a, sigma, y, Z = _problem(n, 2, 12)
+    H = orc.coefficient_matrix(X, ell, a, sigma, kind)
+    B = np.concatenate([y[:, None], Z], axis=1)
+    V, iters, relres = orc.cg_batched(orc.dense_matvec(H), B, tol=1e-10, max_iters=10 * n)
+    # exact arithmetic terminates in <= n steps; allow a couple more for rounding
+    assert iters <= n + 2
+    np.testing.assert_allclose(V, np.linalg.solve(H, B), rtol=1e-7, atol=1e-9)
+    true_rel = np.linalg.norm(H @ V - B, axis=0) / np.linalg.norm(B, axis=0)
+    assert (true_rel < 1e-9).all() and (relres < 1e-10).all()
+
+
+def test_cg_sherman_morrison_closed_form():
+    """ell -> inf: (sigma^2 I + a^2 11^T)^{-1} b = (b - a^2 1 (1^T b)/(sigma^2 + n a^2)) / sigma^2."""
+    n = 40
+    X, _, a, sigma, y, Z = _problem(n, 2, 13)
+    H = orc.coefficient_matrix(X, np.full(2, 1e9), a, sigma, orc.SE)
+    B = np.concatenate([y[:, None], Z], axis=1)
+    V, iters, _ = orc.cg_batched(orc.dense_matvec(H), B, tol=1e-12, max_iters=50)
+    closed = (B - a * a * np.ones((n, 1)) * B.sum(axis=0) / (sigma ** 2 + n * a * a)) / sigma ** 2
+    np.testing.assert_allclose(V, closed, rtol=1e-8, atol=1e-10)
+    assert iters <= 3            # two distinct eigenvalues
+
+
+def test_cg_stopping_rule_freeze_and_warm_start():
+    n = 30
+    X, ell, a, sigma, y, Z = _problem(n, 3, 14)
+    H = orc.coefficient_matrix(X, ell, a, sigma, orc.MATERN32)
+    B = np.concatenate([y[:, None], Z, np.zeros((n, 1))], axis=1)      # last column: b = 0
+    tol = np.array([0.01] + [0.1] * Z.shape[1] + [0.01])               # Appendix B tolerances
+    V, iters, relres = orc.cg_batched(orc.dense_matvec(H), B, tol=tol, max_iters=500)
+    assert (relres < tol).all() and np.all(V[:, -1] == 0.0)
+    true_rel = np.linalg.norm(H @ V[:, :-1] - B[:, :-1], axis=0) / np.linalg.norm(B[:, :-1], axis=0)
+    assert (true_rel < tol[:-1] * 1.0001).all()
+    # x0 = an exact solution: zero iterations, solution returned unchanged
+    Vstar = np.linalg.solve(H, B)
+    V2, it2, _ = orc.cg_batched(orc.dense_matvec(H), B, X0=Vstar, tol=1e-8, max_iters=500)
+    assert it2 == 0 and np.array_equal(V2, Vstar)
+    # warm start from a nearby solution needs fewer iterations than a cold start
+    H2 = orc.coefficient_matrix(X, ell * 1.02, a, sigma, orc.MATERN32)
+    _, it_cold, _ = orc.cg_batched(orc.dense_matvec(H2), B, tol=1e-3, max_iters=500)
+    _, it_warm, _ = orc.cg_batched(orc.dense_matvec(H2), B, X0=Vstar, tol=1e-3, max_iters=500)
+    assert it_warm < it_cold
+    # max_iters cap is honoured
+    _, it_cap, rr = orc.cg_batched(orc.dense_matvec(H), B, tol=1e-12, max_iters=2)
+    assert it_cap == 2 and (rr[:-1] > 1e-12).any()
+
+
+def test_warm_start_first_order_taylor_is_second_order_accurate():
+    """Section 3: v(t+1) ~ v(t) - H_t^{-1} (H_{t+1} - H_t) v(t); halving the step
+    in theta must quarter the error of that approximation."""
+    n = 20
+    X, ell, a, sigma, y, _ = _problem(n, 2, 15)
+    b = y[:, None]
+    H0 = orc.coefficient_matrix(X, ell, a, sigma, orc.MATERN32)
+    v0 = np.linalg.solve(H0, b)
+    errs = []
+    for step in (0.02, 0.01, 0.005):
+        H1 = orc.coefficient_matrix(X, ell * (1 + step), a * (1 + step), sigma * (1 - step), orc.MATERN32)
+        approx = v0 - np.linalg.solve(H0, (H1 - H0) @ v0)
+        errs.append(np.linalg.norm(np.linalg.solve(H1, b) - approx))
+        # warm start is closer to the new solution than zero, in the H-norm (Fig. 1 claim)
+        v1 = np.linalg.solve(H1, b)
+        assert (v0 - v1).T @ H1 @ (v0 - v1) < v1.T @ H1 @ v1
+    assert errs[0] / errs[1] == pytest.approx(4.0, rel=0.15)
+    assert errs[1] / errs[2] == pytest.approx(4.0, rel=0.15)
+
+
+# ---------------------------------------------------------------- outer loop pieces
+def test_softplus_and_adam():
+    t = np.array([0.05, 1.0, 30.0])
+    np.testing.assert_allclose(orc.softplus(orc.softplus_inverse(t)), t, rtol=1e-12)
+    h = 1e-6
+    r = np.array([-2.0, 0.3, 4.0])
+    np.testing.assert_allclose(orc.softplus_grad(r), (orc.softplus(r + h) - orc.softplus(r - h)) / (2 * h), rtol=1e-8)
+    # Adam's first step moves every coordinate by lr in the direction of the gradient sign
+    raw0 = orc.softplus_inverse(np.array([1.0, 1.0]))
+    out = orc.adam_ascent(raw0, lambda th: np.array([3.0, -0.2]), steps=1, lr=0.1)
+    np.testing.assert_allclose(orc.softplus_inverse(out[0]) - raw0, [0.1, -0.1], rtol=1e-6)
+    # ascent on a concave quadratic converges to its maximiser
+    target = np.array([0.8, 2.0])
+    tr = orc.adam_ascent(raw0, lambda th: -(th - target), steps=400, lr=0.05)
+    np.testing.assert_allclose(tr[-1], target, atol=2e-2)
+
+
+# ---------------------------------------------------------------- planted mistakes
+def test_planted_mistakes_are_caught():
+    """Mutated copies of the gradient formula (mistakes planted here, on the CPU)
+    disagree with finite differences of the closed-form MLL, so the pins above have teeth."""
+    X, ell, a, sigma, y, _ = _problem(16, 2, 16)
+    kind = orc.SE
+    fd = _fd_grad(X, y, ell, a, sigma, kind)
+    H = orc.coefficient_matrix(X, ell, a, sigma, kind)
+    Hinv = np.linalg.inv(H)
+    alpha = Hinv @ y
+    dHs = list(orc.dH_list(X, ell, a, sigma, kind))
+
+    def grad(quad_coef, tr_coef, dH_mut=lambda k, M: M):
+        return np.array([quad_coef * alpha @ (dH_mut(k, M) @ alpha) + tr_coef * np.sum(Hinv * dH_mut(k, M))
+                         for k, M in enumerate(dHs)])
+
+    good = grad(0.5, -0.5)
+    np.testing.assert_allclose(good, fd, rtol=2e-6, atol=1e-7)
+    mutants = {
+        "dropped half": grad(1.0, -0.5),
+        "trace sign": grad(0.5, 0.5),
+        "ell^2 instead of ell^3": grad(0.5, -0.5, lambda k, M: M * ell[k] if k < 2 else M),
+        "variance-style dK/da": grad(0.5, -0.5, lambda k, M: M / 2 if k == 2 else M),
+        "dH/dsigma = I": grad(0.5, -0.5, lambda k, M: M / (2 * sigma) if k == 3 else M),
+    }
+    for name, g in mutants.items():
+        assert not np.allclose(g, fd, rtol=1e-3, atol=1e-6), name
