@@ -1,0 +1,141 @@
+/*
+ * gpws.h -- C ABI of libgpws: the hot path of warm-started marginal-likelihood
+ * optimisation for iterative Gaussian processes on one AMD MI355X (gfx950).
+ *
+ * The path (paper Section 2.1): a first-order optimiser needs estimates of the
+ * gradient of the log marginal likelihood; the estimate needs
+ * H^{-1}[y, z_1..z_s] for H = k(x,x) + sigma^2 I; conjugate gradients obtains it
+ * from products H*V that are evaluated matrix-free (K is never stored).  The
+ * warm start (Section 3) passes the previous outer step's solution as x0.
+ *
+ * Conventions
+ *   - Every pointer named d* is DEVICE memory owned by the caller; every
+ *     pointer named h* is HOST memory owned by the caller.  The library owns
+ *     only what lives inside gp_ctx and frees it in gp_destroy.
+ *   - Matrices are row-major fp32: element (i, c) of an n x t block is
+ *     p[i*ld + c], ld >= t.  Column 0 of a right-hand-side block is y, columns
+ *     1..s are the probes z_j; t = s + 1.
+ *   - All work is enqueued on the HIP stream given to gp_create.  Calls that
+ *     return host results (gp_cg_solve, gp_mll_grad) synchronise that stream
+ *     before returning; gp_set_theta and gp_kmv do not.
+ *   - theta = (ell_1..ell_d, a, sigma): lengthscales, signal scale (amplitude,
+ *     K is proportional to a^2), noise scale (H = K + sigma^2 I).
+ *   - No call aborts or throws.  Return value: 0 = GP_OK, > 0 = result usable
+ *     but a condition is flagged, < 0 = error (nothing useful was written);
+ *     gp_last_error gives the text.  Arguments are validated before any launch.
+ *   - One context must not be used from two host threads at once.
+ */
+#ifndef GPWS_H
+#define GPWS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gp_ctx gp_ctx;
+
+enum { GP_SE_ARD = 0, GP_MATERN32_ARD = 1 };
+
+enum {
+  GP_OK = 0,
+  GP_NOT_CONVERGED = 1,   /* max_iters reached before every column met its tolerance */
+  GP_ERR_ARG = -1,        /* NULL pointer, bad size, bad leading dimension, theta not set */
+  GP_ERR_HIP = -2,        /* a HIP runtime call failed */
+  GP_ERR_WORKSPACE = -3,  /* dWork too small or misaligned */
+  GP_ERR_BREAKDOWN = -4   /* CG met p^T H p <= 0 or a non-finite value */
+};
+
+/* Largest input dimension and right-hand-side count the kernels are built for. */
+#define GP_MAX_D 126
+#define GP_MAX_T 1024
+
+/*
+ * Create a context for n training inputs of dimension d (paper Section 2: the
+ * inputs x of the regression model).  dX: device, row-major n x d fp32; it is
+ * read at every gp_set_theta and must stay valid and unchanged until
+ * gp_destroy.  hip_stream: a hipStream_t (NULL = the default stream).
+ * kernel: GP_SE_ARD      k = a^2 exp(-r^2/2)
+ *         GP_MATERN32_ARD k = a^2 (1 + sqrt(3) r) exp(-sqrt(3) r)
+ *         with r^2 = sum_k (x_ik - x_jk)^2 / ell_k^2  (Section 4 names the
+ *         Matern-3/2 kernel with per-dimension lengthscales and a scalar
+ *         signal scale; the formulas are the standard ones).
+ * Errors: GP_ERR_ARG for n < 1, d < 1, d > GP_MAX_D, unknown kernel, NULL
+ * pointers; GP_ERR_HIP if device allocation fails.
+ */
+int gp_create(gp_ctx** out, int kernel, int64_t n, int d, const float* dX, void* hip_stream);
+
+/* Free everything the context owns.  NULL is accepted. */
+int gp_destroy(gp_ctx* ctx);
+
+/*
+ * Set the hyperparameters theta (Section 2: theta = {vartheta, sigma}).
+ * h_lengthscale: d positive doubles; signal_scale > 0; noise_scale >= 0.
+ * Rebuilds the scaled copy of the inputs the tile kernels read (O(n d) device
+ * work, asynchronous).  Must be called before any of the calls below.
+ */
+int gp_set_theta(gp_ctx* ctx, const double* h_lengthscale, double signal_scale, double noise_scale);
+
+/*
+ * OUT = K V (add_noise = 0) or (K + sigma^2 I) V (add_noise = 1): the
+ * matrix-free product at the heart of every solver iteration (Section 2.1,
+ * "Linear System Solver").  dV: n x t, leading dimension ldv; dOut: n x t,
+ * leading dimension ldo; dOut must not overlap dV.  1 <= t <= GP_MAX_T.
+ * Asynchronous on the context's stream.
+ */
+int gp_kmv(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo, int add_noise);
+
+/* Bytes of device workspace gp_cg_solve needs for t right-hand sides (0 on bad arguments). */
+size_t gp_workspace_bytes(const gp_ctx* ctx, int t);
+
+/*
+ * Solve H [v_y, v_1..v_s] = [y, z_1..z_s] (the batched system of Section 2.1)
+ * by conjugate gradients without a preconditioner (Appendix B), one
+ * Hestenes-Stiefel recurrence per column run in lock step so that all columns
+ * share each product H P.
+ *   dB   : n x t right-hand sides (ldb).
+ *   dX0  : n x t initial guess (same leading dimension ldv as dV) or NULL for
+ *          zeros.  Passing the previous outer step's solution is the warm start
+ *          of Section 3.  dX0 may be the same pointer as dV.
+ *   dV   : n x t solution out (ldv).
+ *   h_tol: t relative-residual tolerances; column c stops being updated once
+ *          its recursively updated residual satisfies ||r_c|| / ||b_c|| < tol_c
+ *          (Appendix B: 0.01 for the y system, 0.1 for the probe systems).
+ *          A column with b_c = 0 gets the solution 0.
+ *   max_iters >= 0: cap on the products inside the loop.
+ *   dWork/work_bytes: device scratch, at least gp_workspace_bytes(ctx, t),
+ *          256-byte aligned.  Nothing of size n x t is allocated by the call.
+ *   h_iters     : out, products H P done inside the loop.
+ *   h_kmv_count : out, all products including the warm start's initial residual.
+ *   h_relres    : out, t final recursive relative residuals.
+ * Returns GP_OK, GP_NOT_CONVERGED (dV holds the last iterate), or an error.
+ * Synchronises the stream.
+ */
+int gp_cg_solve(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv,
+                int t, const float* h_tol, int max_iters, void* dWork, size_t work_bytes,
+                int* h_iters, int* h_kmv_count, float* h_relres);
+
+/*
+ * Stochastic estimate of the gradient of the log marginal likelihood (Section 2
+ * gradient equation with the trace replaced by the s-probe estimator of
+ * Section 2.1, normalised by 1/s):
+ *   g_k = 1/2 v_y^T (dH/dtheta_k) v_y - 1/(2s) sum_j v_j^T (dH/dtheta_k) z_j
+ * evaluated matrix-free in one tile pass over all pairs (i, j).
+ *   dV: n x t solutions [v_y, v_1..v_s] (ldv); dB: n x t [y, z_1..z_s] (ldb);
+ *   t = s + 1 >= 1 (s = 0 leaves only the quadratic term).
+ *   h_grad: out, d + 2 doubles: dL/d ell_1..ell_d, dL/da, dL/dsigma, with
+ *   respect to the constrained parameters (a softplus chain rule is the caller's).
+ * Synchronises the stream.
+ */
+int gp_mll_grad(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int64_t ldb, int t,
+                double* h_grad);
+
+/* Text of the last error on this context ("" if none).  Never NULL. */
+const char* gp_last_error(const gp_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GPWS_H */

@@ -1,0 +1,422 @@
+// Batched conjugate gradients without a preconditioner (paper Section 2.1
+// "Linear System Solver", Appendix B): one Hestenes-Stiefel recurrence per
+// column, all columns sharing each matrix-free product H P.  A column is frozen
+// (no further updates) once its recursive relative residual is below its
+// tolerance; the solve ends when every column is frozen.
+//
+// The vector part is HBM-bound streaming.  X, R, P, HP live in the caller's
+// workspace as contiguous n4 x t fp32 arrays (n4 = n rounded up to 4, padding
+// rows kept at zero), so every kernel walks them as one flat float4 stream.
+// The grid is a multiple of t workgroups, which makes each thread's stride a
+// multiple of t: a thread always sees the same 4 columns and keeps their
+// partial dot products in registers.  Per-column sums go thread -> LDS
+// (fixed-order gather) -> per-workgroup fp64 partials -> a one-workgroup
+// finalise kernel; nothing uses atomics, so a solve is bit-reproducible.
+#include "gpws_internal.h"
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int VT = 256;                 // threads per workgroup in the streaming kernels
+constexpr int VW = 4 * VT;              // flat elements one workgroup covers per step
+constexpr int FT = 1024;                // threads of the finalise kernels
+
+struct CgFlags {
+  int all_done;
+  int breakdown;
+  int iters;
+  int pad;
+};
+
+struct CgDev {
+  CgFlags* flags;
+  double* rho;      // [t] current r^T r
+  double* bn2;      // [t] ||b||^2
+  float* alpha;     // [t]
+  float* beta;      // [t]
+  float* tol;       // [t]
+  float* relres;    // [t]
+  int* frozen;      // [t]
+  int* zero_rhs;    // [t]
+  double* part;     // [G][t] workgroup partials
+  double* part2;    // [G][t] second set (init only)
+};
+
+// Sum, for every column c, the per-thread values of the threads that hold c.
+// Thread `tid` holds flat positions 4*tid..4*tid+3 of a 1024-wide window that
+// starts at flat offset `base`; position p belongs to column (base + p) % t.
+__device__ __forceinline__ void block_column_sums(const float v[4], int t, int base_mod, double* out,
+                                                  float* sh /* [VW] */) {
+  const int tid = threadIdx.x;
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < 4; ++q) sh[4 * tid + q] = v[q];
+  __syncthreads();
+  for (int c = tid; c < t; c += VT) {
+    int p0 = c - base_mod;
+    if (p0 < 0) p0 += t;
+    double s = 0.0;
+    for (int p = p0; p < VW; p += t) s += (double)sh[p];
+    out[c] = s;
+  }
+}
+
+__device__ __forceinline__ void thread_columns(int t, int64_t e0, int c[4]) {
+  int c0 = (int)(e0 % t);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    c[q] = c0;
+    c0 = (c0 + 1 == t) ? 0 : c0 + 1;
+  }
+}
+
+// X <- X0 (or 0), R <- B, partial ||b||^2.  Rows >= n of the padded arrays are zeroed.
+__global__ __launch_bounds__(VT) void cg_load_kernel(const float* __restrict__ B, int64_t ldb,
+                                                     const float* __restrict__ X0, int64_t ldx, int64_t n,
+                                                     int64_t n4, int t, float* __restrict__ X,
+                                                     float* __restrict__ R, double* __restrict__ part) {
+  __shared__ float sh[VW];
+  const int64_t total = n4 * t;
+  const int64_t stride = (int64_t)gridDim.x * VW;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int64_t e = ((int64_t)blockIdx.x * VT + threadIdx.x) * 4; e < total; e += stride) {
+    f32x4 b, x;
+    int64_t i = e / t;
+    int c = (int)(e - i * t);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const bool live = i < n;
+      b[q] = live ? B[i * ldb + c] : 0.0f;
+      x[q] = (live && X0) ? X0[i * ldx + c] : 0.0f;
+      acc[q] = fmaf(b[q], b[q], acc[q]);
+      if (++c == t) { c = 0; ++i; }
+    }
+    *reinterpret_cast<f32x4*>(X + e) = x;
+    *reinterpret_cast<f32x4*>(R + e) = b;
+  }
+  block_column_sums(acc, t, (int)(((int64_t)blockIdx.x * VW) % t), part + (int64_t)blockIdx.x * t, sh);
+}
+
+// R <- R - HX (warm start: initial residual), then (both cases) P <- R, partial r^T r
+__global__ __launch_bounds__(VT) void cg_resid_kernel(float* __restrict__ R, const float* __restrict__ HX,
+                                                      int subtract, float* __restrict__ P, int64_t total, int t,
+                                                      double* __restrict__ part) {
+  __shared__ float sh[VW];
+  const int64_t stride = (int64_t)gridDim.x * VW;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int64_t e = ((int64_t)blockIdx.x * VT + threadIdx.x) * 4; e < total; e += stride) {
+    f32x4 r = *reinterpret_cast<const f32x4*>(R + e);
+    if (subtract) {
+      const f32x4 hx = *reinterpret_cast<const f32x4*>(HX + e);
+      r -= hx;
+      *reinterpret_cast<f32x4*>(R + e) = r;
+    }
+    *reinterpret_cast<f32x4*>(P + e) = r;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] = fmaf(r[q], r[q], acc[q]);
+  }
+  block_column_sums(acc, t, (int)(((int64_t)blockIdx.x * VW) % t), part + (int64_t)blockIdx.x * t, sh);
+}
+
+// partial p^T (H p)
+__global__ __launch_bounds__(VT) void cg_dot_kernel(const float* __restrict__ P, const float* __restrict__ HP,
+                                                    int64_t total, int t, const CgFlags* __restrict__ flags,
+                                                    double* __restrict__ part) {
+  __shared__ float sh[VW];
+  if (flags->all_done) return;
+  const int64_t stride = (int64_t)gridDim.x * VW;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int64_t e = ((int64_t)blockIdx.x * VT + threadIdx.x) * 4; e < total; e += stride) {
+    const f32x4 p = *reinterpret_cast<const f32x4*>(P + e);
+    const f32x4 hp = *reinterpret_cast<const f32x4*>(HP + e);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] = fmaf(p[q], hp[q], acc[q]);
+  }
+  block_column_sums(acc, t, (int)(((int64_t)blockIdx.x * VW) % t), part + (int64_t)blockIdx.x * t, sh);
+}
+
+// x += alpha p ; r -= alpha Hp ; partial r^T r
+__global__ __launch_bounds__(VT) void cg_update_xr_kernel(float* __restrict__ X, float* __restrict__ R,
+                                                          const float* __restrict__ P,
+                                                          const float* __restrict__ HP, int64_t total, int t,
+                                                          const float* __restrict__ alpha,
+                                                          const CgFlags* __restrict__ flags,
+                                                          double* __restrict__ part) {
+  __shared__ float sh[VW];
+  if (flags->all_done) return;
+  const int64_t e0 = ((int64_t)blockIdx.x * VT + threadIdx.x) * 4;
+  const int64_t stride = (int64_t)gridDim.x * VW;
+  int c[4];
+  thread_columns(t, e0, c);
+  float al[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) al[q] = alpha[c[q]];
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int64_t e = e0; e < total; e += stride) {
+    const f32x4 p = *reinterpret_cast<const f32x4*>(P + e);
+    const f32x4 hp = *reinterpret_cast<const f32x4*>(HP + e);
+    f32x4 x = *reinterpret_cast<const f32x4*>(X + e);
+    f32x4 r = *reinterpret_cast<const f32x4*>(R + e);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      x[q] = fmaf(al[q], p[q], x[q]);
+      r[q] = fmaf(-al[q], hp[q], r[q]);
+      acc[q] = fmaf(r[q], r[q], acc[q]);
+    }
+    *reinterpret_cast<f32x4*>(X + e) = x;
+    *reinterpret_cast<f32x4*>(R + e) = r;
+  }
+  block_column_sums(acc, t, (int)(((int64_t)blockIdx.x * VW) % t), part + (int64_t)blockIdx.x * t, sh);
+}
+
+// p = r + beta p
+__global__ __launch_bounds__(VT) void cg_update_p_kernel(float* __restrict__ P, const float* __restrict__ R,
+                                                         int64_t total, int t, const float* __restrict__ beta,
+                                                         const CgFlags* __restrict__ flags) {
+  if (flags->all_done) return;
+  const int64_t e0 = ((int64_t)blockIdx.x * VT + threadIdx.x) * 4;
+  const int64_t stride = (int64_t)gridDim.x * VW;
+  int c[4];
+  thread_columns(t, e0, c);
+  float be[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) be[q] = beta[c[q]];
+  for (int64_t e = e0; e < total; e += stride) {
+    const f32x4 r = *reinterpret_cast<const f32x4*>(R + e);
+    f32x4 p = *reinterpret_cast<const f32x4*>(P + e);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) p[q] = fmaf(be[q], p[q], r[q]);
+    *reinterpret_cast<f32x4*>(P + e) = p;
+  }
+}
+
+// dV <- X (columns whose right-hand side is zero get 0)
+__global__ __launch_bounds__(VT) void cg_store_kernel(const float* __restrict__ X, int64_t n, int t,
+                                                      const int* __restrict__ zero_rhs, float* __restrict__ V,
+                                                      int64_t ldv) {
+  const int64_t total = n * t;
+  for (int64_t e = (int64_t)blockIdx.x * VT + threadIdx.x; e < total; e += (int64_t)gridDim.x * VT) {
+    const int64_t i = e / t;
+    const int c = (int)(e - i * t);
+    V[i * ldv + c] = zero_rhs[c] ? 0.0f : X[e];
+  }
+}
+
+// ---- one-workgroup finalise kernels --------------------------------------
+// column sums of the [G][t] workgroup partials, fixed order; result valid for tid < t
+__device__ __forceinline__ double finalize_sum(const double* part, int G, int t, double* sh /* [FT] */) {
+  const int tid = threadIdx.x;
+  const int nparts = FT / t > 0 ? FT / t : 1;
+  const int c = tid % t, pt = tid / t;
+  double s = 0.0;
+  if (pt < nparts)
+    for (int g = pt; g < G; g += nparts) s += part[(int64_t)g * t + c];
+  __syncthreads();
+  sh[tid] = s;
+  __syncthreads();
+  double tot = 0.0;
+  if (tid < t)
+    for (int k = 0; k < nparts; ++k) tot += sh[k * t + c];
+  return tot;
+}
+
+__global__ __launch_bounds__(FT) void cg_fin_init_kernel(CgDev s, int G, int t, int have_bn2) {
+  __shared__ double sh[FT];
+  __shared__ int live_count;
+  if (threadIdx.x == 0) live_count = 0;
+  double bn2 = 0.0;
+  if (have_bn2) bn2 = finalize_sum(s.part2, G, t, sh);
+  const double rho = finalize_sum(s.part, G, t, sh);
+  const int c = threadIdx.x;
+  if (c < t) {
+    if (have_bn2) s.bn2[c] = bn2; else bn2 = s.bn2[c];
+    const int zero = !(bn2 > 0.0);
+    const double rel = zero ? 0.0 : sqrt(rho / bn2);
+    const int fr = zero || rel < (double)s.tol[c];
+    s.rho[c] = rho;
+    s.relres[c] = (float)rel;
+    s.zero_rhs[c] = zero;
+    s.frozen[c] = fr;
+    s.alpha[c] = 0.0f;
+    s.beta[c] = 0.0f;
+    if (!fr) atomicAdd(&live_count, 1);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    s.flags->all_done = live_count == 0;
+    s.flags->breakdown = 0;
+    s.flags->iters = 0;
+  }
+}
+
+__global__ __launch_bounds__(FT) void cg_fin_alpha_kernel(CgDev s, int G, int t) {
+  __shared__ double sh[FT];
+  if (s.flags->all_done) return;
+  const double gamma = finalize_sum(s.part, G, t, sh);
+  const int c = threadIdx.x;
+  if (c < t) {
+    float al = 0.0f;
+    if (!s.frozen[c]) {
+      if (!(gamma > 0.0) || !isfinite(gamma)) {
+        s.flags->breakdown = 1;
+      } else {
+        al = (float)(s.rho[c] / gamma);
+      }
+    }
+    s.alpha[c] = al;
+  }
+}
+
+__global__ __launch_bounds__(FT) void cg_fin_beta_kernel(CgDev s, int G, int t) {
+  __shared__ double sh[FT];
+  __shared__ int live_count;
+  if (s.flags->all_done) return;
+  if (threadIdx.x == 0) live_count = 0;
+  const double rho_new = finalize_sum(s.part, G, t, sh);
+  const int c = threadIdx.x;
+  if (c < t) {
+    float be = 0.0f;
+    int fr = s.frozen[c];
+    if (!fr) {
+      const double rho = s.rho[c];
+      const double rel = sqrt(rho_new / s.bn2[c]);
+      if (!isfinite(rho_new)) s.flags->breakdown = 1;
+      be = (float)(rho_new / rho);
+      s.rho[c] = rho_new;
+      s.relres[c] = (float)rel;
+      fr = rel < (double)s.tol[c];
+      s.frozen[c] = fr;
+    }
+    s.beta[c] = be;
+    if (!fr) atomicAdd(&live_count, 1);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    s.flags->iters += 1;
+    if (live_count == 0 || s.flags->breakdown) s.flags->all_done = 1;
+  }
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct CgLayout {
+  int64_t n4;
+  int G;
+  size_t off_X, off_R, off_P, off_HP, off_state, off_part, off_part2, off_kmv, total;
+  size_t kmv_bytes;
+};
+
+CgLayout cg_layout(const gp_ctx* ctx, int t) {
+  CgLayout L;
+  L.n4 = (ctx->n + GP_VEC_PAD - 1) / GP_VEC_PAD * GP_VEC_PAD;
+  const int per = (2 * ctx->num_cu + t - 1) / t;
+  L.G = t * (per > 0 ? per : 1);
+  const size_t arr = align_up((size_t)L.n4 * t * sizeof(float), 256);
+  size_t o = 0;
+  L.off_X = o; o += arr;
+  L.off_R = o; o += arr;
+  L.off_P = o; o += arr;
+  L.off_HP = o; o += arr;
+  L.off_state = o; o += align_up(sizeof(CgFlags) + (size_t)t * (2 * sizeof(double) + 4 * sizeof(float) + 2 * sizeof(int)) + 256, 256);
+  L.off_part = o; o += align_up((size_t)L.G * t * sizeof(double), 256);
+  L.off_part2 = o; o += align_up((size_t)L.G * t * sizeof(double), 256);
+  L.off_kmv = o;
+  L.kmv_bytes = align_up(gp_kmv_scratch_bytes(ctx, t), 256);
+  o += L.kmv_bytes;
+  L.total = o;
+  return L;
+}
+
+}  // namespace
+
+size_t gp_cg_workspace_bytes(const gp_ctx* ctx, int t) { return cg_layout(ctx, t).total; }
+
+int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv, int t,
+              const float* h_tol, int max_iters, void* dWork, size_t work_bytes, int* h_iters,
+              int* h_kmv_count, float* h_relres) {
+  const CgLayout L = cg_layout(ctx, t);
+  if (work_bytes < L.total) return gp_fail(ctx, GP_ERR_WORKSPACE, "gp_cg_solve: workspace %zu < %zu bytes", work_bytes, L.total);
+  if ((uintptr_t)dWork % 256) return gp_fail(ctx, GP_ERR_WORKSPACE, "gp_cg_solve: workspace not 256-byte aligned");
+  hipStream_t st = ctx->stream;
+  char* w = (char*)dWork;
+  float* X = (float*)(w + L.off_X);
+  float* R = (float*)(w + L.off_R);
+  float* P = (float*)(w + L.off_P);
+  float* HP = (float*)(w + L.off_HP);
+  CgDev s;
+  {
+    char* q = w + L.off_state;
+    s.flags = (CgFlags*)q; q += sizeof(CgFlags);
+    s.rho = (double*)q; q += sizeof(double) * t;
+    s.bn2 = (double*)q; q += sizeof(double) * t;
+    s.alpha = (float*)q; q += sizeof(float) * t;
+    s.beta = (float*)q; q += sizeof(float) * t;
+    s.tol = (float*)q; q += sizeof(float) * t;
+    s.relres = (float*)q; q += sizeof(float) * t;
+    s.frozen = (int*)q; q += sizeof(int) * t;
+    s.zero_rhs = (int*)q; q += sizeof(int) * t;
+  }
+  s.part = (double*)(w + L.off_part);
+  s.part2 = (double*)(w + L.off_part2);
+  void* kmv_scratch = w + L.off_kmv;
+  const int64_t total = L.n4 * t;
+  const dim3 grid(L.G), block(VT);
+
+  // staging through pinned memory: tolerances in, flags and residuals out
+  const size_t need_pinned = sizeof(CgFlags) + sizeof(float) * t * 2;
+  if (ctx->pinned_bytes < need_pinned) return gp_fail(ctx, GP_ERR_ARG, "gp_cg_solve: t too large for the pinned staging block");
+  CgFlags* hflags = (CgFlags*)ctx->hPinned;
+  float* htol = (float*)(hflags + 1);
+  float* hrel = htol + t;
+  for (int c = 0; c < t; ++c) htol[c] = h_tol[c];
+  GP_HIP(ctx, hipMemcpyAsync(s.tol, htol, sizeof(float) * t, hipMemcpyHostToDevice, st));
+  // HP padding rows are never written by the product; keep them zero
+  GP_HIP(ctx, hipMemsetAsync(HP, 0, (size_t)total * sizeof(float), st));
+
+  int kmv_count = 0;
+  hipLaunchKernelGGL(cg_load_kernel, grid, block, 0, st, dB, ldb, dX0, ldv, ctx->n, L.n4, t, X, R, s.part2);
+  GP_HIP(ctx, hipGetLastError());
+  if (dX0) {
+    int rc = gp_kmv_launch(ctx, X, t, t, HP, t, 1, kmv_scratch, L.kmv_bytes);
+    if (rc < 0) return rc;
+    ++kmv_count;
+  }
+  hipLaunchKernelGGL(cg_resid_kernel, grid, block, 0, st, R, (const float*)HP, dX0 ? 1 : 0, P, total, t, s.part);
+  hipLaunchKernelGGL(cg_fin_init_kernel, dim3(1), dim3(FT), 0, st, s, L.G, t, 1);
+  GP_HIP(ctx, hipGetLastError());
+  GP_HIP(ctx, hipMemcpyAsync(hflags, s.flags, sizeof(CgFlags), hipMemcpyDeviceToHost, st));
+  GP_HIP(ctx, hipStreamSynchronize(st));
+
+  int it = 0;
+  while (!hflags->all_done && it < max_iters) {
+    int rc = gp_kmv_launch(ctx, P, t, t, HP, t, 1, kmv_scratch, L.kmv_bytes);
+    if (rc < 0) return rc;
+    ++kmv_count;
+    hipLaunchKernelGGL(cg_dot_kernel, grid, block, 0, st, (const float*)P, (const float*)HP, total, t, s.flags, s.part);
+    hipLaunchKernelGGL(cg_fin_alpha_kernel, dim3(1), dim3(FT), 0, st, s, L.G, t);
+    hipLaunchKernelGGL(cg_update_xr_kernel, grid, block, 0, st, X, R, (const float*)P, (const float*)HP, total, t,
+                       (const float*)s.alpha, s.flags, s.part);
+    hipLaunchKernelGGL(cg_fin_beta_kernel, dim3(1), dim3(FT), 0, st, s, L.G, t);
+    hipLaunchKernelGGL(cg_update_p_kernel, grid, block, 0, st, P, (const float*)R, total, t, (const float*)s.beta, s.flags);
+    GP_HIP(ctx, hipGetLastError());
+    GP_HIP(ctx, hipMemcpyAsync(hflags, s.flags, sizeof(CgFlags), hipMemcpyDeviceToHost, st));
+    GP_HIP(ctx, hipStreamSynchronize(st));
+    ++it;
+  }
+
+  int sblocks = (int)((ctx->n * (int64_t)t + VT - 1) / VT);
+  if (sblocks > 8 * ctx->num_cu) sblocks = 8 * ctx->num_cu;
+  hipLaunchKernelGGL(cg_store_kernel, dim3(sblocks), block, 0, st, (const float*)X, ctx->n, t, (const int*)s.zero_rhs, dV, ldv);
+  GP_HIP(ctx, hipGetLastError());
+  GP_HIP(ctx, hipMemcpyAsync(hrel, s.relres, sizeof(float) * t, hipMemcpyDeviceToHost, st));
+  GP_HIP(ctx, hipMemcpyAsync(hflags, s.flags, sizeof(CgFlags), hipMemcpyDeviceToHost, st));
+  GP_HIP(ctx, hipStreamSynchronize(st));
+  if (h_iters) *h_iters = hflags->iters;
+  if (h_kmv_count) *h_kmv_count = kmv_count;
+  if (h_relres)
+    for (int c = 0; c < t; ++c) h_relres[c] = hrel[c];
+  if (hflags->breakdown) return gp_fail(ctx, GP_ERR_BREAKDOWN, "gp_cg_solve: p^T H p <= 0 or non-finite value at iteration %d", hflags->iters);
+  // all_done is also raised by a breakdown; reaching here it means every column met its tolerance
+  return hflags->all_done ? GP_OK : GP_NOT_CONVERGED;
+}

@@ -1,0 +1,174 @@
+// C ABI entry points of libgpws: argument validation, context lifetime and
+// dispatch to the kernel launchers.  Nothing crosses this boundary but plain
+// pointers and sizes.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <cmath>
+#include <new>
+
+#include "gpws_internal.h"
+
+int gp_fail(gp_ctx* ctx, int code, const char* fmt, ...) {
+  if (ctx) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+    va_end(ap);
+  }
+  return code;
+}
+
+int gp_ensure_scratch(gp_ctx* ctx, size_t bytes) {
+  if (bytes <= ctx->scratch_bytes) return GP_OK;
+  // not stream-ordered: make sure no kernel still uses the old block
+  GP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  if (ctx->dScratch) GP_HIP(ctx, hipFree(ctx->dScratch));
+  ctx->dScratch = nullptr;
+  ctx->scratch_bytes = 0;
+  GP_HIP(ctx, hipMalloc(&ctx->dScratch, bytes));
+  ctx->scratch_bytes = bytes;
+  return GP_OK;
+}
+
+extern "C" {
+
+int gp_create(gp_ctx** out, int kernel, int64_t n, int d, const float* dX, void* hip_stream) {
+  if (!out) return GP_ERR_ARG;
+  *out = nullptr;
+  if (kernel != GP_SE_ARD && kernel != GP_MATERN32_ARD) return GP_ERR_ARG;
+  if (n < 1 || n > ((int64_t)1 << 31) - 4096 || d < 1 || d > GP_MAX_D || !dX) return GP_ERR_ARG;
+  gp_ctx* ctx = new (std::nothrow) gp_ctx();
+  if (!ctx) return GP_ERR_ARG;
+  memset(ctx, 0, sizeof(*ctx));
+  ctx->kernel = kernel;
+  ctx->n = n;
+  ctx->d = d;
+  ctx->KS = gp_ks_bucket(d);
+  ctx->n_pad = (n + GP_ROW_ALIGN - 1) / GP_ROW_ALIGN * GP_ROW_ALIGN;
+  ctx->stream = (hipStream_t)hip_stream;
+  ctx->dX = dX;
+  *out = ctx;   // handed out even on failure below so the caller can read the error, then destroy
+
+  int dev = 0;
+  hipDeviceProp_t prop;
+  GP_HIP(ctx, hipGetDevice(&dev));
+  GP_HIP(ctx, hipGetDeviceProperties(&prop, dev));
+  ctx->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+    return gp_fail(ctx, GP_ERR_HIP, "libgpws is built for gfx950 only, device is %s", prop.gcnArchName);
+
+  const size_t packed = (size_t)(ctx->n_pad / GP_CHUNK) * ctx->KS * 64 * sizeof(float);
+  GP_HIP(ctx, hipMalloc((void**)&ctx->dXA, packed));
+  GP_HIP(ctx, hipMalloc((void**)&ctx->dXB, packed));
+  GP_HIP(ctx, hipMalloc((void**)&ctx->dXs, (size_t)n * d * sizeof(float)));
+  GP_HIP(ctx, hipMalloc((void**)&ctx->dMean, sizeof(double) * d));
+  GP_HIP(ctx, hipMalloc((void**)&ctx->dTheta, sizeof(double) * (d + 2)));
+  ctx->red_bytes = (size_t)1 << 22;
+  GP_HIP(ctx, hipMalloc((void**)&ctx->dRed, ctx->red_bytes));
+  ctx->pinned_bytes = (size_t)1 << 16;
+  GP_HIP(ctx, hipHostMalloc(&ctx->hPinned, ctx->pinned_bytes, hipHostMallocDefault));
+  return gp_launch_column_means(ctx);
+}
+
+int gp_destroy(gp_ctx* ctx) {
+  if (!ctx) return GP_OK;
+  (void)hipStreamSynchronize(ctx->stream);
+  if (ctx->dXA) (void)hipFree(ctx->dXA);
+  if (ctx->dXB) (void)hipFree(ctx->dXB);
+  if (ctx->dXs) (void)hipFree(ctx->dXs);
+  if (ctx->dMean) (void)hipFree(ctx->dMean);
+  if (ctx->dTheta) (void)hipFree(ctx->dTheta);
+  if (ctx->dRed) (void)hipFree(ctx->dRed);
+  if (ctx->dScratch) (void)hipFree(ctx->dScratch);
+  if (ctx->hPinned) (void)hipHostFree(ctx->hPinned);
+  delete ctx;
+  return GP_OK;
+}
+
+int gp_set_theta(gp_ctx* ctx, const double* h_lengthscale, double signal_scale, double noise_scale) {
+  if (!ctx) return GP_ERR_ARG;
+  if (!ctx->dXA) return gp_fail(ctx, GP_ERR_ARG, "gp_set_theta: context was not created successfully");
+  if (!h_lengthscale) return gp_fail(ctx, GP_ERR_ARG, "gp_set_theta: NULL lengthscales");
+  for (int k = 0; k < ctx->d; ++k)
+    if (!(h_lengthscale[k] > 0.0) || !std::isfinite(h_lengthscale[k]))
+      return gp_fail(ctx, GP_ERR_ARG, "gp_set_theta: lengthscale %d = %g is not positive and finite", k, h_lengthscale[k]);
+  if (!(signal_scale > 0.0) || !std::isfinite(signal_scale))
+    return gp_fail(ctx, GP_ERR_ARG, "gp_set_theta: signal scale %g is not positive and finite", signal_scale);
+  if (!(noise_scale >= 0.0) || !std::isfinite(noise_scale))
+    return gp_fail(ctx, GP_ERR_ARG, "gp_set_theta: noise scale %g is negative or not finite", noise_scale);
+  // the pinned block is reused as staging; earlier work on the stream that reads it must be done
+  GP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  double* stage = (double*)ctx->hPinned;
+  for (int k = 0; k < ctx->d; ++k) {
+    ctx->ell[k] = h_lengthscale[k];
+    stage[k] = 1.0 / h_lengthscale[k];
+  }
+  stage[ctx->d] = signal_scale;
+  stage[ctx->d + 1] = noise_scale;
+  ctx->a = signal_scale;
+  ctx->sigma = noise_scale;
+  GP_HIP(ctx, hipMemcpyAsync(ctx->dTheta, stage, sizeof(double) * (ctx->d + 2), hipMemcpyHostToDevice, ctx->stream));
+  int rc = gp_launch_pack(ctx);
+  if (rc < 0) return rc;
+  ctx->theta_set = true;
+  return GP_OK;
+}
+
+static int check_block(gp_ctx* ctx, const char* who, const void* p, int64_t ld, int t) {
+  if (!p) return gp_fail(ctx, GP_ERR_ARG, "%s: NULL device pointer", who);
+  if (ld < t) return gp_fail(ctx, GP_ERR_ARG, "%s: leading dimension %lld < t = %d", who, (long long)ld, t);
+  return GP_OK;
+}
+
+int gp_kmv(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo, int add_noise) {
+  if (!ctx) return GP_ERR_ARG;
+  if (!ctx->theta_set) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: gp_set_theta has not been called");
+  if (t < 1 || t > GP_MAX_T) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: t = %d outside [1, %d]", t, GP_MAX_T);
+  int rc;
+  if ((rc = check_block(ctx, "gp_kmv(dV)", dV, ldv, t)) < 0) return rc;
+  if ((rc = check_block(ctx, "gp_kmv(dOut)", dOut, ldo, t)) < 0) return rc;
+  if ((const float*)dOut == dV) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: dOut must not alias dV");
+  const size_t need = gp_kmv_scratch_bytes(ctx, t);
+  if ((rc = gp_ensure_scratch(ctx, need)) < 0) return rc;
+  return gp_kmv_launch(ctx, dV, ldv, t, dOut, ldo, add_noise ? 1 : 0, ctx->dScratch, ctx->scratch_bytes);
+}
+
+size_t gp_workspace_bytes(const gp_ctx* ctx, int t) {
+  if (!ctx || t < 1 || t > GP_MAX_T) return 0;
+  return gp_cg_workspace_bytes(ctx, t);
+}
+
+int gp_cg_solve(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv, int t,
+                const float* h_tol, int max_iters, void* dWork, size_t work_bytes, int* h_iters,
+                int* h_kmv_count, float* h_relres) {
+  if (!ctx) return GP_ERR_ARG;
+  if (!ctx->theta_set) return gp_fail(ctx, GP_ERR_ARG, "gp_cg_solve: gp_set_theta has not been called");
+  if (t < 1 || t > GP_MAX_T) return gp_fail(ctx, GP_ERR_ARG, "gp_cg_solve: t = %d outside [1, %d]", t, GP_MAX_T);
+  int rc;
+  if ((rc = check_block(ctx, "gp_cg_solve(dB)", dB, ldb, t)) < 0) return rc;
+  if ((rc = check_block(ctx, "gp_cg_solve(dV)", dV, ldv, t)) < 0) return rc;
+  if (!h_tol) return gp_fail(ctx, GP_ERR_ARG, "gp_cg_solve: NULL tolerances");
+  for (int c = 0; c < t; ++c)
+    if (!(h_tol[c] > 0.0f) || !std::isfinite(h_tol[c]))
+      return gp_fail(ctx, GP_ERR_ARG, "gp_cg_solve: tolerance %d = %g is not positive and finite", c, (double)h_tol[c]);
+  if (max_iters < 0) return gp_fail(ctx, GP_ERR_ARG, "gp_cg_solve: max_iters < 0");
+  if (!dWork) return gp_fail(ctx, GP_ERR_WORKSPACE, "gp_cg_solve: NULL workspace");
+  return gp_cg_run(ctx, dB, ldb, dX0, dV, ldv, t, h_tol, max_iters, dWork, work_bytes, h_iters, h_kmv_count,
+                   h_relres);
+}
+
+int gp_mll_grad(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int64_t ldb, int t, double* h_grad) {
+  if (!ctx) return GP_ERR_ARG;
+  if (!ctx->theta_set) return gp_fail(ctx, GP_ERR_ARG, "gp_mll_grad: gp_set_theta has not been called");
+  if (t < 1 || t > GP_MAX_T) return gp_fail(ctx, GP_ERR_ARG, "gp_mll_grad: t = %d outside [1, %d]", t, GP_MAX_T);
+  int rc;
+  if ((rc = check_block(ctx, "gp_mll_grad(dV)", dV, ldv, t)) < 0) return rc;
+  if ((rc = check_block(ctx, "gp_mll_grad(dB)", dB, ldb, t)) < 0) return rc;
+  if (!h_grad) return gp_fail(ctx, GP_ERR_ARG, "gp_mll_grad: NULL output");
+  return gp_grad_run(ctx, dV, ldv, dB, ldb, t, h_grad);
+}
+
+const char* gp_last_error(const gp_ctx* ctx) { return ctx ? ctx->err : "NULL context"; }
+
+}  // extern "C"

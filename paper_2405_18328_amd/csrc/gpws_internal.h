@@ -1,0 +1,95 @@
+// Internal declarations shared by the translation units of libgpws (gfx950 only).
+#ifndef GPWS_INTERNAL_H
+#define GPWS_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/gpws.h"
+
+// ---------------------------------------------------------------------------
+// Geometry of the tile pass.  A wavefront (64 lanes) owns MI sub-tiles of 32
+// rows i and walks over the columns j in chunks of 32; one 32x32 tile of
+// pairs is one v_mfma_f32_32x32x2_f32 accumulator (16 VGPRs per lane).
+// ---------------------------------------------------------------------------
+constexpr int GP_CHUNK = 32;          // rows per packed operand chunk
+constexpr int GP_WAVES = 4;           // wavefronts per workgroup
+constexpr int GP_THREADS = 64 * GP_WAVES;
+constexpr int GP_ROW_ALIGN = 256;     // packed operand arrays are padded to this many rows
+constexpr int GP_VEC_PAD = 4;         // solver arrays are padded to a multiple of 4 rows (float4 streams)
+
+// Operands of the distance contraction, packed so that one wave-wide dword
+// load is one MFMA operand: P[(chunk*KS + ks)*64 + lane] holds, for row
+// 32*chunk + lane%32, the component k = 2*ks + lane/32 of
+//   XA (column side j): [ xs_j(0..d-1), |xs_j|^2, 1, 0.. ]
+//   XB (row side i)   : g * [ -2 xs_i(0..d-1), 1, |xs_i|^2, 0.. ]
+// with xs = (x - mean)/ell and g = -log2(e)/2 (SE) or 3 (Matern-3/2), so that
+// XA_j . XB_i = g * r^2_ij comes straight out of the MFMA chain.
+struct gp_ctx {
+  int kernel;
+  int64_t n;
+  int d;
+  int KS;                 // k-steps (of 2) of the distance chain, bucketed
+  int64_t n_pad;          // n rounded up to GP_ROW_ALIGN
+  hipStream_t stream;
+  const float* dX;        // caller-owned
+  float* dXA;             // packed, n_pad/32 * KS * 64
+  float* dXB;
+  float* dXs;             // scaled centred inputs, row-major n x d (gradient pass)
+  double* dMean;          // d column means of X
+  double* dTheta;         // device copy: 1/ell (d), then a, sigma
+  bool theta_set;
+  double ell[GP_MAX_D];
+  double a, sigma;
+  // lazily grown scratch for split-column partial sums of gp_kmv / gp_mll_grad
+  void* dScratch;
+  size_t scratch_bytes;
+  // small device + pinned host blocks for scalars
+  double* dRed;           // reduction partials
+  size_t red_bytes;
+  void* hPinned;          // pinned host staging for scalar read-back
+  size_t pinned_bytes;
+  int num_cu;
+  char err[256];
+};
+
+int gp_fail(gp_ctx* ctx, int code, const char* fmt, ...);
+#define GP_HIP(ctx, call)                                                              \
+  do {                                                                                 \
+    hipError_t e__ = (call);                                                           \
+    if (e__ != hipSuccess)                                                             \
+      return gp_fail(ctx, GP_ERR_HIP, "%s failed: %s", #call, hipGetErrorString(e__)); \
+  } while (0)
+
+int gp_ks_bucket(int d);   // -1 if d is out of range
+int gp_ensure_scratch(gp_ctx* ctx, size_t bytes);
+
+// ---- prep_kernels.hip
+int gp_launch_column_means(gp_ctx* ctx);
+int gp_launch_pack(gp_ctx* ctx);
+
+// ---- tile_pass.hip
+struct KmvPlan {
+  int MI;        // 32-row sub-tiles per wave
+  int JS;        // column-range splits
+  int row_blocks;
+  int cps;       // chunks per split
+};
+KmvPlan gp_plan_kmv(const gp_ctx* ctx);
+size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t);
+// OUT = K V (+ sigma^2 V).  scratch is used only when the plan splits the column range.
+int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
+                  int add_noise, void* scratch, size_t scratch_bytes);
+
+// ---- cg_kernels.hip
+int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv,
+              int t, const float* h_tol, int max_iters, void* dWork, size_t work_bytes,
+              int* h_iters, int* h_kmv_count, float* h_relres);
+size_t gp_cg_workspace_bytes(const gp_ctx* ctx, int t);
+
+// ---- grad_pass.hip
+int gp_grad_run(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int64_t ldb, int t,
+                double* h_grad);
+
+#endif

@@ -1,0 +1,342 @@
+// Matrix-free product OUT = K V (+ sigma^2 V) for ARD squared-exponential and
+// Matern-3/2 kernels on gfx950: the product inside every solver iteration of
+// the batched system of paper Section 2.1.  K is never stored.
+//
+// Per 32x32 tile of pairs (j, i), one wavefront does
+//   1. S[j][i] = XA_j . XB_i          KS x v_mfma_f32_32x32x2_f32   (= g r^2_ij)
+//   2. phi = exp2(S)                  (SE)   or (1+u) exp2(-log2e u), u = sqrt(max(S,0))  (Matern-3/2)
+//   3. OUT_i += phi[i][j] V_j         16*NT x v_mfma_f32_32x32x2_f32
+// The accumulator layout of step 1 (lane = i, register r <-> j) is exactly the
+// A-operand layout step 3 needs once the V rows are fetched in the matching
+// order, so phi never leaves registers.  One extra column (y, when t = 32q+1)
+// is carried on the VALU so that t = 65 does not pay for a third MFMA N-tile.
+#include "gpws_internal.h"
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+struct TileArgs {
+  const float* XA;
+  const float* XB;
+  const float* V;
+  int64_t ldv;
+  float* OUT;
+  int64_t ldo;
+  int64_t split_stride;   // elements between consecutive split partials
+  int64_t n;
+  int nchunks;            // ceil(n / 32)
+  int col0;               // first column of V on the MFMA
+  int ncols;              // MFMA columns in this pass (<= 32*NT)
+  int vcol;               // column carried on the VALU, or -1
+  int JS;
+  int cps;                // chunks per split
+  float a2;
+  float sigma2;
+  int add_noise;
+};
+
+constexpr float LOG2E = 1.4426950408889634f;
+
+template <int KIND>
+__device__ __forceinline__ float phi_of(float s) {
+  if (KIND == GP_SE_ARD) {
+    return __builtin_amdgcn_exp2f(s);             // s = -log2(e)/2 r^2
+  } else {
+    float u = __builtin_amdgcn_sqrtf(fmaxf(s, 0.0f));   // s = 3 r^2
+    float e = __builtin_amdgcn_exp2f(-LOG2E * u);
+    return fmaf(u, e, e);
+  }
+}
+
+template <int KIND, int KS, int NT, int MI>
+__global__ __launch_bounds__(GP_THREADS) void kmv_tile_kernel(TileArgs p) {
+  constexpr int NC = 32 * NT;
+  constexpr int XA_F = KS * 64;
+  constexpr int V_OFF = XA_F;
+  constexpr int VY_OFF = V_OFF + 32 * NC;
+  constexpr int STAGE = VY_OFF + 32;
+  constexpr int XA_LD = (XA_F + GP_THREADS - 1) / GP_THREADS;
+  __shared__ __attribute__((aligned(16))) float lds[2][STAGE];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int h = lane >> 5;
+  const int li = lane & 31;
+  const int js = blockIdx.x % p.JS;
+  const int rb = blockIdx.x / p.JS;
+  const int sub0 = (rb * GP_WAVES + wave) * MI;     // first 32-row sub-tile of this wave
+
+  const int c_begin = js * p.cps;
+  const int c_end = min(p.nchunks, c_begin + p.cps);
+
+  // row-side operands stay in registers for the whole pass
+  float xb[MI][KS];
+#pragma unroll
+  for (int m = 0; m < MI; ++m)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) xb[m][ks] = p.XB[((int64_t)(sub0 + m) * KS + ks) * 64 + lane];
+
+  f32x16 acc[MI][NT];
+  float accv[MI];
+#pragma unroll
+  for (int m = 0; m < MI; ++m) {
+    accv[m] = 0.0f;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[m][nt][r] = 0.0f;
+  }
+
+  // staging registers for the next chunk
+  float gxa[XA_LD];
+  f32x4 gv[NT];
+  float gvy = 0.0f;
+  const int ld_jq = tid >> 5;        // 0..7 : group of 4 consecutive rows j
+  const int ld_c = tid & 31;
+
+  auto load_chunk = [&](int ch) {
+    const float* xa = p.XA + (int64_t)ch * XA_F;
+#pragma unroll
+    for (int u = 0; u < XA_LD; ++u) {
+      int idx = tid + u * GP_THREADS;
+      gxa[u] = (idx < XA_F) ? xa[idx] : 0.0f;
+    }
+    const int64_t j0 = (int64_t)ch * 32 + 4 * ld_jq;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int cc = ld_c + 32 * nt;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int64_t j = j0 + q;
+        gv[nt][q] = (j < p.n && cc < p.ncols) ? p.V[j * p.ldv + p.col0 + cc] : 0.0f;
+      }
+    }
+    if (tid < 32) {
+      const int64_t j = (int64_t)ch * 32 + tid;
+      gvy = (p.vcol >= 0 && j < p.n) ? p.V[j * p.ldv + p.vcol] : 0.0f;
+    }
+  };
+  auto store_chunk = [&](int st) {
+    float* s = lds[st];
+#pragma unroll
+    for (int u = 0; u < XA_LD; ++u) {
+      int idx = tid + u * GP_THREADS;
+      if (idx < XA_F) s[idx] = gxa[u];
+    }
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+      *reinterpret_cast<f32x4*>(&s[V_OFF + (ld_jq * NC + ld_c + 32 * nt) * 4]) = gv[nt];
+    if (tid < 32) s[VY_OFF + tid] = gvy;
+  };
+
+  if (c_begin < c_end) {
+    load_chunk(c_begin);
+    store_chunk(0);
+  }
+  __syncthreads();
+
+  for (int ch = c_begin; ch < c_end; ++ch) {
+    const int st = (ch - c_begin) & 1;
+    if (ch + 1 < c_end) load_chunk(ch + 1);
+
+    const float* s = lds[st];
+    f32x16 S[MI];
+#pragma unroll
+    for (int m = 0; m < MI; ++m)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) S[m][r] = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const float xa = s[ks * 64 + lane];
+#pragma unroll
+      for (int m = 0; m < MI; ++m) S[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa, xb[m][ks], S[m], 0, 0, 0);
+    }
+    // the pair (i, i): r^2 is exactly zero
+#pragma unroll
+    for (int m = 0; m < MI; ++m) {
+      if (ch == sub0 + m) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (8 * (r >> 2) + 4 * h + (r & 3) == li) S[m][r] = 0.0f;
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int jq = 2 * g + h;
+      const f32x4 vy4 = *reinterpret_cast<const f32x4*>(&s[VY_OFF + 4 * jq]);
+      f32x4 vb[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        vb[nt] = *reinterpret_cast<const f32x4*>(&s[V_OFF + (jq * NC + li + 32 * nt) * 4]);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+#pragma unroll
+        for (int m = 0; m < MI; ++m) {
+          const float ph = phi_of<KIND>(S[m][4 * g + q]);
+          accv[m] = fmaf(ph, vy4[q], accv[m]);
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            acc[m][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(ph, vb[nt][q], acc[m][nt], 0, 0, 0);
+        }
+      }
+    }
+    if (ch + 1 < c_end) store_chunk(st ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue: scale by a^2, add the noise term once (split 0), store
+  float* out = p.OUT + (int64_t)js * p.split_stride;
+  const bool noise = p.add_noise && js == 0;
+#pragma unroll
+  for (int m = 0; m < MI; ++m) {
+    const int64_t ibase = (int64_t)(sub0 + m) * 32;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int c = li + 32 * nt;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t i = ibase + 8 * (r >> 2) + 4 * h + (r & 3);
+        if (i < p.n && c < p.ncols) {
+          float v = p.a2 * acc[m][nt][r];
+          if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.col0 + c], v);
+          out[i * p.ldo + p.col0 + c] = v;
+        }
+      }
+    }
+    if (p.vcol >= 0) {
+      float tot = accv[m] + __shfl_xor(accv[m], 32);
+      const int64_t i = ibase + li;
+      if (h == 0 && i < p.n) {
+        float v = p.a2 * tot;
+        if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.vcol], v);
+        out[i * p.ldo + p.vcol] = v;
+      }
+    }
+  }
+}
+
+// OUT[i][c] = sum_js PART[js][i][c] for c in [c_lo, c_hi)
+__global__ void kmv_reduce_kernel(const float* __restrict__ part, int64_t split_stride, int JS, int64_t n,
+                                  int t, float* __restrict__ out, int64_t ldo) {
+  const int64_t total = n * t;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t i = e / t;
+    const int c = (int)(e - i * t);
+    float s = 0.0f;
+    for (int k = 0; k < JS; ++k) s += part[(int64_t)k * split_stride + e];
+    out[i * ldo + c] = s;
+  }
+}
+
+typedef void (*tile_fn)(TileArgs);
+
+template <int KIND, int KS>
+tile_fn pick_nt_mi(int NT, int MI) {
+  if (NT == 1) return MI == 1 ? kmv_tile_kernel<KIND, KS, 1, 1> : kmv_tile_kernel<KIND, KS, 1, 2>;
+  return MI == 1 ? kmv_tile_kernel<KIND, KS, 2, 1> : kmv_tile_kernel<KIND, KS, 2, 2>;
+}
+
+template <int KIND>
+tile_fn pick_ks(int KS, int NT, int MI) {
+  switch (KS) {
+    case 4: return pick_nt_mi<KIND, 4>(NT, MI);
+    case 7: return pick_nt_mi<KIND, 7>(NT, MI);
+    case 10: return pick_nt_mi<KIND, 10>(NT, MI);
+    case 14: return pick_nt_mi<KIND, 14>(NT, MI);
+    case 24: return pick_nt_mi<KIND, 24>(NT, MI);
+    case 46: return pick_nt_mi<KIND, 46>(NT, MI);
+    case 64: return pick_nt_mi<KIND, 64>(NT, MI);
+  }
+  return nullptr;
+}
+
+}  // namespace
+
+int gp_ks_bucket(int d) {
+  const int need = (d + 2 + 1) / 2;
+  const int buckets[] = {4, 7, 10, 14, 24, 46, 64};
+  for (int b : buckets)
+    if (need <= b) return b;
+  return -1;
+}
+
+KmvPlan gp_plan_kmv(const gp_ctx* ctx) {
+  KmvPlan pl;
+  const int64_t chunks = (ctx->n + 31) / 32;
+  // two sub-tiles per wave once there are enough rows to fill the chip that way
+  pl.MI = (ctx->KS <= 24 && ctx->n >= 8192) ? 2 : 1;
+  const int rows_per_wg = 32 * GP_WAVES * pl.MI;
+  pl.row_blocks = (int)((ctx->n + rows_per_wg - 1) / rows_per_wg);
+  const int target = 2 * ctx->num_cu;
+  int JS = 1;
+  if (pl.row_blocks < target) {
+    JS = (target + pl.row_blocks - 1) / pl.row_blocks;
+    const int64_t max_js = chunks / 4 > 0 ? chunks / 4 : 1;   // keep at least 4 chunks per split
+    if (JS > max_js) JS = (int)max_js;
+    if (JS > 64) JS = 64;
+  }
+  pl.cps = (int)((chunks + JS - 1) / JS);
+  pl.JS = (int)((chunks + pl.cps - 1) / pl.cps);
+  return pl;
+}
+
+size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t) {
+  KmvPlan pl = gp_plan_kmv(ctx);
+  if (pl.JS <= 1) return 0;
+  return (size_t)pl.JS * (size_t)ctx->n * (size_t)t * sizeof(float);
+}
+
+int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
+                  int add_noise, void* scratch, size_t scratch_bytes) {
+  const KmvPlan pl = gp_plan_kmv(ctx);
+  const bool split = pl.JS > 1;
+  if (split && scratch_bytes < gp_kmv_scratch_bytes(ctx, t))
+    return gp_fail(ctx, GP_ERR_WORKSPACE, "gp_kmv: scratch too small for %d column splits", pl.JS);
+
+  TileArgs a;
+  a.XA = ctx->dXA;
+  a.XB = ctx->dXB;
+  a.V = dV;
+  a.ldv = ldv;
+  a.OUT = split ? (float*)scratch : dOut;
+  a.ldo = split ? t : ldo;
+  a.split_stride = split ? ctx->n * (int64_t)t : 0;
+  a.n = ctx->n;
+  a.nchunks = (int)((ctx->n + 31) / 32);
+  a.JS = pl.JS;
+  a.cps = pl.cps;
+  a.a2 = (float)(ctx->a * ctx->a);
+  a.sigma2 = (float)(ctx->sigma * ctx->sigma);
+  a.add_noise = add_noise;
+
+  // column passes: optional VALU column (when t = 32q + 1, q >= 1), then MFMA groups of <= 64
+  int vcol = (t > 1 && t % 32 == 1) ? 0 : -1;
+  int c = vcol >= 0 ? 1 : 0;
+  const dim3 grid(pl.row_blocks * pl.JS), block(GP_THREADS);
+  while (c < t) {
+    const int rem = t - c;
+    const int NT = rem > 32 ? 2 : 1;
+    a.col0 = c;
+    a.ncols = rem < 32 * NT ? rem : 32 * NT;
+    a.vcol = vcol;
+    vcol = -1;   // carried by the first pass only
+    tile_fn fn = ctx->kernel == GP_SE_ARD ? pick_ks<GP_SE_ARD>(ctx->KS, NT, pl.MI)
+                                          : pick_ks<GP_MATERN32_ARD>(ctx->KS, NT, pl.MI);
+    if (!fn) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: no kernel for KS=%d", ctx->KS);
+    hipLaunchKernelGGL(fn, grid, block, 0, ctx->stream, a);
+    GP_HIP(ctx, hipGetLastError());
+    c += a.ncols;
+  }
+  if (split) {
+    const int64_t total = ctx->n * (int64_t)t;
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 4 * ctx->num_cu) blocks = 4 * ctx->num_cu;
+    hipLaunchKernelGGL(kmv_reduce_kernel, dim3(blocks), dim3(256), 0, ctx->stream, (const float*)scratch,
+                       a.split_stride, pl.JS, ctx->n, t, dOut, ldo);
+    GP_HIP(ctx, hipGetLastError());
+  }
+  return GP_OK;
+}
