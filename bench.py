@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the warm-started iterative-GP hot path on one MI355X.
+
+A step = one marginal-likelihood step over the whole workload: set theta, batched CG solve of
+(K + sigma^2 I) V = [y, Z] to the workload's tolerance (warm-started from the previous step's V),
+stochastic gradient, Adam update.  Everything n-sized is resident in HBM before the timed region.
+
+Prints ONE JSON line.  value = algorithmic flops of all K V products launched in the timed steps
+(n^2 (2d + 2t + c_phi) each, c = 4 for SE, 8 for Matern-3/2) divided by the wall time of those
+steps (which also contains the vector updates, the gradient pass and the host loop), in TFLOP/s.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP32_PEAK_TFLOPS = 157.3   # MI355X dense FP32 matrix peak
+
+
+def kmv_flops(n, d, t, kind):
+    return float(n) * float(n) * (2 * d + 2 * t + (4 if kind == "se" else 8))
+
+
+def cpu_baseline(w):
+    """The oracle's fp64 K V timed on the host cores on a row sample of the same workload."""
+    import numpy as np
+    from oracle import gp_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    rng = np.random.default_rng(0)
+    probe = rng.choice(w.n, size=min(64, w.n), replace=False)
+    t0 = time.perf_counter()
+    orc.kmv_rows(w.X, w.ell, w.a, w.kind, w.B, probe, sigma=w.sigma)
+    per_row = (time.perf_counter() - t0) / probe.size
+    # size the sample for about 15 s of oracle work
+    nrows = int(max(64, min(w.n, 15.0 / max(per_row, 1e-9))))
+    rows = rng.choice(w.n, size=nrows, replace=False)
+    t0 = time.perf_counter()
+    orc.kmv_rows(w.X, w.ell, w.a, w.kind, w.B, rows, sigma=w.sigma)
+    dt = time.perf_counter() - t0
+    fl = kmv_flops(1, w.d, w.s + 1, w.kind) * rows.size * w.n
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"fp64 oracle K V for {rows.size} of {w.n} rows against all {w.n} columns, "
+                      f"{dt:.1f} s; host has {os.cpu_count()} logical CPUs",
+            "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config4", "config5"])
+    ap.add_argument("--n", type=int, default=None, help="override n (scaled-down runs)")
+    ap.add_argument("--max-iters", type=int, default=None)
+    ap.add_argument("--no-cold", action="store_true", help="skip the cold-start comparison arm")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--kmv-only", action="store_true", help="time bare K V products instead of MLL steps")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2405_18328_amd import binding as gp
+    from paper_2405_18328_amd.inputs import make
+    from paper_2405_18328_amd.mll import MllOptimizer
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    big = args.workload in ("config3", "config4", "config5")
+    steps = args.steps if args.steps is not None else (2 if big else 20)
+    warmup = args.warmup if args.warmup is not None else (1 if big else 5)
+    max_iters = args.max_iters if args.max_iters is not None else (6 if args.workload == "config5" else (30 if big else 1000))
+
+    kw = {"n": args.n} if args.n else {}
+    t_gen = time.perf_counter()
+    w = make(args.workload, **kw)
+    t_gen = time.perf_counter() - t_gen
+    n, d, t = w.n, w.d, w.s + 1
+    F = kmv_flops(n, d, t, w.kind)
+    desc = (f"{w.name}: n={n}, d={d}, {'SE' if w.kind == 'se' else 'Matern-3/2'}-ARD, s={w.s} {w.probe_law} probes, "
+            f"CG rel tol {w.tol:g}, Adam lr 0.1, warm start")
+
+    opt = MllOptimizer(w.X, w.y, w.Z, w.kind, w.ell, w.a, w.sigma, w.tol, warm=True, max_iters=max_iters)
+    result = {}
+    try:
+        if args.kmv_only:
+            out = torch.empty_like(opt.B)
+            theta = opt.theta
+            gp.gp_set_theta(opt.ctx, theta[:d], theta[d], theta[d + 1])
+            for _ in range(warmup):
+                gp.gp_kmv(opt.ctx, opt.B, t, t, out, t, 1)
+            torch.cuda.synchronize()
+            gp.gp_profile(opt.ctx, 1)
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                gp.gp_kmv(opt.ctx, opt.B, t, t, out, t, 1)
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t0
+            launches, kern_ms = gp.gp_profile_read(opt.ctx)
+            gp.gp_profile(opt.ctx, 0)
+            n_kmv = steps
+            extra = {"mode": "kmv_only"}
+        else:
+            for _ in range(warmup):
+                opt.step()
+            torch.cuda.synchronize()
+            gp.gp_profile(opt.ctx, 1)
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                opt.step()
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t0
+            launches, kern_ms = gp.gp_profile_read(opt.ctx)
+            gp.gp_profile(opt.ctx, 0)
+            timed = opt.history[warmup:]
+            n_kmv = sum(r.kmv_count for r in timed)
+            warm_stats = {"cg_ms_per_step": float(np.mean([r.solve_ms for r in timed])),
+                          "grad_ms_per_step": float(np.mean([r.grad_ms for r in timed])),
+                          "iters_per_step": float(np.mean([r.iters for r in timed])),
+                          "iters": [r.iters for r in opt.history],
+                          "not_converged_steps": int(sum(r.rc != 0 for r in timed))}
+            extra = {"warm": warm_stats}
+            if not args.no_cold:
+                # cold arm on the same theta sequence: zero initialisation and freshly drawn probes
+                gen = torch.Generator(device=opt.dev)
+                gen.manual_seed(4242)
+                Zc = torch.empty_like(opt.B[:, 1:])
+                Vc = torch.zeros_like(opt.B)
+                Bc = opt.B.clone()
+                cold_ms, cold_it, cold_nc = [], [], 0
+                for r in timed:
+                    th = r.theta
+                    gp.gp_set_theta(opt.ctx, th[:d], th[d], th[d + 1])
+                    Zc.normal_(generator=gen)
+                    Bc[:, 1:] = Zc
+                    torch.cuda.synchronize()
+                    c0 = time.perf_counter()
+                    rc, it, _, _ = gp.gp_cg_solve(opt.ctx, Bc, t, None, Vc, t, t, w.tol, max_iters, opt.work,
+                                                  opt.work.numel())
+                    cold_ms.append((time.perf_counter() - c0) * 1e3)
+                    cold_it.append(it)
+                    cold_nc += rc != 0
+                extra["cold"] = {"cg_ms_per_step": float(np.mean(cold_ms)), "iters_per_step": float(np.mean(cold_it)),
+                                 "iters": cold_it, "not_converged_steps": int(cold_nc),
+                                 "note": "zero initialisation + resampled Gaussian probes, same theta sequence"}
+                extra["warm_vs_cold_cg_speedup"] = extra["cold"]["cg_ms_per_step"] / warm_stats["cg_ms_per_step"]
+        value = n_kmv * F / wall / 1e12
+        avg_kern_s = kern_ms / 1e3 / max(launches, 1)
+        achieved = F / avg_kern_s / 1e12 if launches else 0.0
+        result = {
+            "metric": "matrix-free K.V TFLOP/s (% FP32 peak) + CG time per MLL step, warm vs cold",
+            "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+            "ms_per_step": wall / steps * 1e3, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": desc, "n": n, "d": d, "t": t, "kernel": w.kind, "max_iters": max_iters,
+                       "kmv_products_timed": int(n_kmv), "input_generation_s": round(t_gen, 1)},
+            "pct_fp32_peak": 100.0 * value / FP32_PEAK_TFLOPS,
+            "roofline": {"bound": "mfma", "achieved": achieved, "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": achieved / FP32_PEAK_TFLOPS, "traffic": None, "kernel": "kmv_tile_kernel",
+                         "launches": int(launches), "avg_launch_ms": avg_kern_s * 1e3,
+                         "flops_per_launch": F},
+        }
+        result.update(extra)
+    finally:
+        opt.close()
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -132,6 +132,19 @@ int gp_cg_solve(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, flo
 int gp_mll_grad(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int64_t ldb, int t,
                 double* h_grad);
 
+/*
+ * Instrumentation for roofline reports (not part of the method): while enabled,
+ * every launch of the K V tile-pass kernel made through this context (by gp_kmv
+ * or inside gp_cg_solve) is bracketed by a pair of HIP events on the context's
+ * stream.  gp_profile(ctx, 1) resets the counters and starts recording,
+ * gp_profile(ctx, 0) stops.  gp_profile_read synchronises the stream and returns
+ * the number of bracketed launches and the sum of their durations in
+ * milliseconds (at most 8192 launches are recorded per enable; later ones are
+ * not counted).  Either output pointer may be NULL.
+ */
+int gp_profile(gp_ctx* ctx, int enable);
+int gp_profile_read(gp_ctx* ctx, int* h_launches, double* h_total_ms);
+
 /* Text of the last error on this context ("" if none).  Never NULL. */
 const char* gp_last_error(const gp_ctx* ctx);
 

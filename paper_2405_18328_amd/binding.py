@@ -28,7 +28,7 @@ GP_MAX_T = 1024
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgpws.so")
 
 EXPORTS = ["gp_create", "gp_destroy", "gp_set_theta", "gp_kmv", "gp_workspace_bytes", "gp_cg_solve",
-           "gp_mll_grad", "gp_last_error"]
+           "gp_mll_grad", "gp_profile", "gp_profile_read", "gp_last_error"]
 
 
 def _load():
@@ -45,6 +45,8 @@ def _load():
     lib.gp_cg_solve.argtypes = [p, p, i64, p, p, i64, i32, C.POINTER(C.c_float), i32, p, sz,
                                 C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_float)]
     lib.gp_mll_grad.argtypes = [p, p, i64, p, i64, i32, C.POINTER(dbl)]
+    lib.gp_profile.argtypes = [p, i32]
+    lib.gp_profile_read.argtypes = [p, C.POINTER(i32), C.POINTER(dbl)]
     lib.gp_last_error.argtypes = [p]
     lib.gp_last_error.restype = C.c_char_p
     for name in EXPORTS:
@@ -130,3 +132,14 @@ def gp_mll_grad(ctx, dV, ldv, dB, ldb, t, d):
     _check(ctx, _lib.gp_mll_grad(ctx, _ptr(dV), int(ldv), _ptr(dB), int(ldb), int(t),
                                  g.ctypes.data_as(C.POINTER(C.c_double))))
     return g
+
+
+def gp_profile(ctx, enable):
+    return _check(ctx, _lib.gp_profile(ctx, int(enable)))
+
+
+def gp_profile_read(ctx):
+    """Returns (launches, total_ms) of the bracketed tile-pass launches."""
+    n, ms = C.c_int(0), C.c_double(0.0)
+    _check(ctx, _lib.gp_profile_read(ctx, C.byref(n), C.byref(ms)))
+    return n.value, ms.value

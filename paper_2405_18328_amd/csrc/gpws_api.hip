@@ -82,6 +82,10 @@ int gp_destroy(gp_ctx* ctx) {
   if (ctx->dRed) (void)hipFree(ctx->dRed);
   if (ctx->dScratch) (void)hipFree(ctx->dScratch);
   if (ctx->hPinned) (void)hipHostFree(ctx->hPinned);
+  if (ctx->prof_ev) {
+    for (int i = 0; i < 2 * GP_PROF_MAX; ++i) (void)hipEventDestroy(ctx->prof_ev[i]);
+    delete[] ctx->prof_ev;
+  }
   delete ctx;
   return GP_OK;
 }
@@ -167,6 +171,32 @@ int gp_mll_grad(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int6
   if ((rc = check_block(ctx, "gp_mll_grad(dB)", dB, ldb, t)) < 0) return rc;
   if (!h_grad) return gp_fail(ctx, GP_ERR_ARG, "gp_mll_grad: NULL output");
   return gp_grad_run(ctx, dV, ldv, dB, ldb, t, h_grad);
+}
+
+int gp_profile(gp_ctx* ctx, int enable) {
+  if (!ctx) return GP_ERR_ARG;
+  if (enable && !ctx->prof_ev) {
+    ctx->prof_ev = new (std::nothrow) hipEvent_t[2 * GP_PROF_MAX];
+    if (!ctx->prof_ev) return gp_fail(ctx, GP_ERR_ARG, "gp_profile: out of host memory");
+    for (int i = 0; i < 2 * GP_PROF_MAX; ++i) GP_HIP(ctx, hipEventCreate(&ctx->prof_ev[i]));
+  }
+  if (enable) ctx->prof_count = 0;
+  ctx->prof_on = enable != 0;
+  return GP_OK;
+}
+
+int gp_profile_read(gp_ctx* ctx, int* h_launches, double* h_total_ms) {
+  if (!ctx) return GP_ERR_ARG;
+  GP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  double tot = 0.0;
+  for (int i = 0; i < ctx->prof_count; ++i) {
+    float ms = 0.0f;
+    GP_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]));
+    tot += (double)ms;
+  }
+  if (h_launches) *h_launches = ctx->prof_count;
+  if (h_total_ms) *h_total_ms = tot;
+  return GP_OK;
 }
 
 const char* gp_last_error(const gp_ctx* ctx) { return ctx ? ctx->err : "NULL context"; }

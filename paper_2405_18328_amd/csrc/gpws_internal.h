@@ -18,6 +18,7 @@ constexpr int GP_WAVES = 4;           // wavefronts per workgroup
 constexpr int GP_THREADS = 64 * GP_WAVES;
 constexpr int GP_ROW_ALIGN = 256;     // packed operand arrays are padded to this many rows
 constexpr int GP_VEC_PAD = 4;         // solver arrays are padded to a multiple of 4 rows (float4 streams)
+constexpr int GP_PROF_MAX = 8192;     // event pairs available to gp_profile
 
 // Operands of the distance contraction, packed so that one wave-wide dword
 // load is one MFMA operand: P[(chunk*KS + ks)*64 + lane] holds, for row
@@ -51,6 +52,10 @@ struct gp_ctx {
   void* hPinned;          // pinned host staging for scalar read-back
   size_t pinned_bytes;
   int num_cu;
+  // event pairs bracketing tile-pass launches while profiling is on
+  bool prof_on;
+  int prof_count;
+  hipEvent_t* prof_ev;    // 2 * GP_PROF_MAX events, created on first enable
   char err[256];
 };
 
