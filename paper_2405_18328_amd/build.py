@@ -12,8 +12,10 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgpws.so")
 SOURCES = ["gpws_api.hip", "prep_kernels.hip", "tile_pass.hip", "cg_kernels.hip", "grad_pass.hip"]
 # packed FP32 VALU forms are kept off on purpose (some forms have miscomputed on the test machines)
+# MFMA accumulators are kept in ordinary VGPRs (vgpr-form): the tile kernels feed the result of one
+# MFMA chain through the VALU into the next chain, and the AGPR form costs a copy each way per value.
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form=1"]
 
 
 def _compile(src):

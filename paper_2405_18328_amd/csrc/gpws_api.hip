@@ -58,7 +58,7 @@ int gp_create(gp_ctx** out, int kernel, int64_t n, int d, const float* dX, void*
   if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
     return gp_fail(ctx, GP_ERR_HIP, "libgpws is built for gfx950 only, device is %s", prop.gcnArchName);
 
-  const size_t packed = (size_t)(ctx->n_pad / GP_CHUNK) * ctx->KS * 64 * sizeof(float);
+  const size_t packed = ((size_t)(ctx->n_pad / GP_CHUNK) * ctx->KS * 64 + GP_PACK_SLACK) * sizeof(float);
   GP_HIP(ctx, hipMalloc((void**)&ctx->dXA, packed));
   GP_HIP(ctx, hipMalloc((void**)&ctx->dXB, packed));
   GP_HIP(ctx, hipMalloc((void**)&ctx->dXs, (size_t)n * d * sizeof(float)));

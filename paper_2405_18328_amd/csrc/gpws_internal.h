@@ -18,6 +18,8 @@ constexpr int GP_WAVES = 4;           // wavefronts per workgroup
 constexpr int GP_THREADS = 64 * GP_WAVES;
 constexpr int GP_ROW_ALIGN = 256;     // packed operand arrays are padded to this many rows
 constexpr int GP_VEC_PAD = 4;         // solver arrays are padded to a multiple of 4 rows (float4 streams)
+constexpr float GP_PAD_NORM = 1.0e30f; // squared norm given to padding rows of XA (phi underflows to 0)
+constexpr int GP_PACK_SLACK = 256;    // floats allocated past the packed arrays: staging loads overrun by < 256
 constexpr int GP_PROF_MAX = 8192;     // event pairs available to gp_profile
 
 // Operands of the distance contraction, packed so that one wave-wide dword

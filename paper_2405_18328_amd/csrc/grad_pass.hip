@@ -46,12 +46,12 @@ template <int KIND, int KS, int KT, int NT>
 __global__ __launch_bounds__(GP_THREADS) void grad_tile_kernel(GradArgs p) {
   constexpr int NC = 32 * NT;
   constexpr int XA_F = KS * 64;
-  constexpr int CA_OFF = XA_F;
   constexpr int CA_F = KT * 64;
-  constexpr int V_OFF = CA_OFF + CA_F;
+  constexpr int XA_LD = (XA_F + GP_THREADS - 1) / GP_THREADS;
+  constexpr int CA_LD = (CA_F + GP_THREADS - 1) / GP_THREADS;
+  constexpr int CA_OFF = XA_LD * GP_THREADS;       // operand regions rounded up: unguarded staging
+  constexpr int V_OFF = CA_OFF + CA_LD * GP_THREADS;
   constexpr int STAGE = V_OFF + 32 * NC;
-  constexpr int OP_F = XA_F + CA_F;                       // both operand blocks, contiguous in LDS
-  constexpr int OP_LD = (OP_F + GP_THREADS - 1) / GP_THREADS;
   __shared__ __attribute__((aligned(16))) float lds[2][STAGE];
 
   const int tid = threadIdx.x;
@@ -79,49 +79,45 @@ __global__ __launch_bounds__(GP_THREADS) void grad_tile_kernel(GradArgs p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[nt][r] = 0.0f;
 
-  float gop[OP_LD];
+  // staging: unconditional loads, rows clamped to n-1 (padding rows of XA make psi exactly 0),
+  // columns clamped into the pass (their accumulator columns are never stored)
+  float gxa[XA_LD], gca[CA_LD];
   f32x4 gv[NT];
   const int ld_jq = tid >> 5;
   const int ld_c = tid & 31;
+  const int jmax = (int)(p.n - 1);
+  int col_off[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) col_off[nt] = p.col0 + min(ld_c + 32 * nt, p.ncols - 1);
 
   auto load_chunk = [&](int ch) {
     const float* xa = p.XA + (int64_t)ch * XA_F;
     const float* ca = p.CA + (int64_t)ch * CA_F;
 #pragma unroll
-    for (int u = 0; u < OP_LD; ++u) {
-      const int idx = tid + u * GP_THREADS;
-      float v = 0.0f;
-      if (idx < XA_F) v = xa[idx];
-      else if (idx < OP_F) v = ca[idx - XA_F];
-      gop[u] = v;
-    }
-    const int64_t j0 = (int64_t)ch * 32 + 4 * ld_jq;
+    for (int u = 0; u < XA_LD; ++u) gxa[u] = xa[tid + u * GP_THREADS];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const int cc = ld_c + 32 * nt;
+    for (int u = 0; u < CA_LD; ++u) gca[u] = ca[tid + u * GP_THREADS];
+    const int j0 = ch * 32 + 4 * ld_jq;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int64_t j = j0 + q;
-        gv[nt][q] = (j < p.n && cc < p.ncols) ? p.Q[j * p.ldq + p.col0 + cc] : 0.0f;
-      }
+    for (int q = 0; q < 4; ++q) {
+      const float* row = p.Q + (int64_t)min(j0 + q, jmax) * p.ldq;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) gv[nt][q] = row[col_off[nt]];
     }
   };
   auto store_chunk = [&](int st) {
     float* s = lds[st];
 #pragma unroll
-    for (int u = 0; u < OP_LD; ++u) {
-      const int idx = tid + u * GP_THREADS;
-      if (idx < OP_F) s[idx] = gop[u];
-    }
+    for (int u = 0; u < XA_LD; ++u) s[tid + u * GP_THREADS] = gxa[u];
+#pragma unroll
+    for (int u = 0; u < CA_LD; ++u) s[CA_OFF + tid + u * GP_THREADS] = gca[u];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
       *reinterpret_cast<f32x4*>(&s[V_OFF + (ld_jq * NC + ld_c + 32 * nt) * 4]) = gv[nt];
   };
 
-  if (c_begin < c_end) {
-    load_chunk(c_begin);
-    store_chunk(0);
-  }
+  load_chunk(c_begin);
+  store_chunk(0);
   __syncthreads();
 
   for (int ch = c_begin; ch < c_end; ++ch) {
@@ -350,7 +346,7 @@ int gp_grad_run(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int6
   const int KTmax = t <= 18 ? 9 : 33;
   const int G = 2 * ctx->num_cu;
   const size_t q_bytes = align_up((size_t)n * ldq * sizeof(float), 256);
-  const size_t op_bytes = align_up((size_t)(ctx->n_pad / 32) * KTmax * 64 * sizeof(float), 256);
+  const size_t op_bytes = align_up(((size_t)(ctx->n_pad / 32) * KTmax * 64 + GP_PACK_SLACK) * sizeof(float), 256);
   const size_t out_bytes = align_up((size_t)JS * n * nq * sizeof(float), 256);
   const size_t part_bytes = align_up((size_t)G * (d + 2) * sizeof(double), 256);
   const size_t acc_bytes = align_up((size_t)(d + 2) * sizeof(double), 256);

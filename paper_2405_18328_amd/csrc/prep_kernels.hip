@@ -49,6 +49,7 @@ __global__ void pack_kernel(const float* __restrict__ X, int64_t n, int64_t n_pa
   for (int k = d; k < 2 * KS; ++k) {
     const int off = (k >> 1) * 64 + (k & 1) * 32;
     float va = 0.0f, vb = 0.0f;
+    if (!live && k == d) va = GP_PAD_NORM;     // padding rows: r^2 is huge, the kernel value exactly 0
     if (live && k == d) { va = nf; vb = gamma; }
     if (live && k == d + 1) { va = 1.0f; vb = gamma * nf; }
     xa[off] = va;

@@ -54,10 +54,10 @@ template <int KIND, int KS, int NT, int MI>
 __global__ __launch_bounds__(GP_THREADS) void kmv_tile_kernel(TileArgs p) {
   constexpr int NC = 32 * NT;
   constexpr int XA_F = KS * 64;
-  constexpr int V_OFF = XA_F;
+  constexpr int XA_LD = (XA_F + GP_THREADS - 1) / GP_THREADS;
+  constexpr int V_OFF = XA_LD * GP_THREADS;        // XA region rounded up so its staging needs no guard
   constexpr int VY_OFF = V_OFF + 32 * NC;
   constexpr int STAGE = VY_OFF + 32;
-  constexpr int XA_LD = (XA_F + GP_THREADS - 1) / GP_THREADS;
   __shared__ __attribute__((aligned(16))) float lds[2][STAGE];
 
   const int tid = threadIdx.x;
@@ -90,52 +90,48 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_kernel(TileArgs p) {
       for (int r = 0; r < 16; ++r) acc[m][nt][r] = 0.0f;
   }
 
-  // staging registers for the next chunk
+  // Staging of the next chunk.  Every load is unconditional: row indices are clamped to n-1 and
+  // column indices into the pass's range.  Rows j >= n of XA carry a huge squared norm, so phi is
+  // exactly 0 for them whatever V row was read; clamped columns land in accumulator columns that
+  // are never stored.
   float gxa[XA_LD];
   f32x4 gv[NT];
   float gvy = 0.0f;
   const int ld_jq = tid >> 5;        // 0..7 : group of 4 consecutive rows j
   const int ld_c = tid & 31;
+  const int jmax = (int)(p.n - 1);
+  int col_off[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) col_off[nt] = p.col0 + min(ld_c + 32 * nt, p.ncols - 1);
+  const int vy_off = p.vcol >= 0 ? p.vcol : 0;
 
   auto load_chunk = [&](int ch) {
     const float* xa = p.XA + (int64_t)ch * XA_F;
 #pragma unroll
-    for (int u = 0; u < XA_LD; ++u) {
-      int idx = tid + u * GP_THREADS;
-      gxa[u] = (idx < XA_F) ? xa[idx] : 0.0f;
-    }
-    const int64_t j0 = (int64_t)ch * 32 + 4 * ld_jq;
+    for (int u = 0; u < XA_LD; ++u) gxa[u] = xa[tid + u * GP_THREADS];
+    const int j0 = ch * 32 + 4 * ld_jq;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const int cc = ld_c + 32 * nt;
+    for (int q = 0; q < 4; ++q) {
+      const float* row = p.V + (int64_t)min(j0 + q, jmax) * p.ldv;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int64_t j = j0 + q;
-        gv[nt][q] = (j < p.n && cc < p.ncols) ? p.V[j * p.ldv + p.col0 + cc] : 0.0f;
-      }
+      for (int nt = 0; nt < NT; ++nt) gv[nt][q] = row[col_off[nt]];
     }
-    if (tid < 32) {
-      const int64_t j = (int64_t)ch * 32 + tid;
-      gvy = (p.vcol >= 0 && j < p.n) ? p.V[j * p.ldv + p.vcol] : 0.0f;
-    }
+    gvy = p.V[(int64_t)min(ch * 32 + (tid & 31), jmax) * p.ldv + vy_off];
   };
   auto store_chunk = [&](int st) {
     float* s = lds[st];
 #pragma unroll
-    for (int u = 0; u < XA_LD; ++u) {
-      int idx = tid + u * GP_THREADS;
-      if (idx < XA_F) s[idx] = gxa[u];
-    }
+    for (int u = 0; u < XA_LD; ++u) s[tid + u * GP_THREADS] = gxa[u];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
       *reinterpret_cast<f32x4*>(&s[V_OFF + (ld_jq * NC + ld_c + 32 * nt) * 4]) = gv[nt];
     if (tid < 32) s[VY_OFF + tid] = gvy;
   };
 
-  if (c_begin < c_end) {
-    load_chunk(c_begin);
-    store_chunk(0);
-  }
+  // every split owns at least one chunk (the launcher sizes JS that way), so the prologue is
+  // unconditional; its wait for the staged chunk also retires the xb loads above
+  load_chunk(c_begin);
+  store_chunk(0);
   __syncthreads();
 
   for (int ch = c_begin; ch < c_end; ++ch) {
