@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstring>
 #include <cmath>
+#include <cstdlib>
 #include <new>
 
 #include "gpws_internal.h"
@@ -45,6 +46,13 @@ int gp_create(gp_ctx** out, int kernel, int64_t n, int d, const float* dX, void*
   ctx->n = n;
   ctx->d = d;
   ctx->KS = gp_ks_bucket(d);
+  ctx->KH = gp_kh_bucket(d, kernel);
+  ctx->path_forced = -1;
+  if (const char* f = getenv("GPWS_PATH")) {      // testing aid: pin the product path
+    if (!strcmp(f, "fp32")) ctx->path_forced = GP_PATH_FP32;
+    else if (!strcmp(f, "f16x2")) ctx->path_forced = GP_PATH_F16X2;
+    else if (!strcmp(f, "f16x3")) ctx->path_forced = GP_PATH_F16X3;
+  }
   ctx->n_pad = (n + GP_ROW_ALIGN - 1) / GP_ROW_ALIGN * GP_ROW_ALIGN;
   ctx->stream = (hipStream_t)hip_stream;
   ctx->dX = dX;
@@ -62,6 +70,15 @@ int gp_create(gp_ctx** out, int kernel, int64_t n, int d, const float* dX, void*
   GP_HIP(ctx, hipMalloc((void**)&ctx->dXA, packed));
   GP_HIP(ctx, hipMalloc((void**)&ctx->dXB, packed));
   GP_HIP(ctx, hipMalloc((void**)&ctx->dXs, (size_t)n * d * sizeof(float)));
+  GP_HIP(ctx, hipMalloc((void**)&ctx->dNorm, (size_t)ctx->n_pad * sizeof(float)));
+  GP_HIP(ctx, hipMalloc((void**)&ctx->dMaxNorm, 256));
+  {
+    const size_t units = (size_t)(ctx->n_pad / GP_CHUNK) * ctx->KH * 64;
+    for (int pc = 0; pc < 3; ++pc) {
+      GP_HIP(ctx, hipMalloc(&ctx->dXAh[pc], units * 16));
+      GP_HIP(ctx, hipMalloc(&ctx->dXBh[pc], units * 16));
+    }
+  }
   GP_HIP(ctx, hipMalloc((void**)&ctx->dMean, sizeof(double) * d));
   GP_HIP(ctx, hipMalloc((void**)&ctx->dTheta, sizeof(double) * (d + 2)));
   ctx->red_bytes = (size_t)1 << 22;
@@ -77,6 +94,12 @@ int gp_destroy(gp_ctx* ctx) {
   if (ctx->dXA) (void)hipFree(ctx->dXA);
   if (ctx->dXB) (void)hipFree(ctx->dXB);
   if (ctx->dXs) (void)hipFree(ctx->dXs);
+  if (ctx->dNorm) (void)hipFree(ctx->dNorm);
+  if (ctx->dMaxNorm) (void)hipFree(ctx->dMaxNorm);
+  for (int pc = 0; pc < 3; ++pc) {
+    if (ctx->dXAh[pc]) (void)hipFree(ctx->dXAh[pc]);
+    if (ctx->dXBh[pc]) (void)hipFree(ctx->dXBh[pc]);
+  }
   if (ctx->dMean) (void)hipFree(ctx->dMean);
   if (ctx->dTheta) (void)hipFree(ctx->dTheta);
   if (ctx->dRed) (void)hipFree(ctx->dRed);
@@ -113,8 +136,22 @@ int gp_set_theta(gp_ctx* ctx, const double* h_lengthscale, double signal_scale, 
   ctx->a = signal_scale;
   ctx->sigma = noise_scale;
   GP_HIP(ctx, hipMemcpyAsync(ctx->dTheta, stage, sizeof(double) * (ctx->d + 2), hipMemcpyHostToDevice, ctx->stream));
+  GP_HIP(ctx, hipMemsetAsync(ctx->dMaxNorm, 0, sizeof(unsigned), ctx->stream));
   int rc = gp_launch_pack(ctx);
   if (rc < 0) return rc;
+  // the largest scaled squared norm decides which product path holds the error budget
+  float* hmax = (float*)((char*)ctx->hPinned + 4096);
+  GP_HIP(ctx, hipMemcpyAsync(hmax, ctx->dMaxNorm, sizeof(float), hipMemcpyDeviceToHost, ctx->stream));
+  GP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  ctx->max_norm = *hmax;
+  if (!std::isfinite(ctx->max_norm))
+    return gp_fail(ctx, GP_ERR_ARG, "gp_set_theta: inputs scaled by the lengthscales are not finite");
+  int path = ctx->max_norm <= GP_NORM_X2_MAX ? GP_PATH_F16X2
+             : ctx->max_norm <= GP_NORM_X3_MAX ? GP_PATH_F16X3 : GP_PATH_FP32;
+  if (ctx->path_forced >= 0 && !(ctx->path_forced != GP_PATH_FP32 && ctx->max_norm > GP_NORM_X3_MAX))
+    path = ctx->path_forced;
+  ctx->path = path;
+  ctx->XP = path == GP_PATH_F16X3 ? 3 : 2;
   ctx->theta_set = true;
   return GP_OK;
 }

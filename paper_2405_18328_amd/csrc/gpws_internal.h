@@ -20,6 +20,12 @@ constexpr int GP_ROW_ALIGN = 256;     // packed operand arrays are padded to thi
 constexpr int GP_VEC_PAD = 4;         // solver arrays are padded to a multiple of 4 rows (float4 streams)
 constexpr float GP_PAD_NORM = 1.0e30f; // squared norm given to padding rows of XA (phi underflows to 0)
 constexpr int GP_PACK_SLACK = 256;    // floats allocated past the packed arrays: staging loads overrun by < 256
+constexpr float GP_PAD_NORM_H = 60000.0f;  // same for the fp16 operands (must fit fp16)
+enum { GP_PATH_FP32 = 0, GP_PATH_F16X2 = 1, GP_PATH_F16X3 = 2 };
+// fp16 distance pieces: two pieces carry 22 bits, so r^2 has an absolute error ~2^-22 (|xs_i|^2+|xs_j|^2);
+// past this squared norm three pieces (33 bits) are used, and past fp16's range the fp32 MFMA path
+constexpr float GP_NORM_X2_MAX = 64.0f;
+constexpr float GP_NORM_X3_MAX = 16000.0f;
 constexpr int GP_PROF_MAX = 8192;     // event pairs available to gp_profile
 
 // Operands of the distance contraction, packed so that one wave-wide dword
@@ -40,6 +46,17 @@ struct gp_ctx {
   float* dXA;             // packed, n_pad/32 * KS * 64
   float* dXB;
   float* dXs;             // scaled centred inputs, row-major n x d (gradient pass)
+  float* dNorm;           // |xs_i|^2, n_pad entries
+  unsigned* dMaxNorm;     // bit pattern of max_i |xs_i|^2 (device), refreshed by gp_set_theta
+  // split-fp16 operands of the matrix-core path: three pieces (hi, mid, lo) per side, 16-byte units
+  // [(chunk*KH + kh)*64 + lane], element e of a unit = component 16 kh + 8 (lane/32) + e
+  void* dXAh[3];
+  void* dXBh[3];
+  int KH;                 // 16-wide k-steps of the fp16 distance chain, bucketed
+  int XP;                 // pieces used per operand of the distance chain (2 or 3)
+  int path;               // GP_PATH_* chosen by gp_set_theta
+  int path_forced;        // -1, or a GP_PATH_* forced through the GPWS_PATH environment variable
+  float max_norm;         // host copy of max_i |xs_i|^2
   double* dMean;          // d column means of X
   double* dTheta;         // device copy: 1/ell (d), then a, sigma
   bool theta_set;
@@ -84,10 +101,17 @@ struct KmvPlan {
   int cps;       // chunks per split
 };
 KmvPlan gp_plan_kmv(const gp_ctx* ctx);
-size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t);
+size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t);   // worst case over the paths gp_set_theta may choose
 // OUT = K V (+ sigma^2 V).  scratch is used only when the plan splits the column range.
 int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
                   int add_noise, void* scratch, size_t scratch_bytes);
+
+// ---- tile_pass_f16.hip
+int gp_kh_bucket(int d, int kernel);
+KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx);
+size_t gp_kmv_f16_scratch_bytes(const gp_ctx* ctx, int t);
+int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
+                      int add_noise, void* scratch, size_t scratch_bytes);
 
 // ---- cg_kernels.hip
 int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv,

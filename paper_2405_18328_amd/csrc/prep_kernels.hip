@@ -25,7 +25,7 @@ __global__ void column_mean_kernel(const float* __restrict__ X, int64_t n, int d
 __global__ void pack_kernel(const float* __restrict__ X, int64_t n, int64_t n_pad, int d, int KS,
                             const double* __restrict__ mean, const double* __restrict__ theta /* 1/ell (d) */,
                             float gamma, float* __restrict__ XA, float* __restrict__ XB,
-                            float* __restrict__ Xs) {
+                            float* __restrict__ Xs, float* __restrict__ norm, unsigned* __restrict__ max_norm) {
   const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (row >= n_pad) return;
   const int64_t chunk = row >> 5;
@@ -46,6 +46,8 @@ __global__ void pack_kernel(const float* __restrict__ X, int64_t n, int64_t n_pa
     xb[off] = -2.0f * gamma * xs;
   }
   const float nf = (float)nrm;
+  norm[row] = nf;
+  if (live) atomicMax(max_norm, __float_as_uint(nf));     // non-negative floats order like unsigned ints
   for (int k = d; k < 2 * KS; ++k) {
     const int off = (k >> 1) * 64 + (k & 1) * 32;
     float va = 0.0f, vb = 0.0f;
@@ -55,6 +57,59 @@ __global__ void pack_kernel(const float* __restrict__ X, int64_t n, int64_t n_pa
     xa[off] = va;
     xb[off] = vb;
   }
+}
+
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// x = hi + mid + lo with hi, mid truncated to 11 significant bits (exact in fp16), lo rounded
+__device__ __forceinline__ void split3(float x, float& hi, float& mid, float& lo) {
+  hi = __uint_as_float(__float_as_uint(x) & 0xFFFFE000u);
+  const float r1 = x - hi;
+  mid = __uint_as_float(__float_as_uint(r1) & 0xFFFFE000u);
+  lo = r1 - mid;
+}
+
+// split-fp16 operands of the matrix-core path; one thread per (chunk, kh, lane)
+__global__ void pack_f16_kernel(const float* __restrict__ Xs, const float* __restrict__ norm, int64_t n,
+                                int64_t n_pad, int d, int KH, int is_se, float gamma, u32x4* __restrict__ A0,
+                                u32x4* __restrict__ A1, u32x4* __restrict__ A2, u32x4* __restrict__ B0,
+                                u32x4* __restrict__ B1, u32x4* __restrict__ B2) {
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t total = (n_pad / 32) * KH * 64;
+  if (gid >= total) return;
+  const int lane = (int)(gid & 63);
+  const int kh = (int)((gid >> 6) % KH);
+  const int64_t chunk = (gid >> 6) / KH;
+  const int64_t row = chunk * 32 + (lane & 31);
+  const bool live = row < n;
+  const float nf = norm[row];
+  u32x4 a[3], b[3];
+#pragma unroll
+  for (int e2 = 0; e2 < 4; ++e2) {
+    float pa[3][2], pb[3][2];
+#pragma unroll
+    for (int z = 0; z < 2; ++z) {
+      const int k = 16 * kh + 8 * (lane >> 5) + 2 * e2 + z;
+      float va = 0.0f, vb = 0.0f;
+      if (live) {
+        if (k < d) { const float xs = Xs[row * d + k]; va = xs; vb = -2.0f * gamma * xs; }
+        else if (k == d) { va = nf; vb = gamma; }
+        else if (k == d + 1) { va = 1.0f; vb = gamma * nf; }
+        else if (k == d + 2 && is_se) { va = 1.0f; vb = 15.0f; }   // phi is carried as 2^15 phi
+      } else if (k == d) {
+        va = GP_PAD_NORM_H;
+      }
+      split3(va, pa[0][z], pa[1][z], pa[2][z]);
+      split3(vb, pb[0][z], pb[1][z], pb[2][z]);
+    }
+#pragma unroll
+    for (int pc = 0; pc < 3; ++pc) {
+      a[pc][e2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(pa[pc][0], pa[pc][1]));
+      b[pc][e2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(pb[pc][0], pb[pc][1]));
+    }
+  }
+  A0[gid] = a[0]; A1[gid] = a[1]; A2[gid] = a[2];
+  B0[gid] = b[0]; B1[gid] = b[1]; B2[gid] = b[2];
 }
 
 }  // namespace
@@ -71,7 +126,13 @@ int gp_launch_pack(gp_ctx* ctx) {
   const int blocks = (int)((ctx->n_pad + 255) / 256);
   hipLaunchKernelGGL(pack_kernel, dim3(blocks), dim3(256), 0, ctx->stream, ctx->dX, ctx->n, ctx->n_pad, ctx->d,
                      ctx->KS, (const double*)ctx->dMean, (const double*)ctx->dTheta, gamma, ctx->dXA, ctx->dXB,
-                     ctx->dXs);
+                     ctx->dXs, ctx->dNorm, ctx->dMaxNorm);
+  GP_HIP(ctx, hipGetLastError());
+  const int64_t units = (ctx->n_pad / 32) * ctx->KH * 64;
+  hipLaunchKernelGGL(pack_f16_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, ctx->stream,
+                     (const float*)ctx->dXs, (const float*)ctx->dNorm, ctx->n, ctx->n_pad, ctx->d, ctx->KH,
+                     ctx->kernel == GP_SE_ARD ? 1 : 0, gamma, (u32x4*)ctx->dXAh[0], (u32x4*)ctx->dXAh[1],
+                     (u32x4*)ctx->dXAh[2], (u32x4*)ctx->dXBh[0], (u32x4*)ctx->dXBh[1], (u32x4*)ctx->dXBh[2]);
   GP_HIP(ctx, hipGetLastError());
   return GP_OK;
 }

@@ -281,15 +281,18 @@ KmvPlan gp_plan_kmv(const gp_ctx* ctx) {
 
 size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t) {
   KmvPlan pl = gp_plan_kmv(ctx);
-  if (pl.JS <= 1) return 0;
-  return (size_t)pl.JS * (size_t)ctx->n * (size_t)t * sizeof(float);
+  const size_t fp32_bytes = pl.JS <= 1 ? 0 : (size_t)pl.JS * (size_t)ctx->n * (size_t)t * sizeof(float);
+  const size_t f16_bytes = gp_kmv_f16_scratch_bytes(ctx, t);
+  return fp32_bytes > f16_bytes ? fp32_bytes : f16_bytes;
 }
 
 int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
                   int add_noise, void* scratch, size_t scratch_bytes) {
+  if (ctx->path != GP_PATH_FP32)
+    return gp_kmv_launch_f16(ctx, dV, ldv, t, dOut, ldo, add_noise, scratch, scratch_bytes);
   const KmvPlan pl = gp_plan_kmv(ctx);
   const bool split = pl.JS > 1;
-  if (split && scratch_bytes < gp_kmv_scratch_bytes(ctx, t))
+  if (split && scratch_bytes < (size_t)pl.JS * (size_t)ctx->n * (size_t)t * sizeof(float))
     return gp_fail(ctx, GP_ERR_WORKSPACE, "gp_kmv: scratch too small for %d column splits", pl.JS);
 
   TileArgs a;

@@ -1,0 +1,502 @@
+// Matrix-free product OUT = K V (+ sigma^2 V), split-fp16 matrix-core path.
+//
+// On gfx950 the fp32 MFMA shares the SIMD's FMA lanes with the VALU (measured: VALU work adds to
+// fp32-MFMA time instead of hiding under it), while the fp16 MFMA runs on the matrix cores at 16x the
+// rate and overlaps with VALU work.  This path therefore evaluates both contractions of the tile pass
+// with v_mfma_f32_32x32x16_f16 on operands split into fp16 pieces, fp32 accumulation:
+//   x = hi + mid (+ lo), each piece an 11-bit fp16 mantissa, hi and mid obtained by truncation, so
+//   a.b ~ ah.bh + ah.bm + am.bh (+ ah.bl + al.bh + am.bm): relative error 2^-22 (2^-33), i.e. fp32-class.
+// The VALU keeps what needs fp32: the kernel function (exp2 / sqrt) and the split of phi.
+//
+// Per 32x32 tile of pairs (j, i), one wavefront:
+//   1. S[j][i] = XA_j . XB_i     3 (or 6) MFMAs per 16 components      (= g r^2_ij [+ 15 for SE])
+//   2. phi' = 2^15 phi(S)        VALU; hi = phi' & 0xFFFFE000, lo = phi' - hi; packed to fp16 pairs
+//   3. OUT_i += phi'[i][j] V'_j  2 k-steps x NT x 3 MFMAs; V' = V scaled per column by a power of two
+//                                so that max |V'_c| is in [2^13, 2^14), pre-split and pre-packed
+// The accumulator layout of step 1 (lane = i, register r <-> j = 8(r/4) + 4(lane/32) + r%4) gives each lane
+// eight consecutive registers per k-step that are exactly its eight A-operand elements, provided the
+// V' rows are packed in that order; phi never leaves registers, K is never stored.
+#include "gpws_internal.h"
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr unsigned HI_MASK = 0xFFFFE000u;       // keeps sign, exponent and the top 10 mantissa bits
+constexpr int PHI_SHIFT = 15;                   // phi' = 2^15 phi <= 32768 stays inside fp16's range
+constexpr int V_TOP = 14;                       // max |V'_c| in [2^13, 2^14)
+
+// exponent e with max = f 2^e, f in [0.5, 1); 14 for an all-zero column (scale 1)
+__device__ __forceinline__ int column_exponent(unsigned max_bits) {
+  const float m = __uint_as_float(max_bits);
+  if (!(m > 0.0f)) return V_TOP;
+  int e;
+  (void)frexpf(m, &e);
+  return e < -60 ? -60 : e;
+}
+
+struct TileArgsH {
+  const u32x4* XA[3];     // column-side pieces, 16-byte units [(chunk*KH + kh)*64 + lane]
+  const u32x4* XB[3];     // row-side pieces
+  const u32x4* VP;        // packed V' images of this pass, [chunk][mh][nt][part][lane]
+  const float* VY;        // [n_pad] the VALU column, unscaled (zeros when unused)
+  const float* V;         // the caller's V (noise term in the epilogue)
+  int64_t ldv;
+  const unsigned* colmax; // [t] bit patterns of max_i |V_ic|
+  float* OUT;
+  int64_t ldo;
+  int64_t split_stride;
+  int64_t n;
+  int nchunks;
+  int col0, ncols, vcol;
+  int JS, cps;
+  float a2, sigma2;
+  int add_noise;
+};
+
+__device__ __forceinline__ f16x8 as_f16x8(u32x4 v) { return __builtin_bit_cast(f16x8, v); }
+
+template <int KIND, int KH, int XP, int NT, int MI>
+__global__ __launch_bounds__(GP_THREADS) void kmv_tile_f16_kernel(TileArgsH p) {
+  constexpr int XA_U = XP * KH * 64;                                  // 16-byte units of XA per chunk
+  constexpr int XA_LD = (XA_U + GP_THREADS - 1) / GP_THREADS;
+  constexpr int V_OFF = XA_LD * GP_THREADS;
+  constexpr int V_U = 2 * NT * 2 * 64;                                // = 256 NT
+  constexpr int VY_OFF = V_OFF + V_U;
+  constexpr int STAGE = VY_OFF + 8;
+  __shared__ u32x4 lds[2][STAGE];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int h = lane >> 5;
+  const int li = lane & 31;
+  const int js = blockIdx.x % p.JS;
+  const int rb = blockIdx.x / p.JS;
+  const int sub0 = (rb * GP_WAVES + wave) * MI;
+  const int c_begin = js * p.cps;
+  const int c_end = min(p.nchunks, c_begin + p.cps);
+
+  // row-side operands: registers for the whole pass
+  f16x8 xb[MI][XP][KH];
+#pragma unroll
+  for (int m = 0; m < MI; ++m)
+#pragma unroll
+    for (int pc = 0; pc < XP; ++pc)
+#pragma unroll
+      for (int kh = 0; kh < KH; ++kh)
+        xb[m][pc][kh] = as_f16x8(p.XB[pc][((int64_t)(sub0 + m) * KH + kh) * 64 + lane]);
+
+  f32x16 acc[MI][NT];
+  float accv[MI];
+#pragma unroll
+  for (int m = 0; m < MI; ++m) {
+    accv[m] = 0.0f;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[m][nt][r] = 0.0f;
+  }
+
+  // staging: straight 16-byte copies, unconditional (unit indices past the XA image are clamped
+  // for the load and land in the padding of the LDS region)
+  const u32x4* xa_src[XA_LD];
+#pragma unroll
+  for (int x = 0; x < XA_LD; ++x) {
+    const int u = min(tid + x * GP_THREADS, XA_U - 1);
+    xa_src[x] = p.XA[u / (KH * 64)] + (u % (KH * 64));
+  }
+  u32x4 gxa[XA_LD], gv[NT], gvy;
+  gvy = u32x4{0, 0, 0, 0};
+  auto load_chunk = [&](int ch) {
+#pragma unroll
+    for (int x = 0; x < XA_LD; ++x) gxa[x] = xa_src[x][(int64_t)ch * (KH * 64)];
+    const u32x4* vp = p.VP + (int64_t)ch * V_U;
+#pragma unroll
+    for (int x = 0; x < NT; ++x) gv[x] = vp[tid + x * GP_THREADS];
+    if (tid < 8) gvy = reinterpret_cast<const u32x4*>(p.VY + (int64_t)ch * 32)[tid];
+  };
+  auto store_chunk = [&](int st) {
+    u32x4* s = lds[st];
+#pragma unroll
+    for (int x = 0; x < XA_LD; ++x) s[tid + x * GP_THREADS] = gxa[x];
+#pragma unroll
+    for (int x = 0; x < NT; ++x) s[V_OFF + tid + x * GP_THREADS] = gv[x];
+    if (tid < 8) s[VY_OFF + tid] = gvy;
+  };
+
+  load_chunk(c_begin);
+  store_chunk(0);
+  __syncthreads();
+
+  for (int ch = c_begin; ch < c_end; ++ch) {
+    const int st = (ch - c_begin) & 1;
+    if (ch + 1 < c_end) load_chunk(ch + 1);
+    const u32x4* s = lds[st];
+
+    f32x16 S[MI];
+#pragma unroll
+    for (int m = 0; m < MI; ++m)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) S[m][r] = 0.0f;
+#pragma unroll
+    for (int kh = 0; kh < KH; ++kh) {
+      f16x8 xa[XP];
+#pragma unroll
+      for (int pc = 0; pc < XP; ++pc) xa[pc] = as_f16x8(s[(pc * KH + kh) * 64 + lane]);
+#pragma unroll
+      for (int m = 0; m < MI; ++m) {
+        // smallest terms first
+        if constexpr (XP == 3) {
+          S[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[1], xb[m][1][kh], S[m], 0, 0, 0);
+          S[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[2], xb[m][0][kh], S[m], 0, 0, 0);
+          S[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0], xb[m][XP - 1][kh], S[m], 0, 0, 0);
+        }
+        S[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[1], xb[m][0][kh], S[m], 0, 0, 0);
+        S[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0], xb[m][1][kh], S[m], 0, 0, 0);
+        S[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0], xb[m][0][kh], S[m], 0, 0, 0);
+      }
+    }
+    // the pair (i, i): r^2 is exactly zero
+#pragma unroll
+    for (int m = 0; m < MI; ++m) {
+      if (ch == sub0 + m) {
+        const float s0 = KIND == GP_SE_ARD ? (float)PHI_SHIFT : 0.0f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (8 * (r >> 2) + 4 * h + (r & 3) == li) S[m][r] = s0;
+      }
+    }
+
+#pragma unroll
+    for (int mh = 0; mh < 2; ++mh) {
+      // this lane's y values for j = 16 mh + 8 g + 4 h + q
+      f32x4 vy[2];
+#pragma unroll
+      for (int g = 0; g < 2; ++g) vy[g] = __builtin_bit_cast(f32x4, s[VY_OFF + 2 * (2 * mh + g) + h]);
+      f16x8 bh[NT], bl[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        bh[nt] = as_f16x8(s[V_OFF + ((mh * NT + nt) * 2 + 0) * 64 + lane]);
+        bl[nt] = as_f16x8(s[V_OFF + ((mh * NT + nt) * 2 + 1) * 64 + lane]);
+      }
+#pragma unroll
+      for (int m = 0; m < MI; ++m) {
+        u32x4 ph, pl;
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+          float f[2], fh[2], fl[2];
+#pragma unroll
+          for (int z = 0; z < 2; ++z) {
+            const int e = 2 * e2 + z;
+            const float sv = S[m][8 * mh + e];
+            if (KIND == GP_SE_ARD) {
+              f[z] = __builtin_amdgcn_exp2f(sv);                 // sv = -log2(e)/2 r^2 + 15
+            } else {
+              const float u = __builtin_amdgcn_sqrtf(fmaxf(sv, 0.0f));        // sv = 3 r^2
+              const float ex = __builtin_amdgcn_exp2f(fmaf(u, -LOG2E, (float)PHI_SHIFT));
+              f[z] = fmaf(u, ex, ex);
+            }
+            accv[m] = fmaf(f[z], vy[e >> 2][e & 3], accv[m]);
+            fh[z] = __uint_as_float(__float_as_uint(f[z]) & HI_MASK);
+            fl[z] = f[z] - fh[z];
+          }
+          ph[e2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(fh[0], fh[1]));
+          pl[e2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(fl[0], fl[1]));
+        }
+        const f16x8 ah = as_f16x8(ph), al = as_f16x8(pl);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          acc[m][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, bh[nt], acc[m][nt], 0, 0, 0);
+          acc[m][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bl[nt], acc[m][nt], 0, 0, 0);
+          acc[m][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bh[nt], acc[m][nt], 0, 0, 0);
+        }
+      }
+    }
+    if (ch + 1 < c_end) store_chunk(st ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue: undo the power-of-two scalings, multiply by a^2, add the noise term once, store
+  float* out = p.OUT + (int64_t)js * p.split_stride;
+  const bool noise = p.add_noise && js == 0;
+  float oscale[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int c = min(li + 32 * nt, p.ncols - 1);
+    oscale[nt] = p.a2 * ldexpf(1.0f, column_exponent(p.colmax[p.col0 + c]) - V_TOP - PHI_SHIFT);
+  }
+#pragma unroll
+  for (int m = 0; m < MI; ++m) {
+    const int64_t ibase = (int64_t)(sub0 + m) * 32;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int c = li + 32 * nt;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t i = ibase + 8 * (r >> 2) + 4 * h + (r & 3);
+        if (i < p.n && c < p.ncols) {
+          float v = oscale[nt] * acc[m][nt][r];
+          if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.col0 + c], v);
+          out[i * p.ldo + p.col0 + c] = v;
+        }
+      }
+    }
+    if (p.vcol >= 0) {
+      const float tot = accv[m] + __shfl_xor(accv[m], 32);
+      const int64_t i = ibase + li;
+      if (h == 0 && i < p.n) {
+        float v = p.a2 * ldexpf(1.0f, -PHI_SHIFT) * tot;
+        if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.vcol], v);
+        out[i * p.ldo + p.vcol] = v;
+      }
+    }
+  }
+}
+
+// ---- per-call operand preparation -------------------------------------------------------------
+// colmax[c] = max_i |V_ic| as a bit pattern (non-negative floats order like unsigned ints)
+__global__ __launch_bounds__(256) void colmax_kernel(const float* __restrict__ V, int64_t ldv, int64_t n, int t,
+                                                     unsigned* __restrict__ colmax) {
+  extern __shared__ unsigned smax[];   // [t]
+  for (int c = threadIdx.x; c < t; c += 256) smax[c] = 0u;
+  __syncthreads();
+  const int64_t rows_per_block = (n + gridDim.x - 1) / gridDim.x;
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+  const int64_t r1 = min(n, r0 + rows_per_block);
+  const int64_t cnt = (r1 > r0 ? r1 - r0 : 0) * t;
+  for (int64_t e = threadIdx.x; e < cnt; e += 256) {
+    const int64_t i = r0 + e / t;
+    const int c = (int)(e % t);
+    atomicMax(&smax[c], __float_as_uint(fabsf(V[i * ldv + c])));
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < t; c += 256)
+    if (smax[c]) atomicMax(&colmax[c], smax[c]);
+}
+
+// V' images of one column pass: unit u = ((chunk*2 + mh)*NT + nt)*2 + part, lane l: element e is
+// V'[32 chunk + 16 mh + 8 (e/4) + 4 (l/32) + e%4][col0 + 32 nt + l%32]; rows >= n and columns past the pass are zero.
+__global__ __launch_bounds__(256) void pack_v_kernel(const float* __restrict__ V, int64_t ldv, int64_t n, int nchunks,
+                                                     int NT, int col0, int ncols, int vcol,
+                                                     const unsigned* __restrict__ colmax, u32x4* __restrict__ VP,
+                                                     float* __restrict__ VY) {
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t total = (int64_t)nchunks * 2 * NT * 64;
+  if (gid < total) {
+    const int lane = (int)(gid & 63);
+    int64_t q = gid >> 6;
+    const int nt = (int)(q % NT); q /= NT;
+    const int mh = (int)(q & 1);
+    const int64_t chunk = q >> 1;
+    const int hh = lane >> 5;
+    const int cc = 32 * nt + (lane & 31);
+    const bool cok = cc < ncols;
+    const int col = col0 + (cok ? cc : 0);
+    const float scale = ldexpf(1.0f, V_TOP - column_exponent(colmax[col]));
+    u32x4 hi, lo;
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+      float fh[2], fl[2];
+#pragma unroll
+      for (int z = 0; z < 2; ++z) {
+        const int e = 2 * e2 + z;
+        const int64_t j = chunk * 32 + 16 * mh + 8 * (e >> 2) + 4 * hh + (e & 3);
+        const float v = (cok && j < n) ? V[j * ldv + col] * scale : 0.0f;
+        fh[z] = __uint_as_float(__float_as_uint(v) & HI_MASK);
+        fl[z] = v - fh[z];
+      }
+      hi[e2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(fh[0], fh[1]));
+      lo[e2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(fl[0], fl[1]));
+    }
+    u32x4* dst = VP + ((chunk * 2 + mh) * NT + nt) * 2 * 64;
+    dst[lane] = hi;
+    dst[64 + lane] = lo;
+  }
+  // the VALU column, unscaled
+  const int64_t npad = (int64_t)nchunks * 32;
+  if (gid < npad) VY[gid] = (vcol >= 0 && gid < n) ? V[gid * ldv + vcol] : 0.0f;
+}
+
+__global__ void kmv_reduce_f16_kernel(const float* __restrict__ part, int64_t split_stride, int JS, int64_t n, int t,
+                                      float* __restrict__ out, int64_t ldo) {
+  const int64_t total = n * t;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t i = e / t;
+    const int c = (int)(e - i * t);
+    float s = 0.0f;
+    for (int k = 0; k < JS; ++k) s += part[(int64_t)k * split_stride + e];
+    out[i * ldo + c] = s;
+  }
+}
+
+typedef void (*tileh_fn)(TileArgsH);
+
+template <int KIND, int KH, int XP>
+tileh_fn pick_h_nt_mi(int NT, int MI) {
+  if constexpr (KH <= 2) {
+    if (MI == 2) return NT == 1 ? kmv_tile_f16_kernel<KIND, KH, XP, 1, 2> : kmv_tile_f16_kernel<KIND, KH, XP, 2, 2>;
+  }
+  return NT == 1 ? kmv_tile_f16_kernel<KIND, KH, XP, 1, 1> : kmv_tile_f16_kernel<KIND, KH, XP, 2, 1>;
+}
+
+template <int KIND, int XP>
+tileh_fn pick_h_kh(int KH, int NT, int MI) {
+  switch (KH) {
+    case 1: return pick_h_nt_mi<KIND, 1, XP>(NT, MI);
+    case 2: return pick_h_nt_mi<KIND, 2, XP>(NT, MI);
+    case 3: return pick_h_nt_mi<KIND, 3, XP>(NT, MI);
+    case 4: return pick_h_nt_mi<KIND, 4, XP>(NT, MI);
+    case 6: return pick_h_nt_mi<KIND, 6, XP>(NT, MI);
+    case 8: return pick_h_nt_mi<KIND, 8, XP>(NT, MI);
+  }
+  return nullptr;
+}
+
+tileh_fn pick_h(int kind, int KH, int XP, int NT, int MI) {
+  if (kind == GP_SE_ARD) return XP == 2 ? pick_h_kh<GP_SE_ARD, 2>(KH, NT, MI) : pick_h_kh<GP_SE_ARD, 3>(KH, NT, MI);
+  return XP == 2 ? pick_h_kh<GP_MATERN32_ARD, 2>(KH, NT, MI) : pick_h_kh<GP_MATERN32_ARD, 3>(KH, NT, MI);
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct ScratchH {
+  size_t off_colmax, off_vy, off_vp, off_part, total;
+};
+
+ScratchH scratch_layout(const gp_ctx* ctx, int t, int JS) {
+  ScratchH L;
+  const int64_t nchunks = (ctx->n + 31) / 32;
+  size_t o = 0;
+  L.off_colmax = o; o += align_up((size_t)t * sizeof(unsigned), 256);
+  L.off_vy = o; o += align_up((size_t)nchunks * 32 * sizeof(float), 256);
+  L.off_vp = o; o += align_up((size_t)nchunks * 2 * 2 * 2 * 64 * 16, 256);      // NT = 2 images
+  L.off_part = o;
+  if (JS > 1) o += align_up((size_t)JS * ctx->n * t * sizeof(float), 256);
+  L.total = o;
+  return L;
+}
+
+}  // namespace
+
+int gp_kh_bucket(int d, int kernel) {
+  // components: d coordinates, squared norm, one, and for SE the slot that carries the 2^15 shift
+  const int comps = d + 2 + (kernel == GP_SE_ARD ? 1 : 0);
+  const int need = (comps + 15) / 16;
+  const int buckets[] = {1, 2, 3, 4, 6, 8};
+  for (int b : buckets)
+    if (need <= b) return b;
+  return -1;
+}
+
+KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx) {
+  KmvPlan pl;
+  const int64_t chunks = (ctx->n + 31) / 32;
+  pl.MI = (ctx->KH <= 2 && ctx->n >= 8192) ? 2 : 1;
+  const int rows_per_wg = 32 * GP_WAVES * pl.MI;
+  pl.row_blocks = (int)((ctx->n + rows_per_wg - 1) / rows_per_wg);
+  const int target = 2 * ctx->num_cu;
+  int JS = 1;
+  if (pl.row_blocks < target) {
+    JS = (target + pl.row_blocks - 1) / pl.row_blocks;
+    const int64_t max_js = chunks / 4 > 0 ? chunks / 4 : 1;
+    if (JS > max_js) JS = (int)max_js;
+    if (JS > 64) JS = 64;
+  }
+  pl.cps = (int)((chunks + JS - 1) / JS);
+  pl.JS = (int)((chunks + pl.cps - 1) / pl.cps);
+  return pl;
+}
+
+size_t gp_kmv_f16_scratch_bytes(const gp_ctx* ctx, int t) {
+  return scratch_layout(ctx, t, gp_plan_kmv_f16(ctx).JS).total;
+}
+
+int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo, int add_noise,
+                      void* scratch, size_t scratch_bytes) {
+  const KmvPlan pl = gp_plan_kmv_f16(ctx);
+  const ScratchH L = scratch_layout(ctx, t, pl.JS);
+  if (scratch_bytes < L.total || !scratch)
+    return gp_fail(ctx, GP_ERR_WORKSPACE, "gp_kmv: scratch %zu < %zu bytes", scratch_bytes, L.total);
+  hipStream_t st = ctx->stream;
+  char* w = (char*)scratch;
+  unsigned* colmax = (unsigned*)(w + L.off_colmax);
+  float* VY = (float*)(w + L.off_vy);
+  u32x4* VP = (u32x4*)(w + L.off_vp);
+  float* part = (float*)(w + L.off_part);
+  const bool split = pl.JS > 1;
+  const int nchunks = (int)((ctx->n + 31) / 32);
+
+  GP_HIP(ctx, hipMemsetAsync(colmax, 0, (size_t)t * sizeof(unsigned), st));
+  {
+    int blocks = (int)((ctx->n * (int64_t)t + 4095) / 4096);
+    if (blocks > 4 * ctx->num_cu) blocks = 4 * ctx->num_cu;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(colmax_kernel, dim3(blocks), dim3(256), (size_t)t * sizeof(unsigned), st, dV, ldv, ctx->n, t, colmax);
+    GP_HIP(ctx, hipGetLastError());
+  }
+
+  TileArgsH a;
+  for (int pc = 0; pc < 3; ++pc) {
+    a.XA[pc] = (const u32x4*)ctx->dXAh[pc];
+    a.XB[pc] = (const u32x4*)ctx->dXBh[pc];
+  }
+  a.VP = VP;
+  a.VY = VY;
+  a.V = dV;
+  a.ldv = ldv;
+  a.colmax = colmax;
+  a.OUT = split ? part : dOut;
+  a.ldo = split ? t : ldo;
+  a.split_stride = split ? ctx->n * (int64_t)t : 0;
+  a.n = ctx->n;
+  a.nchunks = nchunks;
+  a.JS = pl.JS;
+  a.cps = pl.cps;
+  a.a2 = (float)(ctx->a * ctx->a);
+  a.sigma2 = (float)(ctx->sigma * ctx->sigma);
+  a.add_noise = add_noise;
+
+  int vcol = (t > 1 && t % 32 == 1) ? 0 : -1;
+  int c = vcol >= 0 ? 1 : 0;
+  const dim3 grid(pl.row_blocks * pl.JS), block(GP_THREADS);
+  while (c < t) {
+    const int rem = t - c;
+    const int NT = rem > 32 ? 2 : 1;
+    a.col0 = c;
+    a.ncols = rem < 32 * NT ? rem : 32 * NT;
+    a.vcol = vcol;
+    {
+      const int64_t threads = (int64_t)nchunks * 2 * NT * 64;
+      const int64_t need = threads > (int64_t)nchunks * 32 ? threads : (int64_t)nchunks * 32;
+      hipLaunchKernelGGL(pack_v_kernel, dim3((unsigned)((need + 255) / 256)), dim3(256), 0, st, dV, ldv, ctx->n, nchunks, NT,
+                         a.col0, a.ncols, vcol, (const unsigned*)colmax, VP, VY);
+      GP_HIP(ctx, hipGetLastError());
+    }
+    vcol = -1;
+    tileh_fn fn = pick_h(ctx->kernel, ctx->KH, ctx->XP, NT, pl.MI);
+    if (!fn) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: no fp16 kernel for KH=%d", ctx->KH);
+    const bool prof = ctx->prof_on && ctx->prof_count < GP_PROF_MAX;
+    if (prof) GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count], st));
+    hipLaunchKernelGGL(fn, grid, block, 0, st, a);
+    GP_HIP(ctx, hipGetLastError());
+    if (prof) {
+      GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count + 1], st));
+      ++ctx->prof_count;
+    }
+    c += a.ncols;
+  }
+  if (split) {
+    const int64_t total = ctx->n * (int64_t)t;
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 4 * ctx->num_cu) blocks = 4 * ctx->num_cu;
+    hipLaunchKernelGGL(kmv_reduce_f16_kernel, dim3(blocks), dim3(256), 0, st, (const float*)part, a.split_stride, pl.JS,
+                       ctx->n, t, dOut, ldo);
+    GP_HIP(ctx, hipGetLastError());
+  }
+  return GP_OK;
+}

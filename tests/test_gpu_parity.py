@@ -78,6 +78,44 @@ def test_kmv_column_counts_and_leading_dimensions(t):
         dv.close()
 
 
+PATH_CASES = [("config1", dict(n=1500)), ("config2", dict(n=2100)), ("config4", dict(n=1100)), ("config5", dict(n=2500))]
+
+
+@pytest.mark.parametrize("path", ["fp32", "f16x2", "f16x3"])
+@pytest.mark.parametrize("name,kw", PATH_CASES)
+def test_kmv_every_product_path(monkeypatch, path, name, kw):
+    """The library picks the product path (fp32 MFMA, split-fp16 with 2 or 3 distance pieces) from
+    the largest scaled squared norm; GPWS_PATH pins it so that each path meets the same bar."""
+    monkeypatch.setenv("GPWS_PATH", path)
+    w = make(name, **kw)
+    dv = Dev(w.X, w.kind, w.ell, 0.9, 0.3)
+    try:
+        for V in (w.B, w.B * np.float32(1e-12), w.B * np.logspace(-8, 8, w.s + 1, dtype=np.float32)):
+            got = dv.kmv(V, 1)
+            ref = orc.kmv_dense(w.X, w.ell, 0.9, w.kind, V, sigma=0.3)
+            assert relerr(got, ref) <= KMV_TOL
+            # per column as well: the power-of-two column scaling must not favour large columns
+            cerr = np.linalg.norm(got - ref, axis=0) / np.linalg.norm(ref, axis=0)
+            assert cerr.max() <= KMV_TOL, cerr
+    finally:
+        dv.close()
+
+
+def test_kmv_path_selection_by_norm():
+    """Small lengthscales blow up |x/ell|^2: the automatic choice must still meet the bar
+    (three fp16 pieces, then the fp32 MFMA path beyond fp16's range)."""
+    w = make("config3", n=2000)
+    for scale, in ((1.0,), (0.08,), (0.004,)):
+        ell = w.ell * scale
+        dv = Dev(w.X, w.kind, ell, 1.0, 0.1)
+        try:
+            got = dv.kmv(w.B, 1)
+            ref = orc.kmv_dense(w.X, ell, 1.0, w.kind, w.B, sigma=0.1)
+            assert relerr(got, ref) <= KMV_TOL, scale
+        finally:
+            dv.close()
+
+
 def test_kmv_large_n_sampled_rows_and_properties():
     """n large enough for an unsplit launch with two sub-tiles per wave; the oracle computes exact
     rows for a seeded sample, plus properties that hold at any size."""
