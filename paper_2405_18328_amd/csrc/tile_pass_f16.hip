@@ -16,6 +16,8 @@
 // The accumulator layout of step 1 (lane = i, register r <-> j = 8(r/4) + 4(lane/32) + r%4) gives each lane
 // eight consecutive registers per k-step that are exactly its eight A-operand elements, provided the
 // V' rows are packed in that order; phi never leaves registers, K is never stored.
+#include <cstdlib>
+
 #include "gpws_internal.h"
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -62,13 +64,21 @@ __device__ __forceinline__ f16x8 as_f16x8(u32x4 v) { return __builtin_bit_cast(f
 
 template <int KIND, int KH, int XP, int NT, int MI>
 __global__ __launch_bounds__(GP_THREADS) void kmv_tile_f16_kernel(TileArgsH p) {
-  constexpr int XA_U = XP * KH * 64;                                  // 16-byte units of XA per chunk
-  constexpr int XA_LD = (XA_U + GP_THREADS - 1) / GP_THREADS;
-  constexpr int V_OFF = XA_LD * GP_THREADS;
-  constexpr int V_U = 2 * NT * 2 * 64;                                // = 256 NT
-  constexpr int VY_OFF = V_OFF + V_U;
-  constexpr int STAGE = VY_OFF + 8;
-  __shared__ u32x4 lds[2][STAGE];
+  // One pipeline stage in LDS, in 16-byte units: G groups of 64 units (one wave-wide 16-byte load
+  // each): XP*KH groups of XA pieces, then 4*NT groups of V' images; then one 8-unit y slot per wave.
+  constexpr int XA_G = XP * KH;
+  constexpr int V_G = 4 * NT;
+  constexpr int G = XA_G + V_G;
+  constexpr int V_OFF = XA_G * 64;
+  constexpr int V_U = V_G * 64;
+  constexpr int VY_OFF = G * 64;
+  constexpr int STAGE = VY_OFF + 8 * GP_WAVES;
+  constexpr int NS = G > 12 ? 3 : 4;               // stages: chunks up to ch + NS - 1 are in flight while ch is consumed
+  constexpr int DEPTH = NS - 1;
+  constexpr int LPW = (G + GP_WAVES - 1) / GP_WAVES;   // group loads per wave per chunk
+  constexpr int LPC = LPW + 1;                     // + the y slot
+  static_assert((DEPTH - 1) * LPC < 64, "vmcnt cannot express the pipeline depth");
+  __shared__ u32x4 lds[NS][STAGE];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -102,43 +112,54 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_f16_kernel(TileArgsH p) {
       for (int r = 0; r < 16; ++r) acc[m][nt][r] = 0.0f;
   }
 
-  // staging: straight 16-byte copies, unconditional (unit indices past the XA image are clamped
-  // for the load and land in the padding of the LDS region)
-  const u32x4* xa_src[XA_LD];
+  // Staging goes global -> LDS directly (global_load_lds_dwordx4: lane L of a wave lands at the
+  // wave's LDS base + 16 L), NS - 1 chunks ahead of the chunk being consumed, so no registers are held
+  // and the L2/HBM latency is spread over several chunks of work.  Every wave issues the same number of
+  // loads per chunk (its groups wave, wave + 4, ..; surplus slots repeat the last group, which rewrites
+  // identical bytes), so one vmcnt value tells each wave when its part of a chunk has landed; the
+  // barrier that follows makes the whole chunk visible.
+  const u32x4* g_src[LPW];
+  int g_stride[LPW], g_off[LPW];
 #pragma unroll
-  for (int x = 0; x < XA_LD; ++x) {
-    const int u = min(tid + x * GP_THREADS, XA_U - 1);
-    xa_src[x] = p.XA[u / (KH * 64)] + (u % (KH * 64));
+  for (int x = 0; x < LPW; ++x) {
+    const int g = min(wave + GP_WAVES * x, G - 1);
+    if (g < XA_G) {
+      g_src[x] = p.XA[g / KH] + (g % KH) * 64 + lane;
+      g_stride[x] = KH * 64;
+    } else {
+      g_src[x] = p.VP + (g - XA_G) * 64 + lane;
+      g_stride[x] = V_U;
+    }
+    g_off[x] = g * 64;
   }
-  u32x4 gxa[XA_LD], gv[NT], gvy;
-  gvy = u32x4{0, 0, 0, 0};
-  auto load_chunk = [&](int ch) {
+  // The loads are issued through inline assembly on purpose: the compiler's wait-count pass treats an
+  // LDS-DMA load as aliasing every later LDS read and would drain all chunks in flight (vmcnt(0)) at
+  // each barrier.  Here the ordering is explicit instead: s_waitcnt vmcnt(WAIT_N), then the barrier.
+  const bool vy_lane = lane < 8;
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) void*)&lds[0][0];
+  unsigned g_lds[LPW];
 #pragma unroll
-    for (int x = 0; x < XA_LD; ++x) gxa[x] = xa_src[x][(int64_t)ch * (KH * 64)];
-    const u32x4* vp = p.VP + (int64_t)ch * V_U;
-#pragma unroll
-    for (int x = 0; x < NT; ++x) gv[x] = vp[tid + x * GP_THREADS];
-    if (tid < 8) gvy = reinterpret_cast<const u32x4*>(p.VY + (int64_t)ch * 32)[tid];
+  for (int x = 0; x < LPW; ++x) g_lds[x] = __builtin_amdgcn_readfirstlane(lds_base + 16u * (unsigned)g_off[x]);
+  const unsigned vy_lds = __builtin_amdgcn_readfirstlane(lds_base + 16u * (unsigned)(VY_OFF + 8 * wave));
+  auto dma16 = [](const u32x4* src, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "memory", "m0");
   };
-  auto store_chunk = [&](int st) {
-    u32x4* s = lds[st];
+  auto issue_chunk = [&](int ch_target) {
+    const int ch = min(ch_target, c_end - 1);           // past the end: harmless reload of the last chunk
+    const unsigned stage_off = (unsigned)((ch_target - c_begin) % NS) * (unsigned)(STAGE * 16);
 #pragma unroll
-    for (int x = 0; x < XA_LD; ++x) s[tid + x * GP_THREADS] = gxa[x];
-#pragma unroll
-    for (int x = 0; x < NT; ++x) s[V_OFF + tid + x * GP_THREADS] = gv[x];
-    if (tid < 8) s[VY_OFF + tid] = gvy;
+    for (int x = 0; x < LPW; ++x) dma16(g_src[x] + (int64_t)ch * g_stride[x], g_lds[x] + stage_off);
+    if (vy_lane) dma16(reinterpret_cast<const u32x4*>(p.VY + (int64_t)ch * 32) + lane, vy_lds + stage_off);
   };
+  // vmcnt <= (DEPTH-1)*LPC: everything but the newest DEPTH-1 chunks has landed (loads retire in order)
+  constexpr int WAIT_N = (DEPTH - 1) * LPC;
 
-  load_chunk(c_begin);
-  store_chunk(0);
-  __syncthreads();
+#pragma unroll
+  for (int d0 = 0; d0 < DEPTH; ++d0) issue_chunk(c_begin + d0);
 
-  for (int ch = c_begin; ch < c_end; ++ch) {
-    const int st = (ch - c_begin) & 1;
-    if (ch + 1 < c_end) load_chunk(ch + 1);
-    const u32x4* s = lds[st];
-
-    f32x16 S[MI];
+  // distance chain of one chunk: S[j][i] = XA_j . XB_i, with the pair (i, i) forced to r^2 = 0
+  auto distance = [&](int ch, f32x16 (&S)[MI]) {
+    const u32x4* s = lds[(ch - c_begin) % NS];
 #pragma unroll
     for (int m = 0; m < MI; ++m)
 #pragma unroll
@@ -161,7 +182,6 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_f16_kernel(TileArgsH p) {
         S[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0], xb[m][0][kh], S[m], 0, 0, 0);
       }
     }
-    // the pair (i, i): r^2 is exactly zero
 #pragma unroll
     for (int m = 0; m < MI; ++m) {
       if (ch == sub0 + m) {
@@ -171,13 +191,29 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_f16_kernel(TileArgsH p) {
           if (8 * (r >> 2) + 4 * h + (r & 3) == li) S[m][r] = s0;
       }
     }
+  };
+
+  // The distance chain runs one chunk ahead of the phi/contraction stage, so the VALU never waits
+  // for it: while the VALU works through phi(S) of chunk ch, the matrix core already has S of ch + 1.
+  f32x16 S[MI];
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(WAIT_N) : "memory");
+  __syncthreads();
+  distance(c_begin, S);
+
+  for (int ch = c_begin; ch < c_end; ++ch) {
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(WAIT_N - LPC) : "memory");
+    __syncthreads();            // chunks <= ch + 1 are complete in LDS; every wave is done with chunk ch - 1
+    issue_chunk(ch + DEPTH);    // refills the stage chunk ch - 1 occupied
+    const u32x4* s = lds[(ch - c_begin) % NS];
+    f32x16 Sn[MI];
+    distance(ch + 1, Sn);       // past the last chunk this reads a harmless reload of it
 
 #pragma unroll
     for (int mh = 0; mh < 2; ++mh) {
       // this lane's y values for j = 16 mh + 8 g + 4 h + q
       f32x4 vy[2];
 #pragma unroll
-      for (int g = 0; g < 2; ++g) vy[g] = __builtin_bit_cast(f32x4, s[VY_OFF + 2 * (2 * mh + g) + h]);
+      for (int g = 0; g < 2; ++g) vy[g] = __builtin_bit_cast(f32x4, s[VY_OFF + 8 * wave + 2 * (2 * mh + g) + h]);
       f16x8 bh[NT], bl[NT];
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
@@ -217,10 +253,12 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_f16_kernel(TileArgsH p) {
         }
       }
     }
-    if (ch + 1 < c_end) store_chunk(st ^ 1);
-    __syncthreads();
+#pragma unroll
+    for (int m = 0; m < MI; ++m) S[m] = Sn[m];
   }
 
+  // no LDS write of this workgroup may still be in flight when its LDS is released
+  asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
   // epilogue: undo the power-of-two scalings, multiply by a^2, add the noise term once, store
   float* out = p.OUT + (int64_t)js * p.split_stride;
   const bool noise = p.add_noise && js == 0;
@@ -397,6 +435,7 @@ KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx) {
   KmvPlan pl;
   const int64_t chunks = (ctx->n + 31) / 32;
   pl.MI = (ctx->KH <= 2 && ctx->n >= 8192) ? 2 : 1;
+  if (const char* e = getenv("GPWS_MI")) pl.MI = (atoi(e) == 2 && ctx->KH <= 2) ? 2 : 1;   // tuning aid
   const int rows_per_wg = 32 * GP_WAVES * pl.MI;
   pl.row_blocks = (int)((ctx->n + rows_per_wg - 1) / rows_per_wg);
   const int target = 2 * ctx->num_cu;
