@@ -25,7 +25,7 @@ GP_ERR_BREAKDOWN = -4
 GP_MAX_D = 126
 GP_MAX_T = 1024
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgpws.so")
+LIB_PATH = os.environ.get("GPWS_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgpws.so")
 
 EXPORTS = ["gp_create", "gp_destroy", "gp_set_theta", "gp_kmv", "gp_workspace_bytes", "gp_cg_solve",
            "gp_mll_grad", "gp_profile", "gp_profile_read", "gp_last_error"]

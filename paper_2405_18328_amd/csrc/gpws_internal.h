@@ -16,7 +16,7 @@
 constexpr int GP_CHUNK = 32;          // rows per packed operand chunk
 constexpr int GP_WAVES = 4;           // wavefronts per workgroup
 constexpr int GP_THREADS = 64 * GP_WAVES;
-constexpr int GP_ROW_ALIGN = 256;     // packed operand arrays are padded to this many rows
+constexpr int GP_ROW_ALIGN = 512;     // packed operand arrays are padded to this many rows
 constexpr int GP_VEC_PAD = 4;         // solver arrays are padded to a multiple of 4 rows (float4 streams)
 constexpr float GP_PAD_NORM = 1.0e30f; // squared norm given to padding rows of XA (phi underflows to 0)
 constexpr int GP_PACK_SLACK = 256;    // floats allocated past the packed arrays: staging loads overrun by < 256
@@ -96,6 +96,7 @@ int gp_launch_pack(gp_ctx* ctx);
 // ---- tile_pass.hip
 struct KmvPlan {
   int MI;        // 32-row sub-tiles per wave
+  int W;         // wavefronts per workgroup (fp16 path; the fp32 path always uses GP_WAVES)
   int JS;        // column-range splits
   int row_blocks;
   int cps;       // chunks per split

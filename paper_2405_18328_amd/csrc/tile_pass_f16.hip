@@ -62,8 +62,10 @@ struct TileArgsH {
 
 __device__ __forceinline__ f16x8 as_f16x8(u32x4 v) { return __builtin_bit_cast(f16x8, v); }
 
-template <int KIND, int KH, int XP, int NT, int MI>
-__global__ __launch_bounds__(GP_THREADS) void kmv_tile_f16_kernel(TileArgsH p) {
+// W wavefronts per workgroup: every workgroup streams all of V' and XA through its LDS, so the
+// L2-to-LDS traffic of a launch is inversely proportional to the rows a workgroup owns (32 MI W).
+template <int KIND, int KH, int XP, int NT, int MI, int W>
+__global__ __launch_bounds__(64 * W) void kmv_tile_f16_kernel(TileArgsH p) {
   // One pipeline stage in LDS, in 16-byte units: G groups of 64 units (one wave-wide 16-byte load
   // each): XP*KH groups of XA pieces, then 4*NT groups of V' images; then one 8-unit y slot per wave.
   constexpr int XA_G = XP * KH;
@@ -72,10 +74,10 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_f16_kernel(TileArgsH p) {
   constexpr int V_OFF = XA_G * 64;
   constexpr int V_U = V_G * 64;
   constexpr int VY_OFF = G * 64;
-  constexpr int STAGE = VY_OFF + 8 * GP_WAVES;
+  constexpr int STAGE = VY_OFF + 8 * W;
   constexpr int NS = G > 12 ? 3 : 4;               // stages: chunks up to ch + NS - 1 are in flight while ch is consumed
   constexpr int DEPTH = NS - 1;
-  constexpr int LPW = (G + GP_WAVES - 1) / GP_WAVES;   // group loads per wave per chunk
+  constexpr int LPW = (G + W - 1) / W;             // group loads per wave per chunk
   constexpr int LPC = LPW + 1;                     // + the y slot
   static_assert((DEPTH - 1) * LPC < 64, "vmcnt cannot express the pipeline depth");
   __shared__ u32x4 lds[NS][STAGE];
@@ -87,7 +89,7 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_f16_kernel(TileArgsH p) {
   const int li = lane & 31;
   const int js = blockIdx.x % p.JS;
   const int rb = blockIdx.x / p.JS;
-  const int sub0 = (rb * GP_WAVES + wave) * MI;
+  const int sub0 = (rb * W + wave) * MI;
   const int c_begin = js * p.cps;
   const int c_end = min(p.nchunks, c_begin + p.cps);
 
@@ -115,14 +117,14 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_f16_kernel(TileArgsH p) {
   // Staging goes global -> LDS directly (global_load_lds_dwordx4: lane L of a wave lands at the
   // wave's LDS base + 16 L), NS - 1 chunks ahead of the chunk being consumed, so no registers are held
   // and the L2/HBM latency is spread over several chunks of work.  Every wave issues the same number of
-  // loads per chunk (its groups wave, wave + 4, ..; surplus slots repeat the last group, which rewrites
+  // loads per chunk (its groups wave, wave + W, ..; surplus slots repeat the last group, which rewrites
   // identical bytes), so one vmcnt value tells each wave when its part of a chunk has landed; the
   // barrier that follows makes the whole chunk visible.
   const u32x4* g_src[LPW];
   int g_stride[LPW], g_off[LPW];
 #pragma unroll
   for (int x = 0; x < LPW; ++x) {
-    const int g = min(wave + GP_WAVES * x, G - 1);
+    const int g = min(wave + W * x, G - 1);
     if (g < XA_G) {
       g_src[x] = p.XA[g / KH] + (g % KH) * 64 + lane;
       g_stride[x] = KH * 64;
@@ -142,7 +144,9 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_f16_kernel(TileArgsH p) {
   for (int x = 0; x < LPW; ++x) g_lds[x] = __builtin_amdgcn_readfirstlane(lds_base + 16u * (unsigned)g_off[x]);
   const unsigned vy_lds = __builtin_amdgcn_readfirstlane(lds_base + 16u * (unsigned)(VY_OFF + 8 * wave));
   auto dma16 = [](const u32x4* src, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "memory", "m0");
+    unsigned saved_m0;   // m0 is restored, so the compiler's own uses of it are undisturbed
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0) : "v"(src), "s"(lds_addr) : "memory");
   };
   auto issue_chunk = [&](int ch_target) {
     const int ch = min(ch_target, c_end - 1);           // past the end: harmless reload of the last chunk
@@ -193,68 +197,115 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_f16_kernel(TileArgsH p) {
     }
   };
 
-  // The distance chain runs one chunk ahead of the phi/contraction stage, so the VALU never waits
-  // for it: while the VALU works through phi(S) of chunk ch, the matrix core already has S of ch + 1.
-  f32x16 S[MI];
+  // ---- main loop ---------------------------------------------------------------------------------
+  // A chunk is worked through in NG = 2 MI groups of 8 values per lane (group g = (mh, m): the k-step
+  // mh of sub-tile m).  Two software pipelines keep the matrix core and the VALU busy together:
+  //   * the distance chain runs one chunk ahead (S of chunk ch + 1 while chunk ch is consumed);
+  //   * the phi/split stage runs one group ahead of the contraction, and the two are emitted as
+  //     bundles "one MFMA, then the VALU work of one value pair".  The matrix pipe accepts an MFMA only
+  //     when it is free; a wave that reaches its next MFMA early stalls there with its VALU work
+  //     undone, so MFMAs are spaced by at least their own duration of VALU instructions.
+  constexpr int NG = 2 * MI;
+  constexpr int MPG = 3 * NT;        // contraction MFMAs per group
+
+  // phi and its split for values 2 e2, 2 e2 + 1 of group (mh, m); vy = the lane's y values for that mh
+  auto phi_pair = [&](const f32x16& Sv, int mh, int e2, const f32x4 (&vy)[2], float& av, unsigned& oh, unsigned& ol) {
+    float f[2], fh[2], fl[2];
+#pragma unroll
+    for (int z = 0; z < 2; ++z) {
+      const int e = 2 * e2 + z;
+      const float sv = Sv[8 * mh + e];
+      if (KIND == GP_SE_ARD) {
+        f[z] = __builtin_amdgcn_exp2f(sv);                 // sv = -log2(e)/2 r^2 + 15
+      } else {
+        const float u = __builtin_amdgcn_sqrtf(fmaxf(sv, 0.0f));        // sv = 3 r^2
+        const float ex = __builtin_amdgcn_exp2f(fmaf(u, -LOG2E, (float)PHI_SHIFT));
+        f[z] = fmaf(u, ex, ex);
+      }
+      av = fmaf(f[z], vy[e >> 2][e & 3], av);
+      fh[z] = __uint_as_float(__float_as_uint(f[z]) & HI_MASK);
+      fl[z] = f[z] - fh[z];
+    }
+    oh = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(fh[0], fh[1]));
+    ol = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(fl[0], fl[1]));
+  };
+  auto load_vy = [&](const u32x4* s, int mh, f32x4 (&vy)[2]) {
+#pragma unroll
+    for (int g2 = 0; g2 < 2; ++g2) vy[g2] = __builtin_bit_cast(f32x4, s[VY_OFF + 8 * wave + 2 * (2 * mh + g2) + h]);
+  };
+
+  f32x16 S0[MI], S1[MI];             // S of the chunk being consumed / of the next chunk, roles alternate
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(WAIT_N) : "memory");
   __syncthreads();
-  distance(c_begin, S);
+  distance(c_begin, S0);
+  unsigned ph[4], pl[4];             // packed A operands of the group about to be contracted
+  f32x4 vy0[2];                      // y values of k-step 0 of the chunk being consumed
+  load_vy(lds[0], 0, vy0);
+#pragma unroll
+  for (int e2 = 0; e2 < 4; ++e2) phi_pair(S0[0], 0, e2, vy0, accv[0], ph[e2], pl[e2]);
 
-  for (int ch = c_begin; ch < c_end; ++ch) {
+  // one chunk: S = its distances (ready), Sn = receives the next chunk's
+  auto chunk_body = [&](int ch, f32x16 (&S)[MI], f32x16 (&Sn)[MI]) {
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(WAIT_N - LPC) : "memory");
     __syncthreads();            // chunks <= ch + 1 are complete in LDS; every wave is done with chunk ch - 1
     issue_chunk(ch + DEPTH);    // refills the stage chunk ch - 1 occupied
     const u32x4* s = lds[(ch - c_begin) % NS];
-    f32x16 Sn[MI];
+    const u32x4* s_next = lds[(ch + 1 - c_begin) % NS];
+    // every LDS operand of the chunk is fetched here, ahead of the distance chain, so that no MFMA or
+    // VALU instruction further down waits on LDS latency
+    f16x8 bh[2][NT], bl[2][NT];
+#pragma unroll
+    for (int mh = 0; mh < 2; ++mh)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        bh[mh][nt] = as_f16x8(s[V_OFF + ((mh * NT + nt) * 2 + 0) * 64 + lane]);
+        bl[mh][nt] = as_f16x8(s[V_OFF + ((mh * NT + nt) * 2 + 1) * 64 + lane]);
+      }
+    f32x4 vy1[2], vy0n[2];
+    load_vy(s, 1, vy1);
+    load_vy(s_next, 0, vy0n);
+    {   // past the last chunk the look-ahead group must not reach the y accumulator
+      const float keep = ch + 1 < c_end ? 1.0f : 0.0f;
+      vy0n[0] *= keep;
+      vy0n[1] *= keep;
+    }
     distance(ch + 1, Sn);       // past the last chunk this reads a harmless reload of it
 
 #pragma unroll
-    for (int mh = 0; mh < 2; ++mh) {
-      // this lane's y values for j = 16 mh + 8 g + 4 h + q
-      f32x4 vy[2];
+    for (int g = 0; g < NG; ++g) {
+      const int mh = g / MI, m = g % MI;
+      // the group whose phi stage rides along: g + 1 of this chunk, or group 0 of the next chunk
+      const bool wrap = g + 1 == NG;
+      const int gn = wrap ? 0 : g + 1;
+      const int mhn = gn / MI, mn = gn % MI;
+      const f32x4 (&vyn)[2] = wrap ? vy0n : (mhn == 0 ? vy0 : vy1);
+      const f16x8 ah = as_f16x8(u32x4{ph[0], ph[1], ph[2], ph[3]}), al = as_f16x8(u32x4{pl[0], pl[1], pl[2], pl[3]});
+      unsigned nh[4], nl[4];
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int g = 0; g < 2; ++g) vy[g] = __builtin_bit_cast(f32x4, s[VY_OFF + 8 * wave + 2 * (2 * mh + g) + h]);
-      f16x8 bh[NT], bl[NT];
+      for (int k = 0; k < MPG; ++k) {
+        const int nt = k / 3, term = k % 3;      // smallest terms first: lo*hi, hi*lo, hi*hi
+        acc[m][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(term == 0 ? al : ah, term == 1 ? bl[mh][nt] : bh[mh][nt],
+                                                            acc[m][nt], 0, 0, 0);
+        // the 4 value pairs of the next group, spread over the MPG bundles
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        bh[nt] = as_f16x8(s[V_OFF + ((mh * NT + nt) * 2 + 0) * 64 + lane]);
-        bl[nt] = as_f16x8(s[V_OFF + ((mh * NT + nt) * 2 + 1) * 64 + lane]);
+        for (int e2 = 0; e2 < 4; ++e2)
+          if ((e2 * MPG) / 4 == k) phi_pair(wrap ? Sn[mn] : S[mn], mhn, e2, vyn, accv[mn], nh[e2], nl[e2]);
+        __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
-      for (int m = 0; m < MI; ++m) {
-        u32x4 ph, pl;
-#pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) {
-          float f[2], fh[2], fl[2];
-#pragma unroll
-          for (int z = 0; z < 2; ++z) {
-            const int e = 2 * e2 + z;
-            const float sv = S[m][8 * mh + e];
-            if (KIND == GP_SE_ARD) {
-              f[z] = __builtin_amdgcn_exp2f(sv);                 // sv = -log2(e)/2 r^2 + 15
-            } else {
-              const float u = __builtin_amdgcn_sqrtf(fmaxf(sv, 0.0f));        // sv = 3 r^2
-              const float ex = __builtin_amdgcn_exp2f(fmaf(u, -LOG2E, (float)PHI_SHIFT));
-              f[z] = fmaf(u, ex, ex);
-            }
-            accv[m] = fmaf(f[z], vy[e >> 2][e & 3], accv[m]);
-            fh[z] = __uint_as_float(__float_as_uint(f[z]) & HI_MASK);
-            fl[z] = f[z] - fh[z];
-          }
-          ph[e2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(fh[0], fh[1]));
-          pl[e2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(fl[0], fl[1]));
-        }
-        const f16x8 ah = as_f16x8(ph), al = as_f16x8(pl);
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          acc[m][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, bh[nt], acc[m][nt], 0, 0, 0);
-          acc[m][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bl[nt], acc[m][nt], 0, 0, 0);
-          acc[m][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bh[nt], acc[m][nt], 0, 0, 0);
-        }
+      for (int e2 = 0; e2 < 4; ++e2) {
+        ph[e2] = nh[e2];
+        pl[e2] = nl[e2];
       }
     }
-#pragma unroll
-    for (int m = 0; m < MI; ++m) S[m] = Sn[m];
+    vy0[0] = vy0n[0];
+    vy0[1] = vy0n[1];
+  };
+
+  for (int ch = c_begin; ch < c_end; ch += 2) {
+    chunk_body(ch, S0, S1);
+    if (ch + 1 < c_end) chunk_body(ch + 1, S1, S0);
   }
 
   // no LDS write of this workgroup may still be in flight when its LDS is released
@@ -375,29 +426,31 @@ __global__ void kmv_reduce_f16_kernel(const float* __restrict__ part, int64_t sp
 typedef void (*tileh_fn)(TileArgsH);
 
 template <int KIND, int KH, int XP>
-tileh_fn pick_h_nt_mi(int NT, int MI) {
+tileh_fn pick_h_nt_mi(int NT, int MI, int W) {
   if constexpr (KH <= 2) {
-    if (MI == 2) return NT == 1 ? kmv_tile_f16_kernel<KIND, KH, XP, 1, 2> : kmv_tile_f16_kernel<KIND, KH, XP, 2, 2>;
+    if (MI == 2 && W == 8) return NT == 1 ? kmv_tile_f16_kernel<KIND, KH, XP, 1, 2, 8> : kmv_tile_f16_kernel<KIND, KH, XP, 2, 2, 8>;
+    if (MI == 2) return NT == 1 ? kmv_tile_f16_kernel<KIND, KH, XP, 1, 2, 4> : kmv_tile_f16_kernel<KIND, KH, XP, 2, 2, 4>;
   }
-  return NT == 1 ? kmv_tile_f16_kernel<KIND, KH, XP, 1, 1> : kmv_tile_f16_kernel<KIND, KH, XP, 2, 1>;
+  if (W == 8) return NT == 1 ? kmv_tile_f16_kernel<KIND, KH, XP, 1, 1, 8> : kmv_tile_f16_kernel<KIND, KH, XP, 2, 1, 8>;
+  return NT == 1 ? kmv_tile_f16_kernel<KIND, KH, XP, 1, 1, 4> : kmv_tile_f16_kernel<KIND, KH, XP, 2, 1, 4>;
 }
 
 template <int KIND, int XP>
-tileh_fn pick_h_kh(int KH, int NT, int MI) {
+tileh_fn pick_h_kh(int KH, int NT, int MI, int W) {
   switch (KH) {
-    case 1: return pick_h_nt_mi<KIND, 1, XP>(NT, MI);
-    case 2: return pick_h_nt_mi<KIND, 2, XP>(NT, MI);
-    case 3: return pick_h_nt_mi<KIND, 3, XP>(NT, MI);
-    case 4: return pick_h_nt_mi<KIND, 4, XP>(NT, MI);
-    case 6: return pick_h_nt_mi<KIND, 6, XP>(NT, MI);
-    case 8: return pick_h_nt_mi<KIND, 8, XP>(NT, MI);
+    case 1: return pick_h_nt_mi<KIND, 1, XP>(NT, MI, W);
+    case 2: return pick_h_nt_mi<KIND, 2, XP>(NT, MI, W);
+    case 3: return pick_h_nt_mi<KIND, 3, XP>(NT, MI, W);
+    case 4: return pick_h_nt_mi<KIND, 4, XP>(NT, MI, W);
+    case 6: return pick_h_nt_mi<KIND, 6, XP>(NT, MI, W);
+    case 8: return pick_h_nt_mi<KIND, 8, XP>(NT, MI, W);
   }
   return nullptr;
 }
 
-tileh_fn pick_h(int kind, int KH, int XP, int NT, int MI) {
-  if (kind == GP_SE_ARD) return XP == 2 ? pick_h_kh<GP_SE_ARD, 2>(KH, NT, MI) : pick_h_kh<GP_SE_ARD, 3>(KH, NT, MI);
-  return XP == 2 ? pick_h_kh<GP_MATERN32_ARD, 2>(KH, NT, MI) : pick_h_kh<GP_MATERN32_ARD, 3>(KH, NT, MI);
+tileh_fn pick_h(int kind, int KH, int XP, int NT, int MI, int W) {
+  if (kind == GP_SE_ARD) return XP == 2 ? pick_h_kh<GP_SE_ARD, 2>(KH, NT, MI, W) : pick_h_kh<GP_SE_ARD, 3>(KH, NT, MI, W);
+  return XP == 2 ? pick_h_kh<GP_MATERN32_ARD, 2>(KH, NT, MI, W) : pick_h_kh<GP_MATERN32_ARD, 3>(KH, NT, MI, W);
 }
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -434,9 +487,13 @@ int gp_kh_bucket(int d, int kernel) {
 KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx) {
   KmvPlan pl;
   const int64_t chunks = (ctx->n + 31) / 32;
-  pl.MI = (ctx->KH <= 2 && ctx->n >= 8192) ? 2 : 1;
+  // two sub-tiles per wave halve the LDS operand traffic; past one k-step of distance operands the
+  // second sub-tile no longer fits the register file without spills
+  pl.MI = (ctx->KH == 1 && ctx->n >= 8192) ? 2 : 1;
   if (const char* e = getenv("GPWS_MI")) pl.MI = (atoi(e) == 2 && ctx->KH <= 2) ? 2 : 1;   // tuning aid
-  const int rows_per_wg = 32 * GP_WAVES * pl.MI;
+  pl.W = 4;   // 8-wave workgroups halve the L2-to-LDS traffic but measured no faster on MI355X
+  if (const char* e = getenv("GPWS_W")) pl.W = atoi(e) == 8 ? 8 : 4;                            // tuning aid
+  const int rows_per_wg = 32 * pl.W * pl.MI;
   pl.row_blocks = (int)((ctx->n + rows_per_wg - 1) / rows_per_wg);
   const int target = 2 * ctx->num_cu;
   int JS = 1;
@@ -502,7 +559,7 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
 
   int vcol = (t > 1 && t % 32 == 1) ? 0 : -1;
   int c = vcol >= 0 ? 1 : 0;
-  const dim3 grid(pl.row_blocks * pl.JS), block(GP_THREADS);
+  const dim3 grid(pl.row_blocks * pl.JS), block(64 * pl.W);
   while (c < t) {
     const int rem = t - c;
     const int NT = rem > 32 ? 2 : 1;
@@ -517,7 +574,7 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
       GP_HIP(ctx, hipGetLastError());
     }
     vcol = -1;
-    tileh_fn fn = pick_h(ctx->kernel, ctx->KH, ctx->XP, NT, pl.MI);
+    tileh_fn fn = pick_h(ctx->kernel, ctx->KH, ctx->XP, NT, pl.MI, pl.W);
     if (!fn) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: no fp16 kernel for KH=%d", ctx->KH);
     const bool prof = ctx->prof_on && ctx->prof_count < GP_PROF_MAX;
     if (prof) GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count], st));
