@@ -39,6 +39,7 @@ struct CgDev {
   float* relres;    // [t]
   int* frozen;      // [t]
   int* zero_rhs;    // [t]
+  unsigned* colmax; // [t] bit patterns of max |P_ic|, kept current for the split-fp16 product
   double* part;     // [G][t] workgroup partials
   double* part2;    // [G][t] second set (init only)
 };
@@ -60,6 +61,19 @@ __device__ __forceinline__ void block_column_sums(const float v[4], int t, int b
     for (int p = p0; p < VW; p += t) s += (double)sh[p];
     out[c] = s;
   }
+}
+
+// colmax[c] = max(colmax[c], max over this workgroup's elements of |.|) for the thread's four columns;
+// non-negative floats order like unsigned ints, and max does not depend on the order of the updates
+__device__ __forceinline__ void block_column_max(const float m[4], const int c[4], int t, unsigned* colmax,
+                                                 unsigned* smax /* [t] */) {
+  for (int k = threadIdx.x; k < t; k += VT) smax[k] = 0u;
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < 4; ++q) atomicMax(&smax[c[q]], __float_as_uint(m[q]));
+  __syncthreads();
+  for (int k = threadIdx.x; k < t; k += VT)
+    if (smax[k]) atomicMax(&colmax[k], smax[k]);
 }
 
 __device__ __forceinline__ void thread_columns(int t, int64_t e0, int c[4]) {
@@ -101,11 +115,15 @@ __global__ __launch_bounds__(VT) void cg_load_kernel(const float* __restrict__ B
 // R <- R - HX (warm start: initial residual), then (both cases) P <- R, partial r^T r
 __global__ __launch_bounds__(VT) void cg_resid_kernel(float* __restrict__ R, const float* __restrict__ HX,
                                                       int subtract, float* __restrict__ P, int64_t total, int t,
-                                                      double* __restrict__ part) {
+                                                      double* __restrict__ part, unsigned* __restrict__ colmax) {
   __shared__ float sh[VW];
+  __shared__ unsigned smax[GP_MAX_T];
+  const int64_t e0 = ((int64_t)blockIdx.x * VT + threadIdx.x) * 4;
   const int64_t stride = (int64_t)gridDim.x * VW;
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int64_t e = ((int64_t)blockIdx.x * VT + threadIdx.x) * 4; e < total; e += stride) {
+  int c[4];
+  thread_columns(t, e0, c);
+  float acc[4] = {0.f, 0.f, 0.f, 0.f}, mx[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int64_t e = e0; e < total; e += stride) {
     f32x4 r = *reinterpret_cast<const f32x4*>(R + e);
     if (subtract) {
       const f32x4 hx = *reinterpret_cast<const f32x4*>(HX + e);
@@ -114,9 +132,13 @@ __global__ __launch_bounds__(VT) void cg_resid_kernel(float* __restrict__ R, con
     }
     *reinterpret_cast<f32x4*>(P + e) = r;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) acc[q] = fmaf(r[q], r[q], acc[q]);
+    for (int q = 0; q < 4; ++q) {
+      acc[q] = fmaf(r[q], r[q], acc[q]);
+      mx[q] = fmaxf(mx[q], fabsf(r[q]));
+    }
   }
   block_column_sums(acc, t, (int)(((int64_t)blockIdx.x * VW) % t), part + (int64_t)blockIdx.x * t, sh);
+  block_column_max(mx, c, t, colmax, smax);   // max |P| per column for the product that follows
 }
 
 // partial p^T (H p)
@@ -173,22 +195,28 @@ __global__ __launch_bounds__(VT) void cg_update_xr_kernel(float* __restrict__ X,
 // p = r + beta p
 __global__ __launch_bounds__(VT) void cg_update_p_kernel(float* __restrict__ P, const float* __restrict__ R,
                                                          int64_t total, int t, const float* __restrict__ beta,
-                                                         const CgFlags* __restrict__ flags) {
+                                                         const CgFlags* __restrict__ flags,
+                                                         unsigned* __restrict__ colmax) {
+  __shared__ unsigned smax[GP_MAX_T];
   if (flags->all_done) return;
   const int64_t e0 = ((int64_t)blockIdx.x * VT + threadIdx.x) * 4;
   const int64_t stride = (int64_t)gridDim.x * VW;
   int c[4];
   thread_columns(t, e0, c);
-  float be[4];
+  float be[4], mx[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int q = 0; q < 4; ++q) be[q] = beta[c[q]];
   for (int64_t e = e0; e < total; e += stride) {
     const f32x4 r = *reinterpret_cast<const f32x4*>(R + e);
     f32x4 p = *reinterpret_cast<const f32x4*>(P + e);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) p[q] = fmaf(be[q], p[q], r[q]);
+    for (int q = 0; q < 4; ++q) {
+      p[q] = fmaf(be[q], p[q], r[q]);
+      mx[q] = fmaxf(mx[q], fabsf(p[q]));
+    }
     *reinterpret_cast<f32x4*>(P + e) = p;
   }
+  block_column_max(mx, c, t, colmax, smax);   // max |P| per column for the next product (zeroed by the beta finalise)
 }
 
 // dV <- X (columns whose right-hand side is zero get 0)
@@ -209,9 +237,19 @@ __device__ __forceinline__ double finalize_sum(const double* part, int G, int t,
   const int tid = threadIdx.x;
   const int nparts = FT / t > 0 ? FT / t : 1;
   const int c = tid % t, pt = tid / t;
-  double s = 0.0;
-  if (pt < nparts)
-    for (int g = pt; g < G; g += nparts) s += part[(int64_t)g * t + c];
+  // four independent partial sums keep several loads in flight (the order stays fixed)
+  double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+  if (pt < nparts) {
+    int g = pt;
+    for (; g + 3 * nparts < G; g += 4 * nparts) {
+      s0 += part[(int64_t)g * t + c];
+      s1 += part[(int64_t)(g + nparts) * t + c];
+      s2 += part[(int64_t)(g + 2 * nparts) * t + c];
+      s3 += part[(int64_t)(g + 3 * nparts) * t + c];
+    }
+    for (; g < G; g += nparts) s0 += part[(int64_t)g * t + c];
+  }
+  const double s = (s0 + s1) + (s2 + s3);
   __syncthreads();
   sh[tid] = s;
   __syncthreads();
@@ -289,6 +327,7 @@ __global__ __launch_bounds__(FT) void cg_fin_beta_kernel(CgDev s, int G, int t) 
       s.frozen[c] = fr;
     }
     s.beta[c] = be;
+    s.colmax[c] = 0u;          // the p update that follows accumulates the new column maxima
     if (!fr) atomicAdd(&live_count, 1);
   }
   __syncthreads();
@@ -310,15 +349,21 @@ struct CgLayout {
 CgLayout cg_layout(const gp_ctx* ctx, int t) {
   CgLayout L;
   L.n4 = (ctx->n + GP_VEC_PAD - 1) / GP_VEC_PAD * GP_VEC_PAD;
-  const int per = (2 * ctx->num_cu + t - 1) / t;
-  L.G = t * (per > 0 ? per : 1);
+  // grid of the streaming kernels: a multiple of t workgroups, enough to fill the chip on large
+  // problems, fewer on small ones (about 8 float4 per thread) so the finalise kernels sum fewer partials
+  const int64_t total4 = L.n4 * (int64_t)t / 4;
+  int64_t per = (total4 + (int64_t)VT * 8 * t - 1) / ((int64_t)VT * 8 * t);
+  const int per_max = (2 * ctx->num_cu + t - 1) / t;
+  if (per > per_max) per = per_max;
+  if (per < 1) per = 1;
+  L.G = t * (int)per;
   const size_t arr = align_up((size_t)L.n4 * t * sizeof(float), 256);
   size_t o = 0;
   L.off_X = o; o += arr;
   L.off_R = o; o += arr;
   L.off_P = o; o += arr;
   L.off_HP = o; o += arr;
-  L.off_state = o; o += align_up(sizeof(CgFlags) + (size_t)t * (2 * sizeof(double) + 4 * sizeof(float) + 2 * sizeof(int)) + 256, 256);
+  L.off_state = o; o += align_up(sizeof(CgFlags) + (size_t)t * (2 * sizeof(double) + 4 * sizeof(float) + 3 * sizeof(int)) + 256, 256);
   L.off_part = o; o += align_up((size_t)L.G * t * sizeof(double), 256);
   L.off_part2 = o; o += align_up((size_t)L.G * t * sizeof(double), 256);
   L.off_kmv = o;
@@ -356,6 +401,7 @@ int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     s.relres = (float*)q; q += sizeof(float) * t;
     s.frozen = (int*)q; q += sizeof(int) * t;
     s.zero_rhs = (int*)q; q += sizeof(int) * t;
+    s.colmax = (unsigned*)q; q += sizeof(unsigned) * t;
   }
   s.part = (double*)(w + L.off_part);
   s.part2 = (double*)(w + L.off_part2);
@@ -378,11 +424,12 @@ int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
   hipLaunchKernelGGL(cg_load_kernel, grid, block, 0, st, dB, ldb, dX0, ldv, ctx->n, L.n4, t, X, R, s.part2);
   GP_HIP(ctx, hipGetLastError());
   if (dX0) {
-    int rc = gp_kmv_launch(ctx, X, t, t, HP, t, 1, kmv_scratch, L.kmv_bytes);
+    int rc = gp_kmv_launch(ctx, X, t, t, HP, t, 1, kmv_scratch, L.kmv_bytes, nullptr);
     if (rc < 0) return rc;
     ++kmv_count;
   }
-  hipLaunchKernelGGL(cg_resid_kernel, grid, block, 0, st, R, (const float*)HP, dX0 ? 1 : 0, P, total, t, s.part);
+  GP_HIP(ctx, hipMemsetAsync(s.colmax, 0, sizeof(unsigned) * t, st));
+  hipLaunchKernelGGL(cg_resid_kernel, grid, block, 0, st, R, (const float*)HP, dX0 ? 1 : 0, P, total, t, s.part, s.colmax);
   hipLaunchKernelGGL(cg_fin_init_kernel, dim3(1), dim3(FT), 0, st, s, L.G, t, 1);
   GP_HIP(ctx, hipGetLastError());
   GP_HIP(ctx, hipMemcpyAsync(hflags, s.flags, sizeof(CgFlags), hipMemcpyDeviceToHost, st));
@@ -390,7 +437,7 @@ int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
 
   int it = 0;
   while (!hflags->all_done && it < max_iters) {
-    int rc = gp_kmv_launch(ctx, P, t, t, HP, t, 1, kmv_scratch, L.kmv_bytes);
+    int rc = gp_kmv_launch(ctx, P, t, t, HP, t, 1, kmv_scratch, L.kmv_bytes, s.colmax);
     if (rc < 0) return rc;
     ++kmv_count;
     hipLaunchKernelGGL(cg_dot_kernel, grid, block, 0, st, (const float*)P, (const float*)HP, total, t, s.flags, s.part);
@@ -398,7 +445,7 @@ int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     hipLaunchKernelGGL(cg_update_xr_kernel, grid, block, 0, st, X, R, (const float*)P, (const float*)HP, total, t,
                        (const float*)s.alpha, s.flags, s.part);
     hipLaunchKernelGGL(cg_fin_beta_kernel, dim3(1), dim3(FT), 0, st, s, L.G, t);
-    hipLaunchKernelGGL(cg_update_p_kernel, grid, block, 0, st, P, (const float*)R, total, t, (const float*)s.beta, s.flags);
+    hipLaunchKernelGGL(cg_update_p_kernel, grid, block, 0, st, P, (const float*)R, total, t, (const float*)s.beta, s.flags, s.colmax);
     GP_HIP(ctx, hipGetLastError());
     GP_HIP(ctx, hipMemcpyAsync(hflags, s.flags, sizeof(CgFlags), hipMemcpyDeviceToHost, st));
     GP_HIP(ctx, hipStreamSynchronize(st));

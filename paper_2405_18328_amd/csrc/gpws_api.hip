@@ -172,7 +172,7 @@ int gp_kmv(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_
   if ((const float*)dOut == dV) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: dOut must not alias dV");
   const size_t need = gp_kmv_scratch_bytes(ctx, t);
   if ((rc = gp_ensure_scratch(ctx, need)) < 0) return rc;
-  return gp_kmv_launch(ctx, dV, ldv, t, dOut, ldo, add_noise ? 1 : 0, ctx->dScratch, ctx->scratch_bytes);
+  return gp_kmv_launch(ctx, dV, ldv, t, dOut, ldo, add_noise ? 1 : 0, ctx->dScratch, ctx->scratch_bytes, nullptr);
 }
 
 size_t gp_workspace_bytes(const gp_ctx* ctx, int t) {

@@ -103,16 +103,17 @@ struct KmvPlan {
 };
 KmvPlan gp_plan_kmv(const gp_ctx* ctx);
 size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t);   // worst case over the paths gp_set_theta may choose
-// OUT = K V (+ sigma^2 V).  scratch is used only when the plan splits the column range.
+// OUT = K V (+ sigma^2 V).  colmax: optional device array of t bit patterns of max_i |V_ic| that the
+// caller already holds (the split-fp16 path then skips its own reduction over V); NULL otherwise.
 int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
-                  int add_noise, void* scratch, size_t scratch_bytes);
+                  int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax);
 
 // ---- tile_pass_f16.hip
 int gp_kh_bucket(int d, int kernel);
 KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx);
 size_t gp_kmv_f16_scratch_bytes(const gp_ctx* ctx, int t);
 int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
-                      int add_noise, void* scratch, size_t scratch_bytes);
+                      int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax);
 
 // ---- cg_kernels.hip
 int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv,

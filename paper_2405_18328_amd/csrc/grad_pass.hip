@@ -279,13 +279,20 @@ __global__ __launch_bounds__(256) void grad_reduce_kernel(const float* __restric
   }
 }
 
-// acc[comp] += sum over workgroup partials (one workgroup, fixed order)
-__global__ void grad_finalize_kernel(const double* __restrict__ part, int G, int ncomp, double* __restrict__ acc) {
-  for (int c = threadIdx.x; c < ncomp; c += blockDim.x) {
-    double s = 0.0;
-    for (int g = 0; g < G; ++g) s += part[(int64_t)g * ncomp + c];
-    acc[c] += s;
+// acc[comp] += sum over workgroup partials; one workgroup per component, fixed-order tree
+__global__ __launch_bounds__(256) void grad_finalize_kernel(const double* __restrict__ part, int G, int ncomp,
+                                                            double* __restrict__ acc) {
+  __shared__ double sh[256];
+  const int c = blockIdx.x;
+  double s = 0.0;
+  for (int g = threadIdx.x; g < G; g += 256) s += part[(int64_t)g * ncomp + c];
+  sh[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+    __syncthreads();
   }
+  if (threadIdx.x == 0) acc[c] += sh[0];
 }
 
 typedef void (*grad_fn)(GradArgs);
@@ -415,7 +422,7 @@ int gp_grad_run(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int6
     hipLaunchKernelGGL(grad_reduce_kernel, dim3(G), dim3(256), 256 * sizeof(double), st, (const float*)OUT,
                        a.split_stride, JS, (int64_t)nq, (const float*)ctx->dXs, n, d, dV, ldv, dB, ldb, t, half_w,
                        probe_w, t0 == 0 ? 1 : 0, part);
-    hipLaunchKernelGGL(grad_finalize_kernel, dim3(1), dim3(256), 0, st, (const double*)part, G, d + 2, acc);
+    hipLaunchKernelGGL(grad_finalize_kernel, dim3(d + 2), dim3(256), 0, st, (const double*)part, G, d + 2, acc);
     GP_HIP(ctx, hipGetLastError());
   }
 

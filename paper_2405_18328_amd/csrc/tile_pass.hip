@@ -287,9 +287,9 @@ size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t) {
 }
 
 int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
-                  int add_noise, void* scratch, size_t scratch_bytes) {
+                  int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax) {
   if (ctx->path != GP_PATH_FP32)
-    return gp_kmv_launch_f16(ctx, dV, ldv, t, dOut, ldo, add_noise, scratch, scratch_bytes);
+    return gp_kmv_launch_f16(ctx, dV, ldv, t, dOut, ldo, add_noise, scratch, scratch_bytes, colmax);
   const KmvPlan pl = gp_plan_kmv(ctx);
   const bool split = pl.JS > 1;
   if (split && scratch_bytes < (size_t)pl.JS * (size_t)ctx->n * (size_t)t * sizeof(float))

@@ -513,26 +513,27 @@ size_t gp_kmv_f16_scratch_bytes(const gp_ctx* ctx, int t) {
 }
 
 int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo, int add_noise,
-                      void* scratch, size_t scratch_bytes) {
+                      void* scratch, size_t scratch_bytes, const unsigned* colmax_ready) {
   const KmvPlan pl = gp_plan_kmv_f16(ctx);
   const ScratchH L = scratch_layout(ctx, t, pl.JS);
   if (scratch_bytes < L.total || !scratch)
     return gp_fail(ctx, GP_ERR_WORKSPACE, "gp_kmv: scratch %zu < %zu bytes", scratch_bytes, L.total);
   hipStream_t st = ctx->stream;
   char* w = (char*)scratch;
-  unsigned* colmax = (unsigned*)(w + L.off_colmax);
+  const unsigned* colmax = colmax_ready ? colmax_ready : (const unsigned*)(w + L.off_colmax);
   float* VY = (float*)(w + L.off_vy);
   u32x4* VP = (u32x4*)(w + L.off_vp);
   float* part = (float*)(w + L.off_part);
   const bool split = pl.JS > 1;
   const int nchunks = (int)((ctx->n + 31) / 32);
 
-  GP_HIP(ctx, hipMemsetAsync(colmax, 0, (size_t)t * sizeof(unsigned), st));
-  {
+  if (!colmax_ready) {
+    unsigned* cm = (unsigned*)(w + L.off_colmax);
+    GP_HIP(ctx, hipMemsetAsync(cm, 0, (size_t)t * sizeof(unsigned), st));
     int blocks = (int)((ctx->n * (int64_t)t + 4095) / 4096);
     if (blocks > 4 * ctx->num_cu) blocks = 4 * ctx->num_cu;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(colmax_kernel, dim3(blocks), dim3(256), (size_t)t * sizeof(unsigned), st, dV, ldv, ctx->n, t, colmax);
+    hipLaunchKernelGGL(colmax_kernel, dim3(blocks), dim3(256), (size_t)t * sizeof(unsigned), st, dV, ldv, ctx->n, t, cm);
     GP_HIP(ctx, hipGetLastError());
   }
 
