@@ -20,10 +20,29 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 FP32_PEAK_TFLOPS = 157.3   # MI355X dense FP32 matrix peak
+FP16_PEAK_TFLOPS = 2500.0  # MI355X dense FP16 matrix peak
+PATH_NAMES = {0: "fp32", 1: "f16x2", 2: "f16x3"}
+# HBM bytes per launch of the tile kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script (summaries under profiles/), keyed by (workload, n); filled in from those runs, not measured live
+TRAFFIC = {("config2", 16384): 43.5e6, ("config5", 2000000): 3.79e9}
 
 
 def kmv_flops(n, d, t, kind):
     return float(n) * float(n) * (2 * d + 2 * t + (4 if kind == "se" else 8))
+
+
+def executed_mfma_flops(n, d, t, kind, path):
+    """Matrix-core flops the tile kernel really issues per K V product (padding of the contraction
+    lengths and the extra products of the fp16 splitting included), as opposed to kmv_flops."""
+    nt = (t // 32) if t % 32 == 1 and t > 1 else -(-t // 32)     # a lone 33rd column goes through the vector ALU
+    if path == 0:
+        ks = next(b for b in (4, 7, 10, 14, 24, 46, 64) if 2 * b >= d + 2)
+        per_pair = 2 * 2 * ks + 2 * 32 * nt
+    else:
+        slots = d + 2 + (1 if kind == "se" else 0)
+        kh = next(b for b in (1, 2, 3, 4, 6, 8) if 16 * b >= slots)
+        per_pair = (3 if path == 1 else 6) * 2 * 16 * kh + 3 * 2 * 32 * nt
+    return float(n) * float(n) * per_pair
 
 
 def cpu_baseline(w):
@@ -64,6 +83,9 @@ def main():
     ap.add_argument("--no-cold", action="store_true", help="skip the cold-start comparison arm")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--kmv-only", action="store_true", help="time bare K V products instead of MLL steps")
+    ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
+                    help="also run three plain device copies of MIB MiB (reads MIB, writes MIB): the known-size "
+                         "kernel that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -93,6 +115,13 @@ def main():
     opt = MllOptimizer(w.X, w.y, w.Z, w.kind, w.ell, w.a, w.sigma, w.tol, warm=True, max_iters=max_iters)
     result = {}
     try:
+        if args.calib_copy:
+            src = torch.ones(args.calib_copy << 18, dtype=torch.float32, device=opt.dev)
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                dst.copy_(src)
+            torch.cuda.synchronize()
+            del src, dst
         if args.kmv_only:
             out = torch.empty_like(opt.B)
             theta = opt.theta
@@ -155,20 +184,32 @@ def main():
                                  "note": "zero initialisation + resampled Gaussian probes, same theta sequence"}
                 extra["warm_vs_cold_cg_speedup"] = extra["cold"]["cg_ms_per_step"] / warm_stats["cg_ms_per_step"]
         value = n_kmv * F / wall / 1e12
+        # every tile-kernel launch of the timed region is bracketed; a product is one launch, or several
+        # (long column ranges are cut into passes), so the algorithmic flops of one launch are:
         avg_kern_s = kern_ms / 1e3 / max(launches, 1)
-        achieved = F / avg_kern_s / 1e12 if launches else 0.0
+        F_launch = F * n_kmv / max(launches, 1)
+        achieved = F_launch / avg_kern_s / 1e12 if launches else 0.0
+        path = gp.gp_product_path(opt.ctx)
+        # the contraction runs on the matrix cores in the dtype of the chosen product path
+        peak = FP32_PEAK_TFLOPS if path == 0 else FP16_PEAK_TFLOPS
+        executed = executed_mfma_flops(n, d, t, w.kind, path) * n_kmv / max(launches, 1) / avg_kern_s / 1e12 if launches else 0.0
         result = {
             "metric": "matrix-free K.V TFLOP/s (% FP32 peak) + CG time per MLL step, warm vs cold",
             "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
             "ms_per_step": wall / steps * 1e3, "higher_is_better": True, "scaling": "weak",
-            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "vs_baseline": None, "dtype": "f32" if path == 0 else "f32 (fp16x2-split matrix-core products, fp32 accumulate)",
+            "data": "synthetic",
             "config": {"workload": desc, "n": n, "d": d, "t": t, "kernel": w.kind, "max_iters": max_iters,
                        "kmv_products_timed": int(n_kmv), "input_generation_s": round(t_gen, 1)},
             "pct_fp32_peak": 100.0 * value / FP32_PEAK_TFLOPS,
-            "roofline": {"bound": "mfma", "achieved": achieved, "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": achieved / FP32_PEAK_TFLOPS, "traffic": None, "kernel": "kmv_tile_kernel",
+            "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                         "frac": achieved / peak, "traffic": TRAFFIC.get((args.workload, n)),
+                         "kernel": "kmv_tile_kernel" if path == 0 else "kmv_tile_f16_kernel",
+                         "product_path": PATH_NAMES[path], "peak_dtype": "fp32" if path == 0 else "fp16",
                          "launches": int(launches), "avg_launch_ms": avg_kern_s * 1e3,
-                         "flops_per_launch": F},
+                         "flops_per_launch": F_launch,
+                         "executed_mfma_tflops": executed, "executed_mfma_frac_of_peak": executed / peak,
+                         "achieved_vs_fp32_peak": achieved / FP32_PEAK_TFLOPS},
         }
         result.update(extra)
     finally:

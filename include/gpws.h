@@ -145,6 +145,17 @@ int gp_mll_grad(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int6
 int gp_profile(gp_ctx* ctx, int enable);
 int gp_profile_read(gp_ctx* ctx, int* h_launches, double* h_total_ms);
 
+/*
+ * Which arithmetic the K V tile pass uses for the current theta (Section 2.1 leaves the
+ * arithmetic of the product open; all three meet the same accuracy bar).  gp_set_theta
+ * picks it from the largest scaled squared norm max_i |(x_i - mean)/ell|^2:
+ *   0  fp32 matrix-core products throughout,
+ *   1  fp16 matrix-core products on operands split into two fp16 pieces (fp32 accumulation),
+ *   2  the same with three pieces for the distance operands.
+ * Returns the code, or GP_ERR_ARG for a NULL context or before the first gp_set_theta.
+ */
+int gp_product_path(const gp_ctx* ctx);
+
 /* Text of the last error on this context ("" if none).  Never NULL. */
 const char* gp_last_error(const gp_ctx* ctx);
 

@@ -28,7 +28,7 @@ GP_MAX_T = 1024
 LIB_PATH = os.environ.get("GPWS_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgpws.so")
 
 EXPORTS = ["gp_create", "gp_destroy", "gp_set_theta", "gp_kmv", "gp_workspace_bytes", "gp_cg_solve",
-           "gp_mll_grad", "gp_profile", "gp_profile_read", "gp_last_error"]
+           "gp_mll_grad", "gp_profile", "gp_profile_read", "gp_product_path", "gp_last_error"]
 
 
 def _load():
@@ -47,6 +47,7 @@ def _load():
     lib.gp_mll_grad.argtypes = [p, p, i64, p, i64, i32, C.POINTER(dbl)]
     lib.gp_profile.argtypes = [p, i32]
     lib.gp_profile_read.argtypes = [p, C.POINTER(i32), C.POINTER(dbl)]
+    lib.gp_product_path.argtypes = [p]
     lib.gp_last_error.argtypes = [p]
     lib.gp_last_error.restype = C.c_char_p
     for name in EXPORTS:
@@ -136,6 +137,13 @@ def gp_mll_grad(ctx, dV, ldv, dB, ldb, t, d):
 
 def gp_profile(ctx, enable):
     return _check(ctx, _lib.gp_profile(ctx, int(enable)))
+
+
+def gp_product_path(ctx):
+    rc = _lib.gp_product_path(ctx)
+    if rc < 0:
+        raise GpError(rc, "gp_product_path: no theta set")
+    return rc
 
 
 def gp_profile_read(ctx):

@@ -222,6 +222,11 @@ int gp_profile(gp_ctx* ctx, int enable) {
   return GP_OK;
 }
 
+int gp_product_path(const gp_ctx* ctx) {
+  if (!ctx || !ctx->theta_set) return GP_ERR_ARG;
+  return ctx->path;
+}
+
 int gp_profile_read(gp_ctx* ctx, int* h_launches, double* h_total_ms) {
   if (!ctx) return GP_ERR_ARG;
   GP_HIP(ctx, hipStreamSynchronize(ctx->stream));

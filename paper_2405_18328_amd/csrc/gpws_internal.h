@@ -26,6 +26,7 @@ enum { GP_PATH_FP32 = 0, GP_PATH_F16X2 = 1, GP_PATH_F16X3 = 2 };
 // past this squared norm three pieces (33 bits) are used, and past fp16's range the fp32 MFMA path
 constexpr float GP_NORM_X2_MAX = 64.0f;
 constexpr float GP_NORM_X3_MAX = 16000.0f;
+constexpr int GP_MAX_CPS = 1024;      // longest run of column chunks summed in one chain of fp32 partial sums
 constexpr int GP_PROF_MAX = 8192;     // event pairs available to gp_profile
 
 // Operands of the distance contraction, packed so that one wave-wide dword
@@ -100,6 +101,7 @@ struct KmvPlan {
   int JS;        // column-range splits
   int row_blocks;
   int cps;       // chunks per split
+  int passes;    // sequential launches over successive column ranges, each adding to OUT (1 when JS > 1)
 };
 KmvPlan gp_plan_kmv(const gp_ctx* ctx);
 size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t);   // worst case over the paths gp_set_theta may choose

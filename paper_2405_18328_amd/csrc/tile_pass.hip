@@ -32,6 +32,8 @@ struct TileArgs {
   int vcol;               // column carried on the VALU, or -1
   int JS;
   int cps;                // chunks per split
+  int js0;                // index of this launch's first split among all splits of the product
+  int accumulate;         // add to what OUT already holds (later passes over the column range)
   float a2;
   float sigma2;
   int add_noise;
@@ -69,7 +71,7 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_kernel(TileArgs p) {
   const int rb = blockIdx.x / p.JS;
   const int sub0 = (rb * GP_WAVES + wave) * MI;     // first 32-row sub-tile of this wave
 
-  const int c_begin = js * p.cps;
+  const int c_begin = (p.js0 + js) * p.cps;
   const int c_end = min(p.nchunks, c_begin + p.cps);
 
   // row-side operands stay in registers for the whole pass
@@ -185,7 +187,8 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_kernel(TileArgs p) {
 
   // epilogue: scale by a^2, add the noise term once (split 0), store
   float* out = p.OUT + (int64_t)js * p.split_stride;
-  const bool noise = p.add_noise && js == 0;
+  const bool noise = p.add_noise && p.js0 + js == 0;
+  const bool accumulate = p.accumulate != 0;
 #pragma unroll
   for (int m = 0; m < MI; ++m) {
     const int64_t ibase = (int64_t)(sub0 + m) * 32;
@@ -198,6 +201,7 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_kernel(TileArgs p) {
         if (i < p.n && c < p.ncols) {
           float v = p.a2 * acc[m][nt][r];
           if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.col0 + c], v);
+          if (accumulate) v += out[i * p.ldo + p.col0 + c];
           out[i * p.ldo + p.col0 + c] = v;
         }
       }
@@ -208,6 +212,7 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_kernel(TileArgs p) {
       if (h == 0 && i < p.n) {
         float v = p.a2 * tot;
         if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.vcol], v);
+        if (accumulate) v += out[i * p.ldo + p.vcol];
         out[i * p.ldo + p.vcol] = v;
       }
     }
@@ -276,6 +281,14 @@ KmvPlan gp_plan_kmv(const gp_ctx* ctx) {
   }
   pl.cps = (int)((chunks + JS - 1) / JS);
   pl.JS = (int)((chunks + pl.cps - 1) / pl.cps);
+  // long column ranges are cut into passes (separate launches that add to OUT in order) so that no
+  // chain of fp32 partial sums runs over more than GP_MAX_CPS chunks
+  pl.passes = 1;
+  if (pl.JS == 1 && pl.cps > GP_MAX_CPS) {
+    pl.passes = (int)((chunks + GP_MAX_CPS - 1) / GP_MAX_CPS);
+    pl.cps = (int)((chunks + pl.passes - 1) / pl.passes);
+    pl.passes = (int)((chunks + pl.cps - 1) / pl.cps);
+  }
   return pl;
 }
 
@@ -307,6 +320,8 @@ int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut,
   a.nchunks = (int)((ctx->n + 31) / 32);
   a.JS = pl.JS;
   a.cps = pl.cps;
+  a.js0 = 0;
+  a.accumulate = 0;
   a.a2 = (float)(ctx->a * ctx->a);
   a.sigma2 = (float)(ctx->sigma * ctx->sigma);
   a.add_noise = add_noise;
@@ -325,13 +340,17 @@ int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut,
     tile_fn fn = ctx->kernel == GP_SE_ARD ? pick_ks<GP_SE_ARD>(ctx->KS, NT, pl.MI)
                                           : pick_ks<GP_MATERN32_ARD>(ctx->KS, NT, pl.MI);
     if (!fn) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: no kernel for KS=%d", ctx->KS);
-    const bool prof = ctx->prof_on && ctx->prof_count < GP_PROF_MAX;
-    if (prof) GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count], ctx->stream));
-    hipLaunchKernelGGL(fn, grid, block, 0, ctx->stream, a);
-    GP_HIP(ctx, hipGetLastError());
-    if (prof) {
-      GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count + 1], ctx->stream));
-      ++ctx->prof_count;
+    for (int ps = 0; ps < pl.passes; ++ps) {
+      a.js0 = ps;
+      a.accumulate = ps > 0;
+      const bool prof = ctx->prof_on && ctx->prof_count < GP_PROF_MAX;
+      if (prof) GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count], ctx->stream));
+      hipLaunchKernelGGL(fn, grid, block, 0, ctx->stream, a);
+      GP_HIP(ctx, hipGetLastError());
+      if (prof) {
+        GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count + 1], ctx->stream));
+        ++ctx->prof_count;
+      }
     }
     c += a.ncols;
   }

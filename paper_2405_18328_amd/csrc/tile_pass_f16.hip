@@ -55,7 +55,9 @@ struct TileArgsH {
   int64_t n;
   int nchunks;
   int col0, ncols, vcol;
-  int JS, cps;
+  int JS, cps;             // column-range splits inside this launch, chunks per split
+  int js0;                 // index of this launch's first split among all splits of the product
+  int accumulate;          // add to what OUT already holds (later passes over the column range)
   float a2, sigma2;
   int add_noise;
 };
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(64 * W) void kmv_tile_f16_kernel(TileArgsH p) {
   const int js = blockIdx.x % p.JS;
   const int rb = blockIdx.x / p.JS;
   const int sub0 = (rb * W + wave) * MI;
-  const int c_begin = js * p.cps;
+  const int c_begin = (p.js0 + js) * p.cps;
   const int c_end = min(p.nchunks, c_begin + p.cps);
 
   // row-side operands: registers for the whole pass
@@ -312,7 +314,8 @@ __global__ __launch_bounds__(64 * W) void kmv_tile_f16_kernel(TileArgsH p) {
   asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
   // epilogue: undo the power-of-two scalings, multiply by a^2, add the noise term once, store
   float* out = p.OUT + (int64_t)js * p.split_stride;
-  const bool noise = p.add_noise && js == 0;
+  const bool noise = p.add_noise && p.js0 + js == 0;
+  const bool accumulate = p.accumulate != 0;
   float oscale[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
@@ -331,6 +334,7 @@ __global__ __launch_bounds__(64 * W) void kmv_tile_f16_kernel(TileArgsH p) {
         if (i < p.n && c < p.ncols) {
           float v = oscale[nt] * acc[m][nt][r];
           if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.col0 + c], v);
+          if (accumulate) v += out[i * p.ldo + p.col0 + c];
           out[i * p.ldo + p.col0 + c] = v;
         }
       }
@@ -341,6 +345,7 @@ __global__ __launch_bounds__(64 * W) void kmv_tile_f16_kernel(TileArgsH p) {
       if (h == 0 && i < p.n) {
         float v = p.a2 * ldexpf(1.0f, -PHI_SHIFT) * tot;
         if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.vcol], v);
+        if (accumulate) v += out[i * p.ldo + p.vcol];
         out[i * p.ldo + p.vcol] = v;
       }
     }
@@ -505,6 +510,17 @@ KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx) {
   }
   pl.cps = (int)((chunks + JS - 1) / JS);
   pl.JS = (int)((chunks + pl.cps - 1) / pl.cps);
+  // Rounding error of the fp32 accumulators grows with the length of the chain of partial sums, so a
+  // long column range is cut into passes of at most GP_MAX_CPS chunks; each pass is its own launch
+  // over all row blocks and adds its result to OUT in launch order (deterministic, no scratch).
+  pl.passes = 1;
+  int max_cps = GP_MAX_CPS;
+  if (const char* e = getenv("GPWS_MAX_CPS")) max_cps = atoi(e) > 0 ? atoi(e) : max_cps;               // tuning aid
+  if (pl.JS == 1 && pl.cps > max_cps) {
+    pl.passes = (int)((chunks + max_cps - 1) / max_cps);
+    pl.cps = (int)((chunks + pl.passes - 1) / pl.passes);
+    pl.passes = (int)((chunks + pl.cps - 1) / pl.cps);
+  }
   return pl;
 }
 
@@ -554,6 +570,8 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
   a.nchunks = nchunks;
   a.JS = pl.JS;
   a.cps = pl.cps;
+  a.js0 = 0;
+  a.accumulate = 0;
   a.a2 = (float)(ctx->a * ctx->a);
   a.sigma2 = (float)(ctx->sigma * ctx->sigma);
   a.add_noise = add_noise;
@@ -577,13 +595,17 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
     vcol = -1;
     tileh_fn fn = pick_h(ctx->kernel, ctx->KH, ctx->XP, NT, pl.MI, pl.W);
     if (!fn) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: no fp16 kernel for KH=%d", ctx->KH);
-    const bool prof = ctx->prof_on && ctx->prof_count < GP_PROF_MAX;
-    if (prof) GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count], st));
-    hipLaunchKernelGGL(fn, grid, block, 0, st, a);
-    GP_HIP(ctx, hipGetLastError());
-    if (prof) {
-      GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count + 1], st));
-      ++ctx->prof_count;
+    for (int ps = 0; ps < pl.passes; ++ps) {
+      a.js0 = ps;
+      a.accumulate = ps > 0;
+      const bool prof = ctx->prof_on && ctx->prof_count < GP_PROF_MAX;
+      if (prof) GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count], st));
+      hipLaunchKernelGGL(fn, grid, block, 0, st, a);
+      GP_HIP(ctx, hipGetLastError());
+      if (prof) {
+        GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count + 1], st));
+        ++ctx->prof_count;
+      }
     }
     c += a.ncols;
   }

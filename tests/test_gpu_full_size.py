@@ -1,0 +1,111 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The dense fp64 oracle cannot be run whole at these sizes, so it computes exact output rows for a
+seeded sample (every column of those rows), and the remaining checks are properties that hold at
+any size.  Same tolerances as the small-size parity tests.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gp_oracle as orc
+from paper_2405_18328_amd import binding as gp
+from paper_2405_18328_amd.inputs import make
+from paper_2405_18328_amd.mll import MllOptimizer
+from tests.gpu_util import Dev, relerr
+
+pytestmark = pytest.mark.gpu
+
+KMV_TOL = 1e-5
+
+
+def _note(msg):
+    print(f"[full-size] {msg}", flush=True)
+
+
+def test_config2_full_size_mll_steps_sampled_against_oracle():
+    """n=16384, d=26, Matern-3/2, t=65: the optimiser bench.py runs (warm-started steps), then at the
+    last step's theta: K B on sampled rows, the true residual of the solve on sampled rows, and the
+    noise-scale component of the gradient (closed form from V and Z, Section 2.1 gradient with
+    dH/dsigma = 2 sigma I)."""
+    w = make("config2")
+    assert (w.n, w.d, w.s) == (16384, 26, 64)
+    opt = MllOptimizer(w.X, w.y, w.Z, w.kind, w.ell, w.a, w.sigma, w.tol, warm=True, max_iters=1000)
+    try:
+        recs = [opt.step() for _ in range(4)]
+        _note(f"iterations per step {[r.iters for r in recs]}")
+        assert all(r.rc == 0 for r in recs)
+        # warm start: later solves start from the previous solution and need fewer iterations
+        assert recs[-1].iters < recs[0].iters
+        last = recs[-1]
+        ell, a, sigma = last.theta[: w.d], last.theta[w.d], last.theta[w.d + 1]
+        t = w.s + 1
+        V = opt.V.cpu().numpy().astype(np.float64)
+        B = opt.B.cpu().numpy().astype(np.float64)
+        # the context still holds the last step's theta
+        out = torch.empty_like(opt.B)
+        gp.gp_kmv(opt.ctx, opt.B, t, t, out, t, 1)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+
+        rows = np.sort(np.random.default_rng(11).choice(w.n, size=1536, replace=False))
+        rows[0], rows[-1] = 0, w.n - 1
+        _note("oracle rows")
+        ref = orc.kmv_rows(w.X, ell, a, w.kind, np.concatenate([B, V], axis=1), rows, sigma=sigma)
+        HB, HV = ref[:, :t], ref[:, t:]
+        assert relerr(got[rows], HB) <= KMV_TOL
+        assert np.abs(got[rows] - HB).max() <= 50 * KMV_TOL * np.abs(HB).max()
+
+        # true residual on the sampled rows, scaled to the whole vector: ||r_c|| ~ sqrt(n/m) ||r_c[rows]||
+        res = np.linalg.norm(HV - B[rows], axis=0) * np.sqrt(w.n / rows.size)
+        rel = res / np.linalg.norm(B, axis=0)
+        _note(f"sampled true relative residual max {rel.max():.3e} (tol {w.tol})")
+        assert rel.max() <= 1.5 * w.tol
+
+        # gradient: noise component in closed form
+        g_sigma = 2.0 * sigma * (0.5 * V[:, 0] @ V[:, 0] - 0.5 * np.sum(V[:, 1:] * B[:, 1:]) / w.s)
+        assert abs(last.grad[w.d + 1] - g_sigma) <= 1e-3 * max(abs(g_sigma), sigma * (V[:, 0] @ V[:, 0]))
+        assert np.isfinite(last.grad).all()
+    finally:
+        opt.close()
+
+
+def test_config5_two_million_rows_sampled_against_oracle():
+    """n=2,000,000, d=11, SE, t=65 (5% duplicated rows): one K V product as bench.py --kmv-only
+    launches it; exact rows from the oracle, equal rows for duplicated inputs, symmetry of K."""
+    w = make("config5")
+    assert w.n == 2_000_000 and w.d == 11
+    _note("inputs ready")
+    dv = Dev(w.X, w.kind, w.ell, w.a, w.sigma)
+    try:
+        t = w.s + 1
+        Bd = dv.to(w.B)
+        out = torch.empty_like(Bd)
+        gp.gp_kmv(dv.ctx, Bd, t, t, out, t, 0)
+        torch.cuda.synchronize()
+        _note("product done")
+        got = out.cpu().numpy()
+        assert np.isfinite(got).all()
+        rows = np.random.default_rng(5).choice(w.n, size=48, replace=False)
+        rows[:4] = [0, w.n - 1, 1_048_575, 1_048_576]
+        ref = orc.kmv_rows(w.X, w.ell, w.a, w.kind, w.B, rows, sigma=None)
+        assert relerr(got[rows], ref) <= KMV_TOL
+        assert np.abs(got[rows] - ref).max() <= 50 * KMV_TOL * np.abs(ref).max()
+        _note("rows checked")
+        # duplicated inputs give equal output rows: pair rows up by an exact key, confirm the inputs match
+        key = w.X.astype(np.float64) @ np.random.default_rng(6).standard_normal(w.d)
+        order = np.argsort(key, kind="stable")
+        same = np.nonzero(key[order[1:]] == key[order[:-1]])[0][:2000]
+        i1, i2 = order[same], order[same + 1]
+        ok = (w.X[i1] == w.X[i2]).all(axis=1)
+        i1, i2 = i1[ok], i2[ok]
+        assert i1.size > 500
+        assert np.abs(got[i1] - got[i2]).max() <= 1e-5 * np.abs(got).max()
+        dup = i1
+        _note(f"{dup.size} duplicated rows checked")
+        # symmetry of K: u^T (K v) = v^T (K u) with u, v two probe columns
+        b1, b2 = w.B[:, 1].astype(np.float64), w.B[:, 2].astype(np.float64)
+        k1, k2 = got[:, 1].astype(np.float64), got[:, 2].astype(np.float64)
+        assert abs(b2 @ k1 - b1 @ k2) <= 1e-5 * np.linalg.norm(b2) * np.linalg.norm(k1)
+    finally:
+        dv.close()
