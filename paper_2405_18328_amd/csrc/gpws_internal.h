@@ -26,7 +26,7 @@ enum { GP_PATH_FP32 = 0, GP_PATH_F16X2 = 1, GP_PATH_F16X3 = 2 };
 // past this squared norm three pieces (33 bits) are used, and past fp16's range the fp32 MFMA path
 constexpr float GP_NORM_X2_MAX = 64.0f;
 constexpr float GP_NORM_X3_MAX = 16000.0f;
-constexpr int GP_MAX_CPS = 1024;      // longest run of column chunks summed in one chain of fp32 partial sums
+constexpr int GP_FLUSH_CHUNKS = 1024; // tile kernels add their fp32 accumulators into OUT every this many column chunks (power of 2)
 constexpr int GP_PROF_MAX = 8192;     // event pairs available to gp_profile
 
 // Operands of the distance contraction, packed so that one wave-wide dword
@@ -101,7 +101,6 @@ struct KmvPlan {
   int JS;        // column-range splits
   int row_blocks;
   int cps;       // chunks per split
-  int passes;    // sequential launches over successive column ranges, each adding to OUT (1 when JS > 1)
 };
 KmvPlan gp_plan_kmv(const gp_ctx* ctx);
 size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t);   // worst case over the paths gp_set_theta may choose
@@ -117,6 +116,9 @@ size_t gp_kmv_f16_scratch_bytes(const gp_ctx* ctx, int t);
 int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
                       int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax);
 
+// colmax[c] = bit pattern of max_i |V_ic| for c < t (cleared first); stream-ordered
+int gp_launch_colmax(gp_ctx* ctx, const float* dV, int64_t ldv, int t, unsigned* colmax);
+
 // ---- cg_kernels.hip
 int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv,
               int t, const float* h_tol, int max_iters, void* dWork, size_t work_bytes,
@@ -126,5 +128,14 @@ size_t gp_cg_workspace_bytes(const gp_ctx* ctx, int t);
 // ---- grad_pass.hip
 int gp_grad_run(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int64_t ldb, int t,
                 double* h_grad);
+// fp64 reduction of one right-hand-side block's tile-pass output OUT[JS][n][nq] into acc[d + 2]
+// (part: G x (d + 2) workgroup partials); first_block adds the sigma component sum_i w_ii
+int gp_grad_reduce_launch(gp_ctx* ctx, const float* OUT, int64_t split_stride, int JS, int nq, const float* dV,
+                          int64_t ldv, const float* dB, int64_t ldb, int t, float half_w, float probe_w,
+                          int first_block, double* part, int G, double* acc);
+
+// ---- grad_pass_f16.hip
+int gp_grad_run_f16(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int64_t ldb, int t,
+                    double* h_grad);
 
 #endif

@@ -326,8 +326,21 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace
 
+int gp_grad_reduce_launch(gp_ctx* ctx, const float* OUT, int64_t split_stride, int JS, int nq, const float* dV,
+                          int64_t ldv, const float* dB, int64_t ldb, int t, float half_w, float probe_w,
+                          int first_block, double* part, int G, double* acc) {
+  const int d = ctx->d;
+  hipLaunchKernelGGL(grad_reduce_kernel, dim3(G), dim3(256), 256 * sizeof(double), ctx->stream, OUT, split_stride, JS,
+                     (int64_t)nq, (const float*)ctx->dXs, ctx->n, d, dV, ldv, dB, ldb, t, half_w, probe_w, first_block,
+                     part);
+  hipLaunchKernelGGL(grad_finalize_kernel, dim3(d + 2), dim3(256), 0, ctx->stream, (const double*)part, G, d + 2, acc);
+  GP_HIP(ctx, hipGetLastError());
+  return GP_OK;
+}
+
 int gp_grad_run(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int64_t ldb, int t,
                 double* h_grad) {
+  if (ctx->path != GP_PATH_FP32) return gp_grad_run_f16(ctx, dV, ldv, dB, ldb, t, h_grad);
   const int d = ctx->d;
   const int64_t n = ctx->n;
   const int nq = 2 * d + 2;         // Q columns (2d+1) + the VALU column
@@ -419,11 +432,9 @@ int gp_grad_run(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int6
       GP_HIP(ctx, hipGetLastError());
       c += a.ncols;
     }
-    hipLaunchKernelGGL(grad_reduce_kernel, dim3(G), dim3(256), 256 * sizeof(double), st, (const float*)OUT,
-                       a.split_stride, JS, (int64_t)nq, (const float*)ctx->dXs, n, d, dV, ldv, dB, ldb, t, half_w,
-                       probe_w, t0 == 0 ? 1 : 0, part);
-    hipLaunchKernelGGL(grad_finalize_kernel, dim3(d + 2), dim3(256), 0, st, (const double*)part, G, d + 2, acc);
-    GP_HIP(ctx, hipGetLastError());
+    rc = gp_grad_reduce_launch(ctx, OUT, a.split_stride, JS, nq, dV, ldv, dB, ldb, t, half_w, probe_w, t0 == 0 ? 1 : 0,
+                               part, G, acc);
+    if (rc < 0) return rc;
   }
 
   double* hacc = (double*)ctx->hPinned;

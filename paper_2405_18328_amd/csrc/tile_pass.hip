@@ -32,8 +32,6 @@ struct TileArgs {
   int vcol;               // column carried on the VALU, or -1
   int JS;
   int cps;                // chunks per split
-  int js0;                // index of this launch's first split among all splits of the product
-  int accumulate;         // add to what OUT already holds (later passes over the column range)
   float a2;
   float sigma2;
   int add_noise;
@@ -71,8 +69,12 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_kernel(TileArgs p) {
   const int rb = blockIdx.x / p.JS;
   const int sub0 = (rb * GP_WAVES + wave) * MI;     // first 32-row sub-tile of this wave
 
-  const int c_begin = (p.js0 + js) * p.cps;
-  const int c_end = min(p.nchunks, c_begin + p.cps);
+  // The workgroup's column range [r_begin, r_end) is walked in segments [c_begin, c_end) of at most
+  // GP_FLUSH_CHUNKS chunks; the accumulators are added into OUT after each segment (see flush below).
+  const int r_begin = js * p.cps;
+  const int r_end = min(p.nchunks, r_begin + p.cps);
+  int c_begin = r_begin;
+  int c_end = min(r_end, c_begin + GP_FLUSH_CHUNKS);
 
   // row-side operands stay in registers for the whole pass
   float xb[MI][KS];
@@ -130,12 +132,55 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_kernel(TileArgs p) {
     if (tid < 32) s[VY_OFF + tid] = gvy;
   };
 
+  // Writes what the accumulators hold to OUT (first: stores a^2 acc plus the noise term once; later:
+  // adds to what is there) and clears them.  Doing so after every segment keeps the chains
+  // of fp32 partial sums short; the same threads read and write the same elements, in a fixed order.
+  float* out = p.OUT + (int64_t)js * p.split_stride;
+  auto flush = [&](bool first) {
+    const bool noise = first && p.add_noise && js == 0;
+    // an opaque zero keeps the address arithmetic of the flush inside it: hoisted out of the segment
+    // loop it would hold dozens of registers across the main loop
+    int zero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(zero));
+#pragma unroll
+    for (int m = 0; m < MI; ++m) {
+      const int64_t ibase = (int64_t)(sub0 + m) * 32 + zero;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int c = li + 32 * nt;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int64_t i = ibase + 8 * (r >> 2) + 4 * h + (r & 3);
+          if (i < p.n && c < p.ncols) {
+            float v = p.a2 * acc[m][nt][r];
+            if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.col0 + c], v);
+            if (!first) v += out[i * p.ldo + p.col0 + c];
+            out[i * p.ldo + p.col0 + c] = v;
+          }
+          acc[m][nt][r] = 0.0f;
+        }
+      }
+      if (p.vcol >= 0) {
+        const float tot = accv[m] + __shfl_xor(accv[m], 32);
+        const int64_t i = ibase + li;
+        if (h == 0 && i < p.n) {
+          float v = p.a2 * tot;
+          if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.vcol], v);
+          if (!first) v += out[i * p.ldo + p.vcol];
+          out[i * p.ldo + p.vcol] = v;
+        }
+        accv[m] = 0.0f;
+      }
+    }
+  };
+  bool first = true;
+
+  for (;;) {
   // every split owns at least one chunk (the launcher sizes JS that way), so the prologue is
   // unconditional; its wait for the staged chunk also retires the xb loads above
   load_chunk(c_begin);
   store_chunk(0);
   __syncthreads();
-
   for (int ch = c_begin; ch < c_end; ++ch) {
     const int st = (ch - c_begin) & 1;
     if (ch + 1 < c_end) load_chunk(ch + 1);
@@ -184,38 +229,11 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_kernel(TileArgs p) {
     if (ch + 1 < c_end) store_chunk(st ^ 1);
     __syncthreads();
   }
-
-  // epilogue: scale by a^2, add the noise term once (split 0), store
-  float* out = p.OUT + (int64_t)js * p.split_stride;
-  const bool noise = p.add_noise && p.js0 + js == 0;
-  const bool accumulate = p.accumulate != 0;
-#pragma unroll
-  for (int m = 0; m < MI; ++m) {
-    const int64_t ibase = (int64_t)(sub0 + m) * 32;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const int c = li + 32 * nt;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t i = ibase + 8 * (r >> 2) + 4 * h + (r & 3);
-        if (i < p.n && c < p.ncols) {
-          float v = p.a2 * acc[m][nt][r];
-          if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.col0 + c], v);
-          if (accumulate) v += out[i * p.ldo + p.col0 + c];
-          out[i * p.ldo + p.col0 + c] = v;
-        }
-      }
-    }
-    if (p.vcol >= 0) {
-      float tot = accv[m] + __shfl_xor(accv[m], 32);
-      const int64_t i = ibase + li;
-      if (h == 0 && i < p.n) {
-        float v = p.a2 * tot;
-        if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.vcol], v);
-        if (accumulate) v += out[i * p.ldo + p.vcol];
-        out[i * p.ldo + p.vcol] = v;
-      }
-    }
+  flush(first);
+  first = false;
+  if (c_end >= r_end) break;
+  c_begin = c_end;
+  c_end = min(r_end, c_begin + GP_FLUSH_CHUNKS);
   }
 }
 
@@ -281,14 +299,6 @@ KmvPlan gp_plan_kmv(const gp_ctx* ctx) {
   }
   pl.cps = (int)((chunks + JS - 1) / JS);
   pl.JS = (int)((chunks + pl.cps - 1) / pl.cps);
-  // long column ranges are cut into passes (separate launches that add to OUT in order) so that no
-  // chain of fp32 partial sums runs over more than GP_MAX_CPS chunks
-  pl.passes = 1;
-  if (pl.JS == 1 && pl.cps > GP_MAX_CPS) {
-    pl.passes = (int)((chunks + GP_MAX_CPS - 1) / GP_MAX_CPS);
-    pl.cps = (int)((chunks + pl.passes - 1) / pl.passes);
-    pl.passes = (int)((chunks + pl.cps - 1) / pl.cps);
-  }
   return pl;
 }
 
@@ -320,8 +330,6 @@ int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut,
   a.nchunks = (int)((ctx->n + 31) / 32);
   a.JS = pl.JS;
   a.cps = pl.cps;
-  a.js0 = 0;
-  a.accumulate = 0;
   a.a2 = (float)(ctx->a * ctx->a);
   a.sigma2 = (float)(ctx->sigma * ctx->sigma);
   a.add_noise = add_noise;
@@ -340,17 +348,13 @@ int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut,
     tile_fn fn = ctx->kernel == GP_SE_ARD ? pick_ks<GP_SE_ARD>(ctx->KS, NT, pl.MI)
                                           : pick_ks<GP_MATERN32_ARD>(ctx->KS, NT, pl.MI);
     if (!fn) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: no kernel for KS=%d", ctx->KS);
-    for (int ps = 0; ps < pl.passes; ++ps) {
-      a.js0 = ps;
-      a.accumulate = ps > 0;
-      const bool prof = ctx->prof_on && ctx->prof_count < GP_PROF_MAX;
-      if (prof) GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count], ctx->stream));
-      hipLaunchKernelGGL(fn, grid, block, 0, ctx->stream, a);
-      GP_HIP(ctx, hipGetLastError());
-      if (prof) {
-        GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count + 1], ctx->stream));
-        ++ctx->prof_count;
-      }
+    const bool prof = ctx->prof_on && ctx->prof_count < GP_PROF_MAX;
+    if (prof) GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count], ctx->stream));
+    hipLaunchKernelGGL(fn, grid, block, 0, ctx->stream, a);
+    GP_HIP(ctx, hipGetLastError());
+    if (prof) {
+      GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count + 1], ctx->stream));
+      ++ctx->prof_count;
     }
     c += a.ncols;
   }

@@ -56,8 +56,6 @@ struct TileArgsH {
   int nchunks;
   int col0, ncols, vcol;
   int JS, cps;             // column-range splits inside this launch, chunks per split
-  int js0;                 // index of this launch's first split among all splits of the product
-  int accumulate;          // add to what OUT already holds (later passes over the column range)
   float a2, sigma2;
   int add_noise;
 };
@@ -67,7 +65,7 @@ __device__ __forceinline__ f16x8 as_f16x8(u32x4 v) { return __builtin_bit_cast(f
 // W wavefronts per workgroup: every workgroup streams all of V' and XA through its LDS, so the
 // L2-to-LDS traffic of a launch is inversely proportional to the rows a workgroup owns (32 MI W).
 template <int KIND, int KH, int XP, int NT, int MI, int W>
-__global__ __launch_bounds__(64 * W) void kmv_tile_f16_kernel(TileArgsH p) {
+__global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) void kmv_tile_f16_kernel(TileArgsH p) {
   // One pipeline stage in LDS, in 16-byte units: G groups of 64 units (one wave-wide 16-byte load
   // each): XP*KH groups of XA pieces, then 4*NT groups of V' images; then one 8-unit y slot per wave.
   constexpr int XA_G = XP * KH;
@@ -92,8 +90,12 @@ __global__ __launch_bounds__(64 * W) void kmv_tile_f16_kernel(TileArgsH p) {
   const int js = blockIdx.x % p.JS;
   const int rb = blockIdx.x / p.JS;
   const int sub0 = (rb * W + wave) * MI;
-  const int c_begin = (p.js0 + js) * p.cps;
-  const int c_end = min(p.nchunks, c_begin + p.cps);
+  // The workgroup's column range [r_begin, r_end) is walked in segments [c_begin, c_end) of at most
+  // GP_FLUSH_CHUNKS chunks; the accumulators are added into OUT after each segment (see flush below).
+  const int r_begin = js * p.cps;
+  const int r_end = min(p.nchunks, r_begin + p.cps);
+  int c_begin = r_begin;
+  int c_end = min(r_end, c_begin + GP_FLUSH_CHUNKS);
 
   // row-side operands: registers for the whole pass
   f16x8 xb[MI][XP][KH];
@@ -154,14 +156,11 @@ __global__ __launch_bounds__(64 * W) void kmv_tile_f16_kernel(TileArgsH p) {
     const int ch = min(ch_target, c_end - 1);           // past the end: harmless reload of the last chunk
     const unsigned stage_off = (unsigned)((ch_target - c_begin) % NS) * (unsigned)(STAGE * 16);
 #pragma unroll
-    for (int x = 0; x < LPW; ++x) dma16(g_src[x] + (int64_t)ch * g_stride[x], g_lds[x] + stage_off);
-    if (vy_lane) dma16(reinterpret_cast<const u32x4*>(p.VY + (int64_t)ch * 32) + lane, vy_lds + stage_off);
+    for (int x = 0; x < LPW; ++x) dma16(g_src[x] + (int64_t)ch * g_stride[x], __builtin_amdgcn_readfirstlane(g_lds[x] + stage_off));
+    if (vy_lane) dma16(reinterpret_cast<const u32x4*>(p.VY + (int64_t)ch * 32) + lane, __builtin_amdgcn_readfirstlane(vy_lds + stage_off));
   };
   // vmcnt <= (DEPTH-1)*LPC: everything but the newest DEPTH-1 chunks has landed (loads retire in order)
   constexpr int WAIT_N = (DEPTH - 1) * LPC;
-
-#pragma unroll
-  for (int d0 = 0; d0 < DEPTH; ++d0) issue_chunk(c_begin + d0);
 
   // distance chain of one chunk: S[j][i] = XA_j . XB_i, with the pair (i, i) forced to r^2 = 0
   auto distance = [&](int ch, f32x16 (&S)[MI]) {
@@ -237,14 +236,20 @@ __global__ __launch_bounds__(64 * W) void kmv_tile_f16_kernel(TileArgsH p) {
   };
 
   f32x16 S0[MI], S1[MI];             // S of the chunk being consumed / of the next chunk, roles alternate
-  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(WAIT_N) : "memory");
-  __syncthreads();
-  distance(c_begin, S0);
   unsigned ph[4], pl[4];             // packed A operands of the group about to be contracted
   f32x4 vy0[2];                      // y values of k-step 0 of the chunk being consumed
-  load_vy(lds[0], 0, vy0);
+  // fills the pipelines at the start of a segment: DEPTH chunks in flight, S and the first phi group of
+  // the first chunk ready
+  auto segment_prologue = [&]() {
 #pragma unroll
-  for (int e2 = 0; e2 < 4; ++e2) phi_pair(S0[0], 0, e2, vy0, accv[0], ph[e2], pl[e2]);
+    for (int d0 = 0; d0 < DEPTH; ++d0) issue_chunk(c_begin + d0);
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(WAIT_N) : "memory");
+    __syncthreads();
+    distance(c_begin, S0);
+    load_vy(lds[0], 0, vy0);
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) phi_pair(S0[0], 0, e2, vy0, accv[0], ph[e2], pl[e2]);
+  };
 
   // one chunk: S = its distances (ready), Sn = receives the next chunk's
   auto chunk_body = [&](int ch, f32x16 (&S)[MI], f32x16 (&Sn)[MI]) {
@@ -305,50 +310,71 @@ __global__ __launch_bounds__(64 * W) void kmv_tile_f16_kernel(TileArgsH p) {
     vy0[1] = vy0n[1];
   };
 
-  for (int ch = c_begin; ch < c_end; ch += 2) {
-    chunk_body(ch, S0, S1);
-    if (ch + 1 < c_end) chunk_body(ch + 1, S1, S0);
-  }
-
-  // no LDS write of this workgroup may still be in flight when its LDS is released
-  asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
-  // epilogue: undo the power-of-two scalings, multiply by a^2, add the noise term once, store
+  // Writes what the accumulators hold to OUT (first: stores, adds the noise term once; later: adds to
+  // what is there) and clears them.  Undoes the power-of-two scalings and multiplies by a^2.
   float* out = p.OUT + (int64_t)js * p.split_stride;
-  const bool noise = p.add_noise && p.js0 + js == 0;
-  const bool accumulate = p.accumulate != 0;
   float oscale[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     const int c = min(li + 32 * nt, p.ncols - 1);
     oscale[nt] = p.a2 * ldexpf(1.0f, column_exponent(p.colmax[p.col0 + c]) - V_TOP - PHI_SHIFT);
   }
+  auto flush = [&](bool first) {
+    const bool noise = first && p.add_noise && js == 0;
+    // an opaque zero keeps the address arithmetic of the flush inside it: hoisted out of the segment
+    // loop it would hold dozens of registers across the main loop
+    int zero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(zero));
 #pragma unroll
-  for (int m = 0; m < MI; ++m) {
-    const int64_t ibase = (int64_t)(sub0 + m) * 32;
+    for (int m = 0; m < MI; ++m) {
+      const int64_t ibase = (int64_t)(sub0 + m) * 32 + zero;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const int c = li + 32 * nt;
+      for (int nt = 0; nt < NT; ++nt) {
+        const int c = li + 32 * nt;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t i = ibase + 8 * (r >> 2) + 4 * h + (r & 3);
-        if (i < p.n && c < p.ncols) {
-          float v = oscale[nt] * acc[m][nt][r];
-          if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.col0 + c], v);
-          if (accumulate) v += out[i * p.ldo + p.col0 + c];
-          out[i * p.ldo + p.col0 + c] = v;
+        for (int r = 0; r < 16; ++r) {
+          const int64_t i = ibase + 8 * (r >> 2) + 4 * h + (r & 3);
+          if (i < p.n && c < p.ncols) {
+            float v = oscale[nt] * acc[m][nt][r];
+            if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.col0 + c], v);
+            if (!first) v += out[i * p.ldo + p.col0 + c];
+            out[i * p.ldo + p.col0 + c] = v;
+          }
+          acc[m][nt][r] = 0.0f;
         }
       }
-    }
-    if (p.vcol >= 0) {
-      const float tot = accv[m] + __shfl_xor(accv[m], 32);
-      const int64_t i = ibase + li;
-      if (h == 0 && i < p.n) {
-        float v = p.a2 * ldexpf(1.0f, -PHI_SHIFT) * tot;
-        if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.vcol], v);
-        if (accumulate) v += out[i * p.ldo + p.vcol];
-        out[i * p.ldo + p.vcol] = v;
+      if (p.vcol >= 0) {
+        const float tot = accv[m] + __shfl_xor(accv[m], 32);
+        const int64_t i = ibase + li;
+        if (h == 0 && i < p.n) {
+          float v = p.a2 * ldexpf(1.0f, -PHI_SHIFT) * tot;
+          if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.vcol], v);
+          if (!first) v += out[i * p.ldo + p.vcol];
+          out[i * p.ldo + p.vcol] = v;
+        }
+        accv[m] = 0.0f;
       }
     }
+  };
+
+  // Rounding error of an fp32 accumulator grows with the length of its chain of partial sums, so the
+  // accumulators are added into OUT after every segment (the running sum then sees one addition per
+  // segment).  The same threads read and write the same elements: no race, fixed order.
+  bool first = true;
+  for (;;) {
+    segment_prologue();
+    for (int ch = c_begin; ch < c_end; ch += 2) {
+      chunk_body(ch, S0, S1);
+      if (ch + 1 < c_end) chunk_body(ch + 1, S1, S0);
+    }
+    // no LDS write may be in flight, and no wave still reading, when the ring is refilled or released
+    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+    __syncthreads();
+    flush(first);
+    first = false;
+    if (c_end >= r_end) break;
+    c_begin = c_end;
+    c_end = min(r_end, c_begin + GP_FLUSH_CHUNKS);
   }
 }
 
@@ -510,18 +536,17 @@ KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx) {
   }
   pl.cps = (int)((chunks + JS - 1) / JS);
   pl.JS = (int)((chunks + pl.cps - 1) / pl.cps);
-  // Rounding error of the fp32 accumulators grows with the length of the chain of partial sums, so a
-  // long column range is cut into passes of at most GP_MAX_CPS chunks; each pass is its own launch
-  // over all row blocks and adds its result to OUT in launch order (deterministic, no scratch).
-  pl.passes = 1;
-  int max_cps = GP_MAX_CPS;
-  if (const char* e = getenv("GPWS_MAX_CPS")) max_cps = atoi(e) > 0 ? atoi(e) : max_cps;               // tuning aid
-  if (pl.JS == 1 && pl.cps > max_cps) {
-    pl.passes = (int)((chunks + max_cps - 1) / max_cps);
-    pl.cps = (int)((chunks + pl.passes - 1) / pl.passes);
-    pl.passes = (int)((chunks + pl.cps - 1) / pl.cps);
-  }
   return pl;
+}
+
+int gp_launch_colmax(gp_ctx* ctx, const float* dV, int64_t ldv, int t, unsigned* cm) {
+  GP_HIP(ctx, hipMemsetAsync(cm, 0, (size_t)t * sizeof(unsigned), ctx->stream));
+  int blocks = (int)((ctx->n * (int64_t)t + 4095) / 4096);
+  if (blocks > 4 * ctx->num_cu) blocks = 4 * ctx->num_cu;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(colmax_kernel, dim3(blocks), dim3(256), (size_t)t * sizeof(unsigned), ctx->stream, dV, ldv, ctx->n, t, cm);
+  GP_HIP(ctx, hipGetLastError());
+  return GP_OK;
 }
 
 size_t gp_kmv_f16_scratch_bytes(const gp_ctx* ctx, int t) {
@@ -544,13 +569,8 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
   const int nchunks = (int)((ctx->n + 31) / 32);
 
   if (!colmax_ready) {
-    unsigned* cm = (unsigned*)(w + L.off_colmax);
-    GP_HIP(ctx, hipMemsetAsync(cm, 0, (size_t)t * sizeof(unsigned), st));
-    int blocks = (int)((ctx->n * (int64_t)t + 4095) / 4096);
-    if (blocks > 4 * ctx->num_cu) blocks = 4 * ctx->num_cu;
-    if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(colmax_kernel, dim3(blocks), dim3(256), (size_t)t * sizeof(unsigned), st, dV, ldv, ctx->n, t, cm);
-    GP_HIP(ctx, hipGetLastError());
+    const int rc = gp_launch_colmax(ctx, dV, ldv, t, (unsigned*)(w + L.off_colmax));
+    if (rc < 0) return rc;
   }
 
   TileArgsH a;
@@ -570,8 +590,6 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
   a.nchunks = nchunks;
   a.JS = pl.JS;
   a.cps = pl.cps;
-  a.js0 = 0;
-  a.accumulate = 0;
   a.a2 = (float)(ctx->a * ctx->a);
   a.sigma2 = (float)(ctx->sigma * ctx->sigma);
   a.add_noise = add_noise;
@@ -595,17 +613,13 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
     vcol = -1;
     tileh_fn fn = pick_h(ctx->kernel, ctx->KH, ctx->XP, NT, pl.MI, pl.W);
     if (!fn) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: no fp16 kernel for KH=%d", ctx->KH);
-    for (int ps = 0; ps < pl.passes; ++ps) {
-      a.js0 = ps;
-      a.accumulate = ps > 0;
-      const bool prof = ctx->prof_on && ctx->prof_count < GP_PROF_MAX;
-      if (prof) GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count], st));
-      hipLaunchKernelGGL(fn, grid, block, 0, st, a);
-      GP_HIP(ctx, hipGetLastError());
-      if (prof) {
-        GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count + 1], st));
-        ++ctx->prof_count;
-      }
+    const bool prof = ctx->prof_on && ctx->prof_count < GP_PROF_MAX;
+    if (prof) GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count], st));
+    hipLaunchKernelGGL(fn, grid, block, 0, st, a);
+    GP_HIP(ctx, hipGetLastError());
+    if (prof) {
+      GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count + 1], st));
+      ++ctx->prof_count;
     }
     c += a.ncols;
   }

@@ -342,6 +342,27 @@ def test_gradient_matches_oracle_at_same_V(name, kw):
         dv.close()
 
 
+@pytest.mark.parametrize("path", ["fp32", "f16x2", "f16x3"])
+@pytest.mark.parametrize("name,kw", [("config2", dict(n=1100)), ("config5", dict(n=1300, s=40)), ("config3", dict(n=900, s=5))])
+def test_gradient_every_product_path(monkeypatch, path, name, kw):
+    """Same bar on each arithmetic path of the tile pass, with badly scaled columns of V: the fp16
+    paths rescale the right-hand-side columns by powers of two and must not lose the small ones."""
+    monkeypatch.setenv("GPWS_PATH", path)
+    w = make(name, **kw)
+    dv = Dev(w.X, w.kind, w.ell, 0.8, 0.2)
+    try:
+        rng = np.random.default_rng(23)
+        V0 = rng.standard_normal(w.B.shape).astype(np.float32)
+        for colscale in (np.ones(w.s + 1), np.logspace(-6, 6, w.s + 1), np.full(w.s + 1, 1e-9)):
+            V = (V0 * colscale).astype(np.float32)
+            g = dv.grad(dv.to(V), dv.to(w.B))
+            ref = orc.mll_grad_hutchinson(w.X, w.ell, 0.8, 0.2, w.kind, w.B, V=V)
+            assert np.isfinite(g).all()
+            assert relerr(g, ref) <= GRAD_TOL, (path, g, ref)
+    finally:
+        dv.close()
+
+
 @pytest.mark.parametrize("name,kw", [("config1", dict()), ("config2", dict(n=2000))])
 def test_gradient_end_to_end_after_solve(name, kw):
     """Solve tightly on the GPU, then compare the gradient with the oracle's Cholesky-based
