@@ -22,7 +22,6 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 namespace {
 
 constexpr float LOG2E = 1.4426950408889634f;
-constexpr unsigned HI_MASK = 0xFFFFE000u;   // sign, exponent, top 10 mantissa bits: exact in fp16
 constexpr int C_TOP = 7;                    // max |C'_c| in [2^6, 2^7)
 constexpr int W_TOP = 13;                   // alpha sum_c max|A_c| max|C_c| <= 2^13, so |W' psi| <= 3 2^13 < 2^15
 constexpr int GRAD_TBLOCK_H = 80;           // right-hand-side columns per tile pass (5 k-steps of 16)
@@ -47,6 +46,15 @@ struct GradArgsH {
 };
 
 __device__ __forceinline__ f16x8 as_f16x8(u32x4 v) { return __builtin_bit_cast(f16x8, v); }
+
+// x - (float)half H of pk, one v_fma_mix_f32 (source 0 read as the fp16 half, sources 1 and 2 as fp32)
+template <int H>
+__device__ __forceinline__ float minus_half(unsigned pk, float x) {
+  float r;
+  if (H == 0) asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(pk), "v"(x));
+  else asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(pk), "v"(x));
+  return r;
+}
 
 template <int KIND, int KH, int XP, int KT, int NT>
 __global__ __launch_bounds__(256) void grad_tile_f16_kernel(GradArgsH p) {
@@ -229,7 +237,7 @@ __global__ __launch_bounds__(256) void grad_tile_f16_kernel(GradArgsH p) {
       u32x4 gh, gl;
 #pragma unroll
       for (int e2 = 0; e2 < 4; ++e2) {
-        float fh[2], fl[2];
+        float g[2];
 #pragma unroll
         for (int z = 0; z < 2; ++z) {
           const int r = 8 * mh + 2 * e2 + z;
@@ -238,18 +246,18 @@ __global__ __launch_bounds__(256) void grad_tile_f16_kernel(GradArgsH p) {
             psi = __builtin_amdgcn_exp2f(S[r]);                 // S = -log2(e)/2 r^2
             kval = psi;
           } else {
-            const float u = __builtin_amdgcn_sqrtf(fmaxf(S[r], 0.0f));   // S = 3 r^2
+            // S = 3 r^2; rounding-level negatives are mirrored (free source modifier), (i, i) is exactly 0
+            const float u = __builtin_amdgcn_sqrtf(__builtin_fabsf(S[r]));
             const float e = __builtin_amdgcn_exp2f(-LOG2E * u);
             psi = 3.0f * e;
             kval = fmaf(u, e, e);
           }
-          const float g = Wc[r] * psi;
+          g[z] = Wc[r] * psi;
           accv = fmaf(Wc[r], kval, accv);
-          fh[z] = __uint_as_float(__float_as_uint(g) & HI_MASK);
-          fl[z] = g - fh[z];
         }
-        gh[e2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(fh[0], fh[1]));
-        gl[e2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(fl[0], fl[1]));
+        // hi = g truncated to fp16, lo = g - hi read from the packed halves by the mixed-precision FMA
+        gh[e2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(g[0], g[1]));
+        gl[e2] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(minus_half<0>(gh[e2], g[0]), minus_half<1>(gh[e2], g[1])));
       }
       const f16x8 ah = as_f16x8(gh), al = as_f16x8(gl);
 #pragma unroll

@@ -10,7 +10,7 @@
 //
 // Per 32x32 tile of pairs (j, i), one wavefront:
 //   1. S[j][i] = XA_j . XB_i     3 (or 6) MFMAs per 16 components      (= g r^2_ij [+ 15 for SE])
-//   2. phi' = 2^15 phi(S)        VALU; hi = phi' & 0xFFFFE000, lo = phi' - hi; packed to fp16 pairs
+//   2. phi' = 2^15 phi(S)        VALU; hi = phi' truncated to fp16, lo = phi' - hi; packed to fp16 pairs
 //   3. OUT_i += phi'[i][j] V'_j  2 k-steps x NT x 3 MFMAs; V' = V scaled per column by a power of two
 //                                so that max |V'_c| is in [2^13, 2^14), pre-split and pre-packed
 // The accumulator layout of step 1 (lane = i, register r <-> j = 8(r/4) + 4(lane/32) + r%4) gives each lane
@@ -61,6 +61,15 @@ struct TileArgsH {
 };
 
 __device__ __forceinline__ f16x8 as_f16x8(u32x4 v) { return __builtin_bit_cast(f16x8, v); }
+
+// x - (float)half H of pk, one v_fma_mix_f32 (source 0 read as the fp16 half, sources 1 and 2 as fp32)
+template <int H>
+__device__ __forceinline__ float minus_half(unsigned pk, float x) {
+  float r;
+  if (H == 0) asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(pk), "v"(x));
+  else asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(pk), "v"(x));
+  return r;
+}
 
 // W wavefronts per workgroup: every workgroup streams all of V' and XA through its LDS, so the
 // L2-to-LDS traffic of a launch is inversely proportional to the rows a workgroup owns (32 MI W).
@@ -211,7 +220,7 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 
   // phi and its split for values 2 e2, 2 e2 + 1 of group (mh, m); vy = the lane's y values for that mh
   auto phi_pair = [&](const f32x16& Sv, int mh, int e2, const f32x4 (&vy)[2], float& av, unsigned& oh, unsigned& ol) {
-    float f[2], fh[2], fl[2];
+    float f[2];
 #pragma unroll
     for (int z = 0; z < 2; ++z) {
       const int e = 2 * e2 + z;
@@ -219,16 +228,18 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) 
       if (KIND == GP_SE_ARD) {
         f[z] = __builtin_amdgcn_exp2f(sv);                 // sv = -log2(e)/2 r^2 + 15
       } else {
-        const float u = __builtin_amdgcn_sqrtf(fmaxf(sv, 0.0f));        // sv = 3 r^2
+        // sv = 3 r^2; a rounding-level negative value is mirrored instead of clamped (|.| is a free
+        // source modifier), the pair (i, i) was set to exactly 0 above
+        const float u = __builtin_amdgcn_sqrtf(__builtin_fabsf(sv));
         const float ex = __builtin_amdgcn_exp2f(fmaf(u, -LOG2E, (float)PHI_SHIFT));
         f[z] = fmaf(u, ex, ex);
       }
       av = fmaf(f[z], vy[e >> 2][e & 3], av);
-      fh[z] = __uint_as_float(__float_as_uint(f[z]) & HI_MASK);
-      fl[z] = f[z] - fh[z];
     }
-    oh = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(fh[0], fh[1]));
-    ol = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(fl[0], fl[1]));
+    // hi = f truncated to fp16 (both values in one conversion), lo = f - hi taken straight from the
+    // packed halves by the mixed-precision FMA, so the split costs two instructions per value
+    oh = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(f[0], f[1]));
+    ol = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(minus_half<0>(oh, f[0]), minus_half<1>(oh, f[1])));
   };
   auto load_vy = [&](const u32x4* s, int mh, f32x4 (&vy)[2]) {
 #pragma unroll
