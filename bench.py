@@ -24,7 +24,7 @@ FP16_PEAK_TFLOPS = 2500.0  # MI355X dense FP16 matrix peak
 PATH_NAMES = {0: "fp32", 1: "f16x2", 2: "f16x3"}
 # HBM bytes per launch of the tile kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script (summaries under profiles/), keyed by (workload, n); filled in from those runs, not measured live
-TRAFFIC = {("config2", 16384): 43.5e6, ("config5", 2000000): 3.79e9}
+TRAFFIC = {("config2", 16384): 43.4e6, ("config5", 2000000): 742e9}
 
 
 def kmv_flops(n, d, t, kind):
