@@ -236,9 +236,10 @@ __global__ __launch_bounds__(256) void grad_reduce_kernel(const float* __restric
                                                           double* __restrict__ part /* [grid][d+2] */) {
   extern __shared__ double sh[];   // [256]
   const int nq = 2 * d + 2;
-  // thread <-> (row, component): consecutive threads take consecutive components of a row
-  const int ncomp = d + 2;
-  double* mypart = part + (int64_t)blockIdx.x * ncomp;
+  // thread <-> (row, component): consecutive threads take consecutive components of a row;
+  // components 0..d-1 are the lengthscales, d the amplitude
+  const int ncomp = d + 1;
+  double* mypart = part + (int64_t)blockIdx.x * (d + 2);
   for (int comp0 = 0; comp0 < ncomp; comp0 += 256) {
     const int comp = comp0 + (threadIdx.x % min(256, ncomp - comp0));
     const int lanes_per_row = min(256, ncomp - comp0);
@@ -249,21 +250,18 @@ __global__ __launch_bounds__(256) void grad_reduce_kernel(const float* __restric
       for (int64_t i = (int64_t)blockIdx.x * rows_per_step + rsub; i < n; i += (int64_t)gridDim.x * rows_per_step) {
         if (comp < d) {
           float y = 0.f, t2 = 0.f, t1 = 0.f;
+#pragma unroll 4
           for (int k = 0; k < JS; ++k) {
             const float* o = OUT + (int64_t)k * split_stride + i * ldo;
             y += o[comp]; t2 += o[d + comp]; t1 += o[2 * d];
           }
           const double x = (double)Xs[i * d + comp];
           s += x * x * (double)t1 + (double)t2 - 2.0 * x * (double)y;
-        } else if (comp == d) {
+        } else {
           float ga = 0.f;
+#pragma unroll 4
           for (int k = 0; k < JS; ++k) ga += OUT[(int64_t)k * split_stride + i * ldo + nq - 1];
           s += (double)ga;
-        } else if (first_block) {
-          // sum_i w_ii = sum_i A_i . C_i over all t columns
-          double w = (double)half_w * (double)V[i * ldv] * (double)V[i * ldv];
-          for (int c = 1; c < t; ++c) w += (double)probe_w * (double)V[i * ldv + c] * (double)B[i * ldb + c];
-          s += w;
         }
       }
     }
@@ -277,6 +275,30 @@ __global__ __launch_bounds__(256) void grad_reduce_kernel(const float* __restric
       mypart[comp] = tot;
     }
   }
+  // noise component: sum_i w_ii = sum_i A_i . C_i over all t columns, the workgroup's threads sharing
+  // the elements of 8 rows at a time; fixed-order tree at the end
+  double w = 0.0;
+  if (first_block) {
+    constexpr int RPS = 8;
+    for (int64_t base = (int64_t)blockIdx.x * RPS; base < n; base += (int64_t)gridDim.x * RPS) {
+      const int rows = (int)min((int64_t)RPS, n - base);
+      const int cnt = rows * t;
+      for (int e = threadIdx.x; e < cnt; e += 256) {
+        const int r = e / t, c = e - r * t;
+        const int64_t i = base + r;
+        const double v = (double)V[i * ldv + c];
+        w += c == 0 ? (double)half_w * v * v : (double)probe_w * v * (double)B[i * ldb + c];
+      }
+    }
+  }
+  __syncthreads();
+  sh[threadIdx.x] = w;
+  __syncthreads();
+  for (int k = 128; k > 0; k >>= 1) {
+    if ((int)threadIdx.x < k) sh[threadIdx.x] += sh[threadIdx.x + k];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) mypart[d + 1] = sh[0];
 }
 
 // acc[comp] += sum over workgroup partials; one workgroup per component, fixed-order tree
@@ -364,7 +386,15 @@ int gp_grad_run(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int6
   JS = (int)((chunks + cps - 1) / cps);
 
   const int KTmax = t <= 18 ? 9 : 33;
-  const int G = 2 * ctx->num_cu;
+  // workgroups of the fp64 reduction: one step of 256 / (d + 2) rows each when n allows, so that
+  // enough loads are in flight (the kernel is latency-bound at small n)
+  int G;
+  {
+    const int per_step = 256 / (d + 2 < 256 ? d + 2 : 256);
+    const int64_t want = (n + per_step - 1) / per_step;
+    G = (int)(want < 8 * ctx->num_cu ? want : 8 * ctx->num_cu);
+    if (G < 1) G = 1;
+  }
   const size_t q_bytes = align_up((size_t)n * ldq * sizeof(float), 256);
   const size_t op_bytes = align_up(((size_t)(ctx->n_pad / 32) * KTmax * 64 + GP_PACK_SLACK) * sizeof(float), 256);
   const size_t out_bytes = align_up((size_t)JS * n * nq * sizeof(float), 256);

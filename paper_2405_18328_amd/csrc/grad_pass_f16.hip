@@ -463,7 +463,15 @@ int gp_grad_run_f16(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, 
   const int cps = (int)((chunks + JS - 1) / JS);
   JS = (int)((chunks + cps - 1) / cps);
   const int KTmax = t <= 32 ? 2 : 5;
-  const int G = 2 * ctx->num_cu;
+  // workgroups of the fp64 reduction: one step of 256 / (d + 2) rows each when n allows, so that
+  // enough loads are in flight (the kernel is latency-bound at small n)
+  int G;
+  {
+    const int per_step = 256 / (d + 2 < 256 ? d + 2 : 256);
+    const int64_t want = (n + per_step - 1) / per_step;
+    G = (int)(want < 8 * ctx->num_cu ? want : 8 * ctx->num_cu);
+    if (G < 1) G = 1;
+  }
   const size_t op_bytes = align_up((size_t)chunks_pad * 2 * KTmax * 64 * 16, 256);
   const size_t q_bytes = align_up((size_t)chunks * 2 * 2 * 2 * 64 * 16, 256);
   const size_t out_bytes = align_up((size_t)JS * n * nq * sizeof(float), 256);

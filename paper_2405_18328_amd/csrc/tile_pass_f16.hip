@@ -393,17 +393,31 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 // colmax[c] = max_i |V_ic| as a bit pattern (non-negative floats order like unsigned ints)
 __global__ __launch_bounds__(256) void colmax_kernel(const float* __restrict__ V, int64_t ldv, int64_t n, int t,
                                                      unsigned* __restrict__ colmax) {
+  // a thread keeps one column (per group of 256 columns) and walks rows: consecutive threads read
+  // consecutive columns of a row, the running maximum stays in a register
   extern __shared__ unsigned smax[];   // [t]
   for (int c = threadIdx.x; c < t; c += 256) smax[c] = 0u;
   __syncthreads();
   const int64_t rows_per_block = (n + gridDim.x - 1) / gridDim.x;
   const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
   const int64_t r1 = min(n, r0 + rows_per_block);
-  const int64_t cnt = (r1 > r0 ? r1 - r0 : 0) * t;
-  for (int64_t e = threadIdx.x; e < cnt; e += 256) {
-    const int64_t i = r0 + e / t;
-    const int c = (int)(e % t);
-    atomicMax(&smax[c], __float_as_uint(fabsf(V[i * ldv + c])));
+  const int tw = t < 256 ? t : 256;        // columns handled side by side
+  const int lanes = 256 / tw;              // rows handled side by side
+  const int cl = threadIdx.x % tw, rl = threadIdx.x / tw;
+  if (rl < lanes) {
+    for (int c = cl; c < t; c += tw) {
+      float m0 = 0.0f, m1 = 0.0f, m2 = 0.0f, m3 = 0.0f;
+      int64_t i = r0 + rl;
+      for (; i + 3 * lanes < r1; i += 4 * lanes) {
+        m0 = fmaxf(m0, fabsf(V[i * ldv + c]));
+        m1 = fmaxf(m1, fabsf(V[(i + lanes) * ldv + c]));
+        m2 = fmaxf(m2, fabsf(V[(i + 2 * lanes) * ldv + c]));
+        m3 = fmaxf(m3, fabsf(V[(i + 3 * lanes) * ldv + c]));
+      }
+      for (; i < r1; i += lanes) m0 = fmaxf(m0, fabsf(V[i * ldv + c]));
+      m0 = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
+      atomicMax(&smax[c], __float_as_uint(m0));
+    }
   }
   __syncthreads();
   for (int c = threadIdx.x; c < t; c += 256)
@@ -552,8 +566,9 @@ KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx) {
 
 int gp_launch_colmax(gp_ctx* ctx, const float* dV, int64_t ldv, int t, unsigned* cm) {
   GP_HIP(ctx, hipMemsetAsync(cm, 0, (size_t)t * sizeof(unsigned), ctx->stream));
-  int blocks = (int)((ctx->n * (int64_t)t + 4095) / 4096);
-  if (blocks > 4 * ctx->num_cu) blocks = 4 * ctx->num_cu;
+  // few workgroups: every one ends with t atomic maxima on the same t words
+  int blocks = (int)((ctx->n * (int64_t)t + 8191) / 8192);
+  if (blocks > 2 * ctx->num_cu) blocks = 2 * ctx->num_cu;
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(colmax_kernel, dim3(blocks), dim3(256), (size_t)t * sizeof(unsigned), ctx->stream, dV, ldv, ctx->n, t, cm);
   GP_HIP(ctx, hipGetLastError());
