@@ -133,6 +133,19 @@ int gp_mll_grad(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int6
                 double* h_grad);
 
 /*
+ * Cross-covariance product OUT = K(X*, X) V between m other inputs X* and the context's n
+ * inputs, for the current theta, matrix-free with the same tile pass as gp_kmv (Section 2,
+ * Eq. 1: with V = v_y = H^{-1} y, t = 1, this is the posterior mean at X*; with the columns
+ * of a solved batch it gives the data-dependent term of each posterior sample).
+ *   dXstar: device, m x d row-major fp32, 1 <= m <= 2^30; read during the call only.
+ *   dV: device, n x t, leading dimension ldv >= t.  dOut: device, m x t, ldo >= t; written.
+ * No noise term is added.  Synchronises the stream once (to read the largest scaled norm of
+ * X*, which together with the training inputs' selects the arithmetic of the product).
+ */
+int gp_predict(gp_ctx* ctx, const float* dXstar, int64_t m, const float* dV, int64_t ldv, int t, float* dOut,
+               int64_t ldo);
+
+/*
  * Instrumentation for roofline reports (not part of the method): while enabled,
  * every launch of the K V tile-pass kernel made through this context (by gp_kmv
  * or inside gp_cg_solve) is bracketed by a pair of HIP events on the context's

@@ -138,6 +138,12 @@ def kmv_rows(X, ell, a, kind, V, rows, sigma=None, col_block=32768):
     return out
 
 
+def cross_kmv(Xstar, X, ell, a, kind, V):
+    """k(X*, X) V, m x t.  With V = v_y = H^{-1} y this is the posterior mean at the
+    inputs X* (Section 2, Eq. 1); dense fp64, the definition."""
+    return kernel_cross(_f64(Xstar), _f64(X), ell, a, kind) @ _f64(V)
+
+
 def chol_solve(H, B):
     """V* = H^{-1} B via Cholesky and two triangular solves (Section 2)."""
     c, low = sla.cho_factor(_f64(H), lower=True)

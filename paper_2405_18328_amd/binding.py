@@ -28,7 +28,7 @@ GP_MAX_T = 1024
 LIB_PATH = os.environ.get("GPWS_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgpws.so")
 
 EXPORTS = ["gp_create", "gp_destroy", "gp_set_theta", "gp_kmv", "gp_workspace_bytes", "gp_cg_solve",
-           "gp_mll_grad", "gp_profile", "gp_profile_read", "gp_product_path", "gp_last_error"]
+           "gp_mll_grad", "gp_predict", "gp_profile", "gp_profile_read", "gp_product_path", "gp_last_error"]
 
 
 def _load():
@@ -45,6 +45,7 @@ def _load():
     lib.gp_cg_solve.argtypes = [p, p, i64, p, p, i64, i32, C.POINTER(C.c_float), i32, p, sz,
                                 C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_float)]
     lib.gp_mll_grad.argtypes = [p, p, i64, p, i64, i32, C.POINTER(dbl)]
+    lib.gp_predict.argtypes = [p, p, i64, p, i64, i32, p, i64]
     lib.gp_profile.argtypes = [p, i32]
     lib.gp_profile_read.argtypes = [p, C.POINTER(i32), C.POINTER(dbl)]
     lib.gp_product_path.argtypes = [p]
@@ -133,6 +134,10 @@ def gp_mll_grad(ctx, dV, ldv, dB, ldb, t, d):
     _check(ctx, _lib.gp_mll_grad(ctx, _ptr(dV), int(ldv), _ptr(dB), int(ldb), int(t),
                                  g.ctypes.data_as(C.POINTER(C.c_double))))
     return g
+
+
+def gp_predict(ctx, dXstar, m, dV, ldv, t, dOut, ldo):
+    return _check(ctx, _lib.gp_predict(ctx, _ptr(dXstar), int(m), _ptr(dV), int(ldv), int(t), _ptr(dOut), int(ldo)))
 
 
 def gp_profile(ctx, enable):

@@ -175,6 +175,24 @@ int gp_kmv(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_
   return gp_kmv_launch(ctx, dV, ldv, t, dOut, ldo, add_noise ? 1 : 0, ctx->dScratch, ctx->scratch_bytes, nullptr);
 }
 
+int gp_predict(gp_ctx* ctx, const float* dXstar, int64_t m, const float* dV, int64_t ldv, int t, float* dOut,
+               int64_t ldo) {
+  if (!ctx) return GP_ERR_ARG;
+  if (!ctx->theta_set) return gp_fail(ctx, GP_ERR_ARG, "gp_predict: gp_set_theta has not been called");
+  if (t < 1 || t > GP_MAX_T) return gp_fail(ctx, GP_ERR_ARG, "gp_predict: t = %d outside [1, %d]", t, GP_MAX_T);
+  if (m < 1 || m > ((int64_t)1 << 30)) return gp_fail(ctx, GP_ERR_ARG, "gp_predict: m = %lld outside [1, 2^30]", (long long)m);
+  if (!dXstar) return gp_fail(ctx, GP_ERR_ARG, "gp_predict: NULL dXstar");
+  int rc;
+  if ((rc = check_block(ctx, "gp_predict(dV)", dV, ldv, t)) < 0) return rc;
+  if ((rc = check_block(ctx, "gp_predict(dOut)", dOut, ldo, t)) < 0) return rc;
+  const size_t pack_bytes = gp_pack_rows_bytes(ctx, m);
+  const size_t kmv_bytes = (gp_kmv_rect_scratch_bytes(ctx, t, m) + 255) / 256 * 256;
+  if ((rc = gp_ensure_scratch(ctx, pack_bytes + kmv_bytes)) < 0) return rc;
+  KmvRows rows;
+  if ((rc = gp_pack_rows(ctx, dXstar, m, ctx->dScratch, &rows)) < 0) return rc;
+  return gp_kmv_launch(ctx, dV, ldv, t, dOut, ldo, 0, (char*)ctx->dScratch + pack_bytes, kmv_bytes, nullptr, &rows);
+}
+
 size_t gp_workspace_bytes(const gp_ctx* ctx, int t) {
   if (!ctx || t < 1 || t > GP_MAX_T) return 0;
   return gp_cg_workspace_bytes(ctx, t);

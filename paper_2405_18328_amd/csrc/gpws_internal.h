@@ -79,6 +79,15 @@ struct gp_ctx {
   char err[256];
 };
 
+// Row side of a rectangular product K(X*, X) V: m other points packed like the context's own rows
+// (same centring, lengthscales and scaling).  NULL everywhere below means the square product.
+struct KmvRows {
+  int64_t m;
+  const float* XB;        // fp32 packed row operands, [m_pad/32][KS][64]
+  const void* XBh[3];     // fp16 pieces, [m_pad/32][KH][64] 16-byte units
+  int path;               // GP_PATH_* to use (covers the norms of both point sets)
+};
+
 int gp_fail(gp_ctx* ctx, int code, const char* fmt, ...);
 #define GP_HIP(ctx, call)                                                              \
   do {                                                                                 \
@@ -93,6 +102,11 @@ int gp_ensure_scratch(gp_ctx* ctx, size_t bytes);
 // ---- prep_kernels.hip
 int gp_launch_column_means(gp_ctx* ctx);
 int gp_launch_pack(gp_ctx* ctx);
+// packs m other points (device, row-major m x d) against the context's centring and theta into
+// caller-provided buffers sized by gp_pack_rows_bytes; fills rows (path from the larger of the two
+// sets' scaled norms; synchronises the stream to read that norm back)
+size_t gp_pack_rows_bytes(const gp_ctx* ctx, int64_t m);
+int gp_pack_rows(gp_ctx* ctx, const float* dXstar, int64_t m, void* buf, KmvRows* rows);
 
 // ---- tile_pass.hip
 struct KmvPlan {
@@ -102,19 +116,23 @@ struct KmvPlan {
   int row_blocks;
   int cps;       // chunks per split
 };
-KmvPlan gp_plan_kmv(const gp_ctx* ctx);
-size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t);   // worst case over the paths gp_set_theta may choose
+KmvPlan gp_plan_kmv(const gp_ctx* ctx, int64_t rows);
+size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t);   // square product, worst case over the paths gp_set_theta may choose
+size_t gp_kmv_rect_scratch_bytes(const gp_ctx* ctx, int t, int64_t rows);
 // OUT = K V (+ sigma^2 V).  colmax: optional device array of t bit patterns of max_i |V_ic| that the
 // caller already holds (the split-fp16 path then skips its own reduction over V); NULL otherwise.
+// rows: NULL, or the row side of a rectangular product (add_noise must then be 0).
 int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
-                  int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax);
+                  int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax,
+                  const KmvRows* rows = nullptr);
 
 // ---- tile_pass_f16.hip
 int gp_kh_bucket(int d, int kernel);
-KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx);
-size_t gp_kmv_f16_scratch_bytes(const gp_ctx* ctx, int t);
+KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx, int64_t rows);
+size_t gp_kmv_f16_scratch_bytes(const gp_ctx* ctx, int t, int64_t rows);
 int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
-                      int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax);
+                      int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax,
+                      const KmvRows* rows);
 
 // colmax[c] = bit pattern of max_i |V_ic| for c < t (cleared first); stream-ordered
 int gp_launch_colmax(gp_ctx* ctx, const float* dV, int64_t ldv, int t, unsigned* colmax);

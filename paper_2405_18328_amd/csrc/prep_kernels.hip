@@ -2,6 +2,8 @@
 // the packed, pre-scaled operand arrays the tile kernels read (layout in
 // gpws_internal.h).  Distances are translation invariant, so centring only
 // shrinks |xs|^2 and with it the rounding of the dot-form r^2.
+#include <cstring>
+
 #include "gpws_internal.h"
 
 namespace {
@@ -134,5 +136,64 @@ int gp_launch_pack(gp_ctx* ctx) {
                      ctx->kernel == GP_SE_ARD ? 1 : 0, gamma, (u32x4*)ctx->dXAh[0], (u32x4*)ctx->dXAh[1],
                      (u32x4*)ctx->dXAh[2], (u32x4*)ctx->dXBh[0], (u32x4*)ctx->dXBh[1], (u32x4*)ctx->dXBh[2]);
   GP_HIP(ctx, hipGetLastError());
+  return GP_OK;
+}
+
+namespace {
+inline size_t up256(size_t v) { return (v + 255) / 256 * 256; }
+
+struct RowBufs {
+  size_t off_xa, off_xb, off_xs, off_norm, off_max, off_a[3], off_b[3], total;
+};
+RowBufs row_bufs(const gp_ctx* ctx, int64_t m) {
+  RowBufs L;
+  const int64_t m_pad = (m + GP_ROW_ALIGN - 1) / GP_ROW_ALIGN * GP_ROW_ALIGN;
+  const size_t p32 = up256(((size_t)(m_pad / 32) * ctx->KS * 64 + GP_PACK_SLACK) * sizeof(float));
+  const size_t p16 = up256((size_t)(m_pad / 32) * ctx->KH * 64 * 16);
+  size_t o = 0;
+  L.off_xa = o; o += p32;
+  L.off_xb = o; o += p32;
+  L.off_xs = o; o += up256((size_t)m * ctx->d * sizeof(float));
+  L.off_norm = o; o += up256((size_t)m_pad * sizeof(float));
+  L.off_max = o; o += 256;
+  for (int pc = 0; pc < 3; ++pc) { L.off_a[pc] = o; o += p16; }
+  for (int pc = 0; pc < 3; ++pc) { L.off_b[pc] = o; o += p16; }
+  L.total = o;
+  return L;
+}
+}  // namespace
+
+size_t gp_pack_rows_bytes(const gp_ctx* ctx, int64_t m) { return row_bufs(ctx, m).total; }
+
+int gp_pack_rows(gp_ctx* ctx, const float* dXstar, int64_t m, void* buf, KmvRows* rows) {
+  const RowBufs L = row_bufs(ctx, m);
+  char* w = (char*)buf;
+  const int64_t m_pad = (m + GP_ROW_ALIGN - 1) / GP_ROW_ALIGN * GP_ROW_ALIGN;
+  const float gamma = ctx->kernel == GP_SE_ARD ? (float)(-0.5 * 1.4426950408889634) : 3.0f;
+  unsigned* dmax = (unsigned*)(w + L.off_max);
+  GP_HIP(ctx, hipMemsetAsync(dmax, 0, sizeof(unsigned), ctx->stream));
+  hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((m_pad + 255) / 256)), dim3(256), 0, ctx->stream, dXstar, m, m_pad,
+                     ctx->d, ctx->KS, (const double*)ctx->dMean, (const double*)ctx->dTheta, gamma,
+                     (float*)(w + L.off_xa), (float*)(w + L.off_xb), (float*)(w + L.off_xs), (float*)(w + L.off_norm), dmax);
+  GP_HIP(ctx, hipGetLastError());
+  const int64_t units = (m_pad / 32) * ctx->KH * 64;
+  hipLaunchKernelGGL(pack_f16_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, ctx->stream,
+                     (const float*)(w + L.off_xs), (const float*)(w + L.off_norm), m, m_pad, ctx->d, ctx->KH,
+                     ctx->kernel == GP_SE_ARD ? 1 : 0, gamma, (u32x4*)(w + L.off_a[0]), (u32x4*)(w + L.off_a[1]),
+                     (u32x4*)(w + L.off_a[2]), (u32x4*)(w + L.off_b[0]), (u32x4*)(w + L.off_b[1]), (u32x4*)(w + L.off_b[2]));
+  GP_HIP(ctx, hipGetLastError());
+  // the product path must cover the scaled norms of both point sets
+  unsigned* hmax = (unsigned*)ctx->hPinned;
+  GP_HIP(ctx, hipMemcpyAsync(hmax, dmax, sizeof(unsigned), hipMemcpyDeviceToHost, ctx->stream));
+  GP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  float mx;
+  memcpy(&mx, hmax, sizeof(float));
+  if (ctx->max_norm > mx) mx = ctx->max_norm;
+  int path = mx <= GP_NORM_X2_MAX ? GP_PATH_F16X2 : (mx <= GP_NORM_X3_MAX ? GP_PATH_F16X3 : GP_PATH_FP32);
+  if (ctx->path_forced >= 0 && !(ctx->path_forced != GP_PATH_FP32 && mx > GP_NORM_X3_MAX)) path = ctx->path_forced;
+  rows->m = m;
+  rows->XB = (const float*)(w + L.off_xb);
+  for (int pc = 0; pc < 3; ++pc) rows->XBh[pc] = w + L.off_b[pc];
+  rows->path = path;
   return GP_OK;
 }

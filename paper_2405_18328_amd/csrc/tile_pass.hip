@@ -25,7 +25,9 @@ struct TileArgs {
   float* OUT;
   int64_t ldo;
   int64_t split_stride;   // elements between consecutive split partials
-  int64_t n;
+  int64_t n;              // points on the column side (the context's n)
+  int64_t nrows;          // rows of the output (n, or m for a rectangular product)
+  int diag;               // square product: the pair (i, i) gets r^2 = 0 exactly
   int nchunks;            // ceil(n / 32)
   int col0;               // first column of V on the MFMA
   int ncols;              // MFMA columns in this pass (<= 32*NT)
@@ -151,7 +153,7 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_kernel(TileArgs p) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int64_t i = ibase + 8 * (r >> 2) + 4 * h + (r & 3);
-          if (i < p.n && c < p.ncols) {
+          if (i < p.nrows && c < p.ncols) {
             float v = p.a2 * acc[m][nt][r];
             if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.col0 + c], v);
             if (!first) v += out[i * p.ldo + p.col0 + c];
@@ -163,7 +165,7 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_kernel(TileArgs p) {
       if (p.vcol >= 0) {
         const float tot = accv[m] + __shfl_xor(accv[m], 32);
         const int64_t i = ibase + li;
-        if (h == 0 && i < p.n) {
+        if (h == 0 && i < p.nrows) {
           float v = p.a2 * tot;
           if (noise) v = fmaf(p.sigma2, p.V[i * p.ldv + p.vcol], v);
           if (!first) v += out[i * p.ldo + p.vcol];
@@ -200,7 +202,7 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_kernel(TileArgs p) {
     // the pair (i, i): r^2 is exactly zero
 #pragma unroll
     for (int m = 0; m < MI; ++m) {
-      if (ch == sub0 + m) {
+      if (p.diag && ch == sub0 + m) {
 #pragma unroll
         for (int r = 0; r < 16; ++r)
           if (8 * (r >> 2) + 4 * h + (r & 3) == li) S[m][r] = 0.0f;
@@ -282,13 +284,13 @@ int gp_ks_bucket(int d) {
   return -1;
 }
 
-KmvPlan gp_plan_kmv(const gp_ctx* ctx) {
+KmvPlan gp_plan_kmv(const gp_ctx* ctx, int64_t rows) {
   KmvPlan pl;
   const int64_t chunks = (ctx->n + 31) / 32;
   // two sub-tiles per wave once there are enough rows to fill the chip that way
-  pl.MI = (ctx->KS <= 24 && ctx->n >= 8192) ? 2 : 1;
+  pl.MI = (ctx->KS <= 24 && rows >= 8192) ? 2 : 1;
   const int rows_per_wg = 32 * GP_WAVES * pl.MI;
-  pl.row_blocks = (int)((ctx->n + rows_per_wg - 1) / rows_per_wg);
+  pl.row_blocks = (int)((rows + rows_per_wg - 1) / rows_per_wg);
   const int target = 2 * ctx->num_cu;
   int JS = 1;
   if (pl.row_blocks < target) {
@@ -302,31 +304,37 @@ KmvPlan gp_plan_kmv(const gp_ctx* ctx) {
   return pl;
 }
 
-size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t) {
-  KmvPlan pl = gp_plan_kmv(ctx);
-  const size_t fp32_bytes = pl.JS <= 1 ? 0 : (size_t)pl.JS * (size_t)ctx->n * (size_t)t * sizeof(float);
-  const size_t f16_bytes = gp_kmv_f16_scratch_bytes(ctx, t);
+size_t gp_kmv_rect_scratch_bytes(const gp_ctx* ctx, int t, int64_t rows) {
+  KmvPlan pl = gp_plan_kmv(ctx, rows);
+  const size_t fp32_bytes = pl.JS <= 1 ? 0 : (size_t)pl.JS * (size_t)rows * (size_t)t * sizeof(float);
+  const size_t f16_bytes = gp_kmv_f16_scratch_bytes(ctx, t, rows);
   return fp32_bytes > f16_bytes ? fp32_bytes : f16_bytes;
 }
 
+size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t) { return gp_kmv_rect_scratch_bytes(ctx, t, ctx->n); }
+
 int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
-                  int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax) {
-  if (ctx->path != GP_PATH_FP32)
-    return gp_kmv_launch_f16(ctx, dV, ldv, t, dOut, ldo, add_noise, scratch, scratch_bytes, colmax);
-  const KmvPlan pl = gp_plan_kmv(ctx);
+                  int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax, const KmvRows* rows) {
+  if (rows && add_noise) return gp_fail(ctx, GP_ERR_ARG, "rectangular product with a noise term");
+  if ((rows ? rows->path : ctx->path) != GP_PATH_FP32)
+    return gp_kmv_launch_f16(ctx, dV, ldv, t, dOut, ldo, add_noise, scratch, scratch_bytes, colmax, rows);
+  const int64_t nrows = rows ? rows->m : ctx->n;
+  const KmvPlan pl = gp_plan_kmv(ctx, nrows);
   const bool split = pl.JS > 1;
-  if (split && scratch_bytes < (size_t)pl.JS * (size_t)ctx->n * (size_t)t * sizeof(float))
+  if (split && scratch_bytes < (size_t)pl.JS * (size_t)nrows * (size_t)t * sizeof(float))
     return gp_fail(ctx, GP_ERR_WORKSPACE, "gp_kmv: scratch too small for %d column splits", pl.JS);
 
   TileArgs a;
   a.XA = ctx->dXA;
-  a.XB = ctx->dXB;
+  a.XB = rows ? rows->XB : ctx->dXB;
   a.V = dV;
   a.ldv = ldv;
   a.OUT = split ? (float*)scratch : dOut;
   a.ldo = split ? t : ldo;
-  a.split_stride = split ? ctx->n * (int64_t)t : 0;
+  a.split_stride = split ? nrows * (int64_t)t : 0;
   a.n = ctx->n;
+  a.nrows = nrows;
+  a.diag = rows ? 0 : 1;
   a.nchunks = (int)((ctx->n + 31) / 32);
   a.JS = pl.JS;
   a.cps = pl.cps;
@@ -359,11 +367,11 @@ int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut,
     c += a.ncols;
   }
   if (split) {
-    const int64_t total = ctx->n * (int64_t)t;
+    const int64_t total = nrows * (int64_t)t;
     int blocks = (int)((total + 255) / 256);
     if (blocks > 4 * ctx->num_cu) blocks = 4 * ctx->num_cu;
     hipLaunchKernelGGL(kmv_reduce_kernel, dim3(blocks), dim3(256), 0, ctx->stream, (const float*)scratch,
-                       a.split_stride, pl.JS, ctx->n, t, dOut, ldo);
+                       a.split_stride, pl.JS, nrows, t, dOut, ldo);
     GP_HIP(ctx, hipGetLastError());
   }
   return GP_OK;

@@ -52,8 +52,9 @@ struct TileArgsH {
   float* OUT;
   int64_t ldo;
   int64_t split_stride;
-  int64_t n;
-  int nchunks;
+  int64_t n;               // rows of the output (the context's n, or m for a rectangular product)
+  int diag;                // square product: the pair (i, i) gets r^2 = 0 exactly
+  int nchunks;             // column chunks (always the context's points)
   int col0, ncols, vcol;
   int JS, cps;             // column-range splits inside this launch, chunks per split
   float a2, sigma2;
@@ -198,7 +199,7 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     }
 #pragma unroll
     for (int m = 0; m < MI; ++m) {
-      if (ch == sub0 + m) {
+      if (p.diag && ch == sub0 + m) {
         const float s0 = KIND == GP_SE_ARD ? (float)PHI_SHIFT : 0.0f;
 #pragma unroll
         for (int r = 0; r < 16; ++r)
@@ -515,7 +516,7 @@ struct ScratchH {
   size_t off_colmax, off_vy, off_vp, off_part, total;
 };
 
-ScratchH scratch_layout(const gp_ctx* ctx, int t, int JS) {
+ScratchH scratch_layout(const gp_ctx* ctx, int t, int JS, int64_t rows) {
   ScratchH L;
   const int64_t nchunks = (ctx->n + 31) / 32;
   size_t o = 0;
@@ -523,7 +524,7 @@ ScratchH scratch_layout(const gp_ctx* ctx, int t, int JS) {
   L.off_vy = o; o += align_up((size_t)nchunks * 32 * sizeof(float), 256);
   L.off_vp = o; o += align_up((size_t)nchunks * 2 * 2 * 2 * 64 * 16, 256);      // NT = 2 images
   L.off_part = o;
-  if (JS > 1) o += align_up((size_t)JS * ctx->n * t * sizeof(float), 256);
+  if (JS > 1) o += align_up((size_t)JS * rows * t * sizeof(float), 256);
   L.total = o;
   return L;
 }
@@ -540,17 +541,17 @@ int gp_kh_bucket(int d, int kernel) {
   return -1;
 }
 
-KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx) {
+KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx, int64_t rows) {
   KmvPlan pl;
   const int64_t chunks = (ctx->n + 31) / 32;
   // two sub-tiles per wave halve the LDS operand traffic; past one k-step of distance operands the
   // second sub-tile no longer fits the register file without spills
-  pl.MI = (ctx->KH == 1 && ctx->n >= 8192) ? 2 : 1;
+  pl.MI = (ctx->KH == 1 && rows >= 8192) ? 2 : 1;
   if (const char* e = getenv("GPWS_MI")) pl.MI = (atoi(e) == 2 && ctx->KH <= 2) ? 2 : 1;   // tuning aid
   pl.W = 4;   // 8-wave workgroups halve the L2-to-LDS traffic but measured no faster on MI355X
   if (const char* e = getenv("GPWS_W")) pl.W = atoi(e) == 8 ? 8 : 4;                            // tuning aid
   const int rows_per_wg = 32 * pl.W * pl.MI;
-  pl.row_blocks = (int)((ctx->n + rows_per_wg - 1) / rows_per_wg);
+  pl.row_blocks = (int)((rows + rows_per_wg - 1) / rows_per_wg);
   const int target = 2 * ctx->num_cu;
   int JS = 1;
   if (pl.row_blocks < target) {
@@ -575,14 +576,16 @@ int gp_launch_colmax(gp_ctx* ctx, const float* dV, int64_t ldv, int t, unsigned*
   return GP_OK;
 }
 
-size_t gp_kmv_f16_scratch_bytes(const gp_ctx* ctx, int t) {
-  return scratch_layout(ctx, t, gp_plan_kmv_f16(ctx).JS).total;
+size_t gp_kmv_f16_scratch_bytes(const gp_ctx* ctx, int t, int64_t rows) {
+  return scratch_layout(ctx, t, gp_plan_kmv_f16(ctx, rows).JS, rows).total;
 }
 
 int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo, int add_noise,
-                      void* scratch, size_t scratch_bytes, const unsigned* colmax_ready) {
-  const KmvPlan pl = gp_plan_kmv_f16(ctx);
-  const ScratchH L = scratch_layout(ctx, t, pl.JS);
+                      void* scratch, size_t scratch_bytes, const unsigned* colmax_ready, const KmvRows* rows) {
+  const int64_t nrows = rows ? rows->m : ctx->n;
+  const int XP = rows ? (rows->path == GP_PATH_F16X3 ? 3 : 2) : ctx->XP;
+  const KmvPlan pl = gp_plan_kmv_f16(ctx, nrows);
+  const ScratchH L = scratch_layout(ctx, t, pl.JS, nrows);
   if (scratch_bytes < L.total || !scratch)
     return gp_fail(ctx, GP_ERR_WORKSPACE, "gp_kmv: scratch %zu < %zu bytes", scratch_bytes, L.total);
   hipStream_t st = ctx->stream;
@@ -602,7 +605,7 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
   TileArgsH a;
   for (int pc = 0; pc < 3; ++pc) {
     a.XA[pc] = (const u32x4*)ctx->dXAh[pc];
-    a.XB[pc] = (const u32x4*)ctx->dXBh[pc];
+    a.XB[pc] = (const u32x4*)(rows ? rows->XBh[pc] : ctx->dXBh[pc]);
   }
   a.VP = VP;
   a.VY = VY;
@@ -611,8 +614,9 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
   a.colmax = colmax;
   a.OUT = split ? part : dOut;
   a.ldo = split ? t : ldo;
-  a.split_stride = split ? ctx->n * (int64_t)t : 0;
-  a.n = ctx->n;
+  a.split_stride = split ? nrows * (int64_t)t : 0;
+  a.n = nrows;
+  a.diag = rows ? 0 : 1;
   a.nchunks = nchunks;
   a.JS = pl.JS;
   a.cps = pl.cps;
@@ -637,7 +641,7 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
       GP_HIP(ctx, hipGetLastError());
     }
     vcol = -1;
-    tileh_fn fn = pick_h(ctx->kernel, ctx->KH, ctx->XP, NT, pl.MI, pl.W);
+    tileh_fn fn = pick_h(ctx->kernel, ctx->KH, XP, NT, pl.MI, pl.W);
     if (!fn) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: no fp16 kernel for KH=%d", ctx->KH);
     const bool prof = ctx->prof_on && ctx->prof_count < GP_PROF_MAX;
     if (prof) GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count], st));
@@ -650,11 +654,11 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
     c += a.ncols;
   }
   if (split) {
-    const int64_t total = ctx->n * (int64_t)t;
+    const int64_t total = nrows * (int64_t)t;
     int blocks = (int)((total + 255) / 256);
     if (blocks > 4 * ctx->num_cu) blocks = 4 * ctx->num_cu;
     hipLaunchKernelGGL(kmv_reduce_f16_kernel, dim3(blocks), dim3(256), 0, st, (const float*)part, a.split_stride, pl.JS,
-                       ctx->n, t, dOut, ldo);
+                       nrows, t, dOut, ldo);
     GP_HIP(ctx, hipGetLastError());
   }
   return GP_OK;

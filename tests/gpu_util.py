@@ -38,6 +38,19 @@ class Dev:
             assert (o[:, t:] == -777.0).all(), "padding columns of the output were written"
         return o[:, :t]
 
+    def predict(self, Xstar, V, ldo=None):
+        m, t = Xstar.shape[0], V.shape[1]
+        ldo = ldo or t
+        Xd = torch.from_numpy(np.ascontiguousarray(Xstar, dtype=np.float32)).to(self.dev)
+        Vd = self.to(V)
+        out = torch.full((m, ldo), -777.0, device=self.dev)
+        self.gp.gp_predict(self.ctx, Xd, m, Vd, t, t, out, ldo)
+        torch.cuda.synchronize()
+        o = out.cpu().numpy().astype(np.float64)
+        if ldo > t:
+            assert (o[:, t:] == -777.0).all(), "padding columns of the output were written"
+        return o[:, :t]
+
     def work(self, t):
         need = self.gp.gp_workspace_bytes(self.ctx, t)
         if self._work is None or self._work.numel() < need:

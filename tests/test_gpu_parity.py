@@ -379,6 +379,90 @@ def test_gradient_end_to_end_after_solve(name, kw):
         dv.close()
 
 
+# ------------------------------------------------------------------ prediction (cross-covariance product)
+PREDICT_CASES = [
+    ("config1", dict(n=1500), 333, 1),       # t = 1: the posterior mean, ragged m
+    ("config2", dict(n=2100), 700, 65),      # Matern d = 26, all columns of a batch
+    ("config5", dict(n=9000), 8500, 3),      # m large enough for two sub-tiles per wave
+    ("config3", dict(n=1200), 1, 2),         # a single test point
+    ("config4", dict(n=1000), 40, 5),        # d = 90
+]
+
+
+@pytest.mark.parametrize("name,kw,m,t", PREDICT_CASES)
+def test_predict_matches_dense_oracle(name, kw, m, t):
+    """OUT = k(X*, X) V against the dense oracle, X* drawn around the training inputs."""
+    w = make(name, **kw)
+    rng = np.random.default_rng(m + t)
+    Xs = (w.X[rng.integers(0, w.n, size=m)] + 0.3 * rng.standard_normal((m, w.d)) * w.X.std(axis=0)).astype(np.float32)
+    if m > 4:
+        Xs[:3] = w.X[:3]                       # test points that coincide with training points
+    V = rng.standard_normal((w.n, t)).astype(np.float32)
+    dv = Dev(w.X, w.kind, w.ell, 1.1, 0.2)
+    try:
+        got = dv.predict(Xs, V, ldo=t + 2)
+        ref = orc.cross_kmv(Xs, w.X, w.ell, 1.1, w.kind, V)
+        assert got.shape == (m, t) and np.isfinite(got).all()
+        assert relerr(got, ref) <= KMV_TOL
+        assert np.abs(got - ref).max() <= 50 * KMV_TOL * np.abs(ref).max()
+        # X* = X reproduces the square product without the noise term
+        if w.n <= 2100:
+            sq = dv.kmv(V, 0)
+            assert relerr(dv.predict(w.X, V), sq) <= KMV_TOL   # coincident points: only the square product sets r^2 = 0 exactly
+    finally:
+        dv.close()
+
+
+@pytest.mark.parametrize("path", ["fp32", "f16x2", "f16x3"])
+def test_predict_every_product_path_and_far_points(monkeypatch, path):
+    """Test points far from the data raise the scaled norm: the product must move to the arithmetic
+    that covers it (three fp16 pieces, then fp32) whatever the training inputs alone would select."""
+    monkeypatch.setenv("GPWS_PATH", path)
+    w = make("config3", n=1800)
+    rng = np.random.default_rng(9)
+    V = rng.standard_normal((w.n, 4)).astype(np.float32)
+    dv = Dev(w.X, w.kind, w.ell * 2.0, 1.0, 0.1)
+    try:
+        for spread in (1.0, 12.0):
+            Xs = (spread * rng.standard_normal((257, w.d))).astype(np.float32)
+            got = dv.predict(Xs, V)
+            ref = orc.cross_kmv(Xs, w.X, w.ell * 2.0, 1.0, w.kind, V)
+            assert np.abs(got - ref).max() <= KMV_TOL * max(np.abs(ref).max(), 1e-3 * np.abs(V).sum(axis=0).max())
+    finally:
+        dv.close()
+    monkeypatch.delenv("GPWS_PATH")
+    dv = Dev(w.X, w.kind, w.ell * 0.05, 1.0, 0.1)   # automatic choice, scaled norms beyond fp16's range for far points
+    try:
+        Xs = np.concatenate([w.X[:50], 40.0 * rng.standard_normal((50, w.d))]).astype(np.float32)
+        got = dv.predict(Xs, V)
+        ref = orc.cross_kmv(Xs, w.X, w.ell * 0.05, 1.0, w.kind, V)
+        # Here |x/ell|^2 reaches ~1e6 and the fp32 fallback forms r^2 by cancellation of terms that
+        # large: its absolute error is eps32 (|xs_i|^2 + |xs_j|^2), which for the coincident pairs of
+        # the first 50 rows (r^2 = 0, K = 1) is a 1e-4-class error of the row; K is almost the
+        # identity in this regime.  The far rows must come out as (numerically) zero.
+        assert np.abs(got[:50] - ref[:50]).max() <= 1e-3 * np.abs(ref).max()
+        assert np.abs(got[50:] - ref[50:]).max() <= KMV_TOL * np.abs(ref).max()
+    finally:
+        dv.close()
+
+
+def test_posterior_mean_end_to_end():
+    """Solve H v_y = y on the GPU, predict at held-out points, compare with the oracle's Cholesky mean."""
+    w = make("config1", n=1200)
+    rng = np.random.default_rng(4)
+    Xs = rng.standard_normal((300, w.d)).astype(np.float32)
+    dv = _dev(w)
+    try:
+        rc, _, _, _, Vd = dv.solve(w.B[:, :1], 1e-6)
+        assert rc == 0
+        mu = dv.predict(Xs, Vd.cpu().numpy())
+        vy = orc.chol_solve(orc.coefficient_matrix(w.X, w.ell, w.a, w.sigma, w.kind), w.B[:, :1])
+        ref = orc.cross_kmv(Xs, w.X, w.ell, w.a, w.kind, vy)
+        assert np.abs(mu - ref).max() <= 1e-4 * np.abs(ref).max()
+    finally:
+        dv.close()
+
+
 # ------------------------------------------------------------------ error paths (host-side checks)
 def test_argument_errors_return_codes():
     w = make("config1", n=200, s=3)
@@ -406,6 +490,15 @@ def test_argument_errors_return_codes():
         assert e.value.code == gp.GP_ERR_WORKSPACE
         with pytest.raises(gp.GpError) as e:
             gp.gp_cg_solve(dv.ctx, Bd, t, None, out, t, t, 0.0, 10, dv.work(t), dv.work(t).numel())
+        assert e.value.code == gp.GP_ERR_ARG
+        with pytest.raises(gp.GpError) as e:
+            gp.gp_predict(dv.ctx, dv.X, 0, Bd, t, t, out, t)  # no test points
+        assert e.value.code == gp.GP_ERR_ARG
+        with pytest.raises(gp.GpError) as e:
+            gp.gp_predict(dv.ctx, None, 5, Bd, t, t, out, t)
+        assert e.value.code == gp.GP_ERR_ARG
+        with pytest.raises(gp.GpError) as e:
+            gp.gp_predict(dv.ctx, dv.X, 5, Bd, t, t, out, t - 1)
         assert e.value.code == gp.GP_ERR_ARG
         # a context without theta refuses to compute
         ctx2 = gp.gp_create(0, w.n, w.d, dv.X, None)

@@ -334,3 +334,28 @@ def test_planted_mistakes_are_caught():
     }
     for name, g in mutants.items():
         assert not np.allclose(g, fd, rtol=1e-3, atol=1e-6), name
+
+
+def test_cross_kmv_is_the_posterior_mean_of_a_library_gp():
+    """Eq. 1: mu(X*) = k(X*, X) H^{-1} y.  scikit-learn's GaussianProcessRegressor with a fixed
+    kernel a^2 RBF(ell) / a^2 Matern(ell, nu=1.5) and alpha = sigma^2 computes the same mean."""
+    from sklearn.gaussian_process import GaussianProcessRegressor
+    from sklearn.gaussian_process.kernels import RBF, ConstantKernel, Matern
+    rng = np.random.default_rng(77)
+    n, m, d = 60, 17, 3
+    X, Xs = rng.standard_normal((n, d)), rng.standard_normal((m, d)) * 1.5
+    y = rng.standard_normal(n)
+    ell, a, sigma = np.array([0.7, 1.3, 2.1]), 1.4, 0.3
+    for kind, base in ((orc.SE, RBF(length_scale=ell)), (orc.MATERN32, Matern(length_scale=ell, nu=1.5))):
+        gpr = GaussianProcessRegressor(kernel=ConstantKernel(a * a, "fixed") * base, alpha=sigma ** 2, optimizer=None)
+        gpr.fit(X, y)
+        vy = orc.chol_solve(orc.coefficient_matrix(X, ell, a, sigma, kind), y[:, None])
+        mu = orc.cross_kmv(Xs, X, ell, a, kind, vy)[:, 0]
+        assert np.allclose(mu, gpr.predict(Xs), rtol=1e-9, atol=1e-10)
+    # rectangular shape and the transposed-operand mistake: k(X*, X) is m x n, not n x m
+    V = rng.standard_normal((n, 4))
+    out = orc.cross_kmv(Xs, X, ell, a, orc.SE, V)
+    assert out.shape == (m, 4)
+    brute = np.array([[sum(a * a * np.exp(-0.5 * np.sum(((Xs[i] - X[j]) / ell) ** 2)) * V[j, c] for j in range(n))
+                       for c in range(4)] for i in range(m)])
+    assert np.allclose(out, brute, rtol=1e-12)
