@@ -31,7 +31,7 @@ def kmv_flops(n, d, t, kind):
     return float(n) * float(n) * (2 * d + 2 * t + (4 if kind == "se" else 8))
 
 
-def executed_mfma_flops(n, d, t, kind, path):
+def executed_mfma_flops(n, d, t, kind, path, rows=None):
     """Matrix-core flops the tile kernel really issues per K V product (padding of the contraction
     lengths and the extra products of the fp16 splitting included), as opposed to kmv_flops."""
     nt = (t // 32) if t % 32 == 1 and t > 1 else -(-t // 32)     # a lone 33rd column goes through the vector ALU
@@ -42,7 +42,7 @@ def executed_mfma_flops(n, d, t, kind, path):
         slots = d + 2 + (1 if kind == "se" else 0)
         kh = next(b for b in (1, 2, 3, 4, 6, 8) if 16 * b >= slots)
         per_pair = (3 if path == 1 else 6) * 2 * 16 * kh + 3 * 2 * 32 * nt
-    return float(n) * float(n) * per_pair
+    return float(n) * float(rows if rows else n) * per_pair
 
 
 def cpu_baseline(w):
@@ -83,6 +83,8 @@ def main():
     ap.add_argument("--no-cold", action="store_true", help="skip the cold-start comparison arm")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--kmv-only", action="store_true", help="time bare K V products instead of MLL steps")
+    ap.add_argument("--predict", type=int, default=0, metavar="M",
+                    help="time gp_predict (posterior mean, t = 1) at M synthetic test inputs instead of MLL steps")
     ap.add_argument("--probe-tol", type=float, default=None,
                     help="tolerance of the probe systems when it differs from the workload's (Appendix B of the "
                          "paper solves y to 0.01 and the probes to 0.1); default: the workload's tolerance for all")
@@ -130,7 +132,32 @@ def main():
                 dst.copy_(src)
             torch.cuda.synchronize()
             del src, dst
-        if args.kmv_only:
+        if args.predict:
+            # posterior-mean product k(X*, X) v_y for M test inputs drawn like the training inputs
+            M = args.predict
+            rng = np.random.default_rng(77)
+            Xs = torch.from_numpy(w.X[rng.integers(0, n, size=M)].astype(np.float32)
+                                  + 0.1 * rng.standard_normal((M, d)).astype(np.float32)).to(opt.dev)
+            theta = opt.theta
+            gp.gp_set_theta(opt.ctx, theta[:d], theta[d], theta[d + 1])
+            vy = opt.B[:, :1].contiguous()
+            out = torch.empty((M, 1), device=opt.dev)
+            for _ in range(warmup):
+                gp.gp_predict(opt.ctx, Xs, M, vy, 1, 1, out, 1)
+            torch.cuda.synchronize()
+            gp.gp_profile(opt.ctx, 1)
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                gp.gp_predict(opt.ctx, Xs, M, vy, 1, 1, out, 1)
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t0
+            launches, kern_ms = gp.gp_profile_read(opt.ctx)
+            gp.gp_profile(opt.ctx, 0)
+            F = float(M) * float(n) * (2 * d + 2 * 1 + (4 if w.kind == "se" else 8))
+            t = 1
+            n_kmv = steps
+            extra = {"mode": "predict", "test_inputs": M, "pairs_per_s": float(M) * n * steps / wall}
+        elif args.kmv_only:
             out = torch.empty_like(opt.B)
             theta = opt.theta
             gp.gp_set_theta(opt.ctx, theta[:d], theta[d], theta[d + 1])
@@ -208,7 +235,7 @@ def main():
         path = gp.gp_product_path(opt.ctx)
         # the contraction runs on the matrix cores in the dtype of the chosen product path
         peak = FP32_PEAK_TFLOPS if path == 0 else FP16_PEAK_TFLOPS
-        executed = executed_mfma_flops(n, d, t, w.kind, path) * n_kmv / max(launches, 1) / avg_kern_s / 1e12 if launches else 0.0
+        executed = executed_mfma_flops(n, d, t, w.kind, path, args.predict or None) * n_kmv / max(launches, 1) / avg_kern_s / 1e12 if launches else 0.0
         result = {
             "metric": "matrix-free K.V TFLOP/s (% FP32 peak) + CG time per MLL step, warm vs cold",
             "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
