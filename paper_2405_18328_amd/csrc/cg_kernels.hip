@@ -141,17 +141,35 @@ __global__ __launch_bounds__(VT) void cg_resid_kernel(float* __restrict__ R, con
   block_column_max(mx, c, t, colmax, smax);   // max |P| per column for the product that follows
 }
 
-// partial p^T (H p)
-__global__ __launch_bounds__(VT) void cg_dot_kernel(const float* __restrict__ P, const float* __restrict__ HP,
-                                                    int64_t total, int t, const CgFlags* __restrict__ flags,
-                                                    double* __restrict__ part) {
+// partial p^T (H p).  When the product left column-split partials (JS > 1), H p is first formed here as
+// their fixed-order sum and written to HP (flat index e = i t + c, identical in both layouts; elements
+// at or past n t are padding and stay zero).
+__global__ __launch_bounds__(VT) void cg_dot_kernel(const float* __restrict__ P, float* __restrict__ HP,
+                                                    const float* __restrict__ part_in, int64_t part_stride, int JS,
+                                                    int64_t valid, int64_t total, int t,
+                                                    const CgFlags* __restrict__ flags, double* __restrict__ part) {
   __shared__ float sh[VW];
   if (flags->all_done) return;
   const int64_t stride = (int64_t)gridDim.x * VW;
+  const bool vec_ok = (part_stride & 3) == 0;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   for (int64_t e = ((int64_t)blockIdx.x * VT + threadIdx.x) * 4; e < total; e += stride) {
     const f32x4 p = *reinterpret_cast<const f32x4*>(P + e);
-    const f32x4 hp = *reinterpret_cast<const f32x4*>(HP + e);
+    f32x4 hp;
+    if (JS > 1) {
+      hp = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (vec_ok && e + 4 <= valid) {
+        for (int k = 0; k < JS; ++k) hp += *reinterpret_cast<const f32x4*>(part_in + (int64_t)k * part_stride + e);
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (e + q < valid)
+            for (int k = 0; k < JS; ++k) hp[q] += part_in[(int64_t)k * part_stride + e + q];
+      }
+      *reinterpret_cast<f32x4*>(HP + e) = hp;
+    } else {
+      hp = *reinterpret_cast<const f32x4*>(HP + e);
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q) acc[q] = fmaf(p[q], hp[q], acc[q]);
   }
@@ -437,10 +455,12 @@ int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
 
   int it = 0;
   while (!hflags->all_done && it < max_iters) {
-    int rc = gp_kmv_launch(ctx, P, t, t, HP, t, 1, kmv_scratch, L.kmv_bytes, s.colmax);
+    KmvDeferred df = {nullptr, 0, 1};
+    int rc = gp_kmv_launch(ctx, P, t, t, HP, t, 1, kmv_scratch, L.kmv_bytes, s.colmax, nullptr, &df);
     if (rc < 0) return rc;
     ++kmv_count;
-    hipLaunchKernelGGL(cg_dot_kernel, grid, block, 0, st, (const float*)P, (const float*)HP, total, t, s.flags, s.part);
+    hipLaunchKernelGGL(cg_dot_kernel, grid, block, 0, st, (const float*)P, HP, df.part, df.stride, df.JS,
+                       ctx->n * (int64_t)t, total, t, s.flags, s.part);
     hipLaunchKernelGGL(cg_fin_alpha_kernel, dim3(1), dim3(FT), 0, st, s, L.G, t);
     hipLaunchKernelGGL(cg_update_xr_kernel, grid, block, 0, st, X, R, (const float*)P, (const float*)HP, total, t,
                        (const float*)s.alpha, s.flags, s.part);

@@ -88,6 +88,15 @@ struct KmvRows {
   int path;               // GP_PATH_* to use (covers the norms of both point sets)
 };
 
+// Column-split partial results of a product whose final sum the caller takes over (the CG dot-product
+// kernel adds the partials while it reads H P anyway): OUT_ic = sum_k part[k stride + i t + c].
+// JS == 1 means the launcher wrote OUT itself.
+struct KmvDeferred {
+  const float* part;
+  int64_t stride;
+  int JS;
+};
+
 int gp_fail(gp_ctx* ctx, int code, const char* fmt, ...);
 #define GP_HIP(ctx, call)                                                              \
   do {                                                                                 \
@@ -122,9 +131,10 @@ size_t gp_kmv_rect_scratch_bytes(const gp_ctx* ctx, int t, int64_t rows);
 // OUT = K V (+ sigma^2 V).  colmax: optional device array of t bit patterns of max_i |V_ic| that the
 // caller already holds (the split-fp16 path then skips its own reduction over V); NULL otherwise.
 // rows: NULL, or the row side of a rectangular product (add_noise must then be 0).
+// defer: NULL, or where to report column-split partials instead of summing them into OUT.
 int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
                   int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax,
-                  const KmvRows* rows = nullptr);
+                  const KmvRows* rows = nullptr, KmvDeferred* defer = nullptr);
 
 // ---- tile_pass_f16.hip
 int gp_kh_bucket(int d, int kernel);
@@ -132,7 +142,7 @@ KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx, int64_t rows);
 size_t gp_kmv_f16_scratch_bytes(const gp_ctx* ctx, int t, int64_t rows);
 int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
                       int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax,
-                      const KmvRows* rows);
+                      const KmvRows* rows, KmvDeferred* defer);
 
 // colmax[c] = bit pattern of max_i |V_ic| for c < t (cleared first); stream-ordered
 int gp_launch_colmax(gp_ctx* ctx, const float* dV, int64_t ldv, int t, unsigned* colmax);

@@ -314,10 +314,11 @@ size_t gp_kmv_rect_scratch_bytes(const gp_ctx* ctx, int t, int64_t rows) {
 size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t) { return gp_kmv_rect_scratch_bytes(ctx, t, ctx->n); }
 
 int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
-                  int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax, const KmvRows* rows) {
+                  int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax, const KmvRows* rows,
+                  KmvDeferred* defer) {
   if (rows && add_noise) return gp_fail(ctx, GP_ERR_ARG, "rectangular product with a noise term");
   if ((rows ? rows->path : ctx->path) != GP_PATH_FP32)
-    return gp_kmv_launch_f16(ctx, dV, ldv, t, dOut, ldo, add_noise, scratch, scratch_bytes, colmax, rows);
+    return gp_kmv_launch_f16(ctx, dV, ldv, t, dOut, ldo, add_noise, scratch, scratch_bytes, colmax, rows, defer);
   const int64_t nrows = rows ? rows->m : ctx->n;
   const KmvPlan pl = gp_plan_kmv(ctx, nrows);
   const bool split = pl.JS > 1;
@@ -366,7 +367,12 @@ int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut,
     }
     c += a.ncols;
   }
-  if (split) {
+  if (defer) {
+    defer->part = (const float*)scratch;
+    defer->stride = a.split_stride;
+    defer->JS = pl.JS;
+  }
+  if (split && !defer) {
     const int64_t total = nrows * (int64_t)t;
     int blocks = (int)((total + 255) / 256);
     if (blocks > 4 * ctx->num_cu) blocks = 4 * ctx->num_cu;

@@ -581,7 +581,8 @@ size_t gp_kmv_f16_scratch_bytes(const gp_ctx* ctx, int t, int64_t rows) {
 }
 
 int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo, int add_noise,
-                      void* scratch, size_t scratch_bytes, const unsigned* colmax_ready, const KmvRows* rows) {
+                      void* scratch, size_t scratch_bytes, const unsigned* colmax_ready, const KmvRows* rows,
+                      KmvDeferred* defer) {
   const int64_t nrows = rows ? rows->m : ctx->n;
   const int XP = rows ? (rows->path == GP_PATH_F16X3 ? 3 : 2) : ctx->XP;
   const KmvPlan pl = gp_plan_kmv_f16(ctx, nrows);
@@ -653,7 +654,12 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
     }
     c += a.ncols;
   }
-  if (split) {
+  if (defer) {
+    defer->part = part;
+    defer->stride = a.split_stride;
+    defer->JS = pl.JS;
+  }
+  if (split && !defer) {
     const int64_t total = nrows * (int64_t)t;
     int blocks = (int)((total + 255) / 256);
     if (blocks > 4 * ctx->num_cu) blocks = 4 * ctx->num_cu;
