@@ -26,11 +26,12 @@ struct CgFlags {
   int all_done;
   int breakdown;
   int iters;
-  int pad;
+  int seq;          // host mirror only: number of finalise steps posted so far (written last)
 };
 
 struct CgDev {
   CgFlags* flags;
+  CgFlags* post;    // pinned host memory: the finalise kernels post the flags there for the host loop
   double* rho;      // [t] current r^T r
   double* bn2;      // [t] ||b||^2
   float* alpha;     // [t]
@@ -277,6 +278,17 @@ __device__ __forceinline__ double finalize_sum(const double* part, int G, int t,
   return tot;
 }
 
+// Copy the flags to the host mirror; seq goes last, behind a system-scope fence, so that a host that
+// sees the new seq also sees the flags that belong to it.  One thread.
+__device__ __forceinline__ void post_flags(const CgDev& s, int seq) {
+  volatile CgFlags* h = s.post;
+  h->all_done = s.flags->all_done;
+  h->breakdown = s.flags->breakdown;
+  h->iters = s.flags->iters;
+  __threadfence_system();
+  h->seq = seq;
+}
+
 __global__ __launch_bounds__(FT) void cg_fin_init_kernel(CgDev s, int G, int t, int have_bn2) {
   __shared__ double sh[FT];
   __shared__ int live_count;
@@ -303,6 +315,8 @@ __global__ __launch_bounds__(FT) void cg_fin_init_kernel(CgDev s, int G, int t, 
     s.flags->all_done = live_count == 0;
     s.flags->breakdown = 0;
     s.flags->iters = 0;
+    __threadfence();
+    post_flags(s, 1);
   }
 }
 
@@ -352,6 +366,8 @@ __global__ __launch_bounds__(FT) void cg_fin_beta_kernel(CgDev s, int G, int t) 
   if (threadIdx.x == 0) {
     s.flags->iters += 1;
     if (live_count == 0 || s.flags->breakdown) s.flags->all_done = 1;
+    __threadfence();
+    post_flags(s, s.flags->iters + 1);
   }
 }
 
@@ -438,6 +454,29 @@ int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
   // HP padding rows are never written by the product; keep them zero
   GP_HIP(ctx, hipMemsetAsync(HP, 0, (size_t)total * sizeof(float), st));
 
+  // The finalise kernels post the flags into pinned host memory themselves (no copy command in the
+  // stream between iterations); the host polls the sequence number, and checks the stream now and
+  // then so that a failed launch or a missing post ends the wait instead of hanging it.
+  CgFlags* hpost = (CgFlags*)((char*)ctx->hPinned + 32768);
+  s.post = (CgFlags*)((char*)ctx->dPinned + 32768);
+  hpost->seq = 0;
+  auto wait_seq = [&](int want) -> int {
+    volatile CgFlags* h = hpost;
+    for (unsigned spins = 1;; ++spins) {
+      if (h->seq >= want) break;
+      if ((spins & 4095u) == 0) {
+        const hipError_t q = hipStreamQuery(st);
+        if (q == hipSuccess) {          // nothing left to run: the post must be there by now
+          if (h->seq >= want) break;
+          return gp_fail(ctx, GP_ERR_HIP, "gp_cg_solve: the solver kernels did not report their state");
+        }
+        if (q != hipErrorNotReady) return gp_fail(ctx, GP_ERR_HIP, "gp_cg_solve: %s", hipGetErrorString(q));
+      }
+    }
+    __atomic_thread_fence(__ATOMIC_ACQUIRE);
+    return GP_OK;
+  };
+
   int kmv_count = 0;
   hipLaunchKernelGGL(cg_load_kernel, grid, block, 0, st, dB, ldb, dX0, ldv, ctx->n, L.n4, t, X, R, s.part2);
   GP_HIP(ctx, hipGetLastError());
@@ -450,11 +489,13 @@ int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
   hipLaunchKernelGGL(cg_resid_kernel, grid, block, 0, st, R, (const float*)HP, dX0 ? 1 : 0, P, total, t, s.part, s.colmax);
   hipLaunchKernelGGL(cg_fin_init_kernel, dim3(1), dim3(FT), 0, st, s, L.G, t, 1);
   GP_HIP(ctx, hipGetLastError());
-  GP_HIP(ctx, hipMemcpyAsync(hflags, s.flags, sizeof(CgFlags), hipMemcpyDeviceToHost, st));
-  GP_HIP(ctx, hipStreamSynchronize(st));
+  {
+    const int rc = wait_seq(1);
+    if (rc < 0) return rc;
+  }
 
   int it = 0;
-  while (!hflags->all_done && it < max_iters) {
+  while (!hpost->all_done && it < max_iters) {
     KmvDeferred df = {nullptr, 0, 1};
     int rc = gp_kmv_launch(ctx, P, t, t, HP, t, 1, kmv_scratch, L.kmv_bytes, s.colmax, nullptr, &df);
     if (rc < 0) return rc;
@@ -467,8 +508,8 @@ int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     hipLaunchKernelGGL(cg_fin_beta_kernel, dim3(1), dim3(FT), 0, st, s, L.G, t);
     hipLaunchKernelGGL(cg_update_p_kernel, grid, block, 0, st, P, (const float*)R, total, t, (const float*)s.beta, s.flags, s.colmax);
     GP_HIP(ctx, hipGetLastError());
-    GP_HIP(ctx, hipMemcpyAsync(hflags, s.flags, sizeof(CgFlags), hipMemcpyDeviceToHost, st));
-    GP_HIP(ctx, hipStreamSynchronize(st));
+    rc = wait_seq(it + 2);
+    if (rc < 0) return rc;
     ++it;
   }
 

@@ -85,6 +85,7 @@ int gp_create(gp_ctx** out, int kernel, int64_t n, int d, const float* dX, void*
   GP_HIP(ctx, hipMalloc((void**)&ctx->dRed, ctx->red_bytes));
   ctx->pinned_bytes = (size_t)1 << 16;
   GP_HIP(ctx, hipHostMalloc(&ctx->hPinned, ctx->pinned_bytes, hipHostMallocDefault));
+  GP_HIP(ctx, hipHostGetDevicePointer(&ctx->dPinned, ctx->hPinned, 0));
   return gp_launch_column_means(ctx);
 }
 

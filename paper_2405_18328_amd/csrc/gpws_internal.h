@@ -70,6 +70,7 @@ struct gp_ctx {
   double* dRed;           // reduction partials
   size_t red_bytes;
   void* hPinned;          // pinned host staging for scalar read-back
+  void* dPinned;          // the same block as the device addresses it (kernels post small results there)
   size_t pinned_bytes;
   int num_cu;
   // event pairs bracketing tile-pass launches while profiling is on
