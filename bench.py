@@ -25,6 +25,10 @@ PATH_NAMES = {0: "fp32", 1: "f16x2", 2: "f16x3"}
 # HBM bytes per launch of the tile kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script (summaries under profiles/), keyed by (workload, n); filled in from those runs, not measured live
 TRAFFIC = {("config2", 16384): 43.4e6, ("config5", 2000000): 742e9}
+# Vector-ALU instructions per launch of the tile kernel (SQ_INSTS_VALU, wave-level) from the same kind of
+# run; the chip issues at most 256 CUs x 4 SIMDs x 2.4e9 / 4 = 6.14e11 wave-instructions per second
+VALU_INSTS = {("config2", 16384): 5.365e7}
+VALU_ISSUE_PEAK = 256 * 4 * 2.4e9 / 4
 
 
 def kmv_flops(n, d, t, kind):
@@ -252,7 +256,10 @@ def main():
                          "launches": int(launches), "avg_launch_ms": avg_kern_s * 1e3,
                          "flops_per_launch": F_launch,
                          "executed_mfma_tflops": executed, "executed_mfma_frac_of_peak": executed / peak,
-                         "achieved_vs_fp32_peak": achieved / FP32_PEAK_TFLOPS},
+                         "achieved_vs_fp32_peak": achieved / FP32_PEAK_TFLOPS,
+                         "valu_issue_frac": (VALU_INSTS[(args.workload, n)] / avg_kern_s / VALU_ISSUE_PEAK
+                                             if (args.workload, n) in VALU_INSTS and launches and not args.predict
+                                             else None)},
         }
         result.update(extra)
     finally:

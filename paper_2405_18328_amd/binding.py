@@ -25,6 +25,7 @@ GP_ERR_BREAKDOWN = -4
 GP_MAX_D = 126
 GP_MAX_T = 1024
 
+# GPWS_LIB names another build of the library (developer aid for side-by-side timing of two builds)
 LIB_PATH = os.environ.get("GPWS_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgpws.so")
 
 EXPORTS = ["gp_create", "gp_destroy", "gp_set_theta", "gp_kmv", "gp_workspace_bytes", "gp_cg_solve",

@@ -27,11 +27,6 @@ def _compile(src):
 
 def build_library(verbose=True, jobs=8):
     os.makedirs(OBJ, exist_ok=True)
-    global LIB
-    extra = os.environ.get("GPWS_EXTRA_FLAGS", "").split()
-    if extra:
-        FLAGS.extend(extra)
-        LIB = os.environ.get("GPWS_LIB_OUT", LIB)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         results = list(ex.map(_compile, SOURCES))
     objs = []
