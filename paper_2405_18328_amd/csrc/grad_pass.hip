@@ -56,7 +56,7 @@ __global__ __launch_bounds__(GP_THREADS) void grad_tile_kernel(GradArgs p) {
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: lets the compiler branch on it
   const int h = lane >> 5;
   const int li = lane & 31;
   const int js = blockIdx.x % p.JS;
@@ -135,6 +135,7 @@ __global__ __launch_bounds__(GP_THREADS) void grad_tile_kernel(GradArgs p) {
     for (int ks = 0; ks < KT; ++ks)
       W = __builtin_amdgcn_mfma_f32_32x32x2f32(s[CA_OFF + ks * 64 + lane], ab[ks], W, 0, 0, 0);
     if (ch == sub0) {
+      asm volatile("" ::: "memory");   // keeps this a real (wave-uniform) branch instead of selects on every chunk
 #pragma unroll
       for (int r = 0; r < 16; ++r)
         if (8 * (r >> 2) + 4 * h + (r & 3) == li) S[r] = 0.0f;

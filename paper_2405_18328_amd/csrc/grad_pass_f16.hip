@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void grad_tile_f16_kernel(GradArgsH p) {
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: lets the compiler branch on it
   const int h = lane >> 5;
   const int li = lane & 31;
   const int js = blockIdx.x % p.JS;
@@ -227,6 +227,7 @@ __global__ __launch_bounds__(256) void grad_tile_f16_kernel(GradArgsH p) {
       Wc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ch_, abh[kt], Wc, 0, 0, 0);
     }
     if (ch == sub0) {   // the pair (i, i): r^2 = 0 exactly
+      asm volatile("" ::: "memory");   // keeps this a real (wave-uniform) branch instead of selects on every chunk
 #pragma unroll
       for (int r = 0; r < 16; ++r)
         if (8 * (r >> 2) + 4 * h + (r & 3) == li) S[r] = 0.0f;

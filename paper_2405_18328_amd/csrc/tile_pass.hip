@@ -64,7 +64,7 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_kernel(TileArgs p) {
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: lets the compiler branch on it
   const int h = lane >> 5;
   const int li = lane & 31;
   const int js = blockIdx.x % p.JS;
@@ -203,6 +203,9 @@ __global__ __launch_bounds__(GP_THREADS) void kmv_tile_kernel(TileArgs p) {
 #pragma unroll
     for (int m = 0; m < MI; ++m) {
       if (p.diag && ch == sub0 + m) {
+        // one chunk in thousands: an opaque statement keeps this a real (wave-uniform) branch instead of
+        // sixteen selects executed on every chunk
+        asm volatile("" ::: "memory");
 #pragma unroll
         for (int r = 0; r < 16; ++r)
           if (8 * (r >> 2) + 4 * h + (r & 3) == li) S[m][r] = 0.0f;

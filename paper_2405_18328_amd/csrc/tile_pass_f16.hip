@@ -94,7 +94,7 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: lets the compiler branch on it
   const int h = lane >> 5;
   const int li = lane & 31;
   const int js = blockIdx.x % p.JS;
@@ -200,6 +200,9 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 #pragma unroll
     for (int m = 0; m < MI; ++m) {
       if (p.diag && ch == sub0 + m) {
+        // one chunk in thousands: an opaque statement keeps this a real (wave-uniform) branch instead of
+        // sixteen selects executed on every chunk
+        asm volatile("" ::: "memory");
         const float s0 = KIND == GP_SE_ARD ? (float)PHI_SHIFT : 0.0f;
 #pragma unroll
         for (int r = 0; r < 16; ++r)
