@@ -27,7 +27,7 @@ PATH_NAMES = {0: "fp32", 1: "f16x2", 2: "f16x3"}
 TRAFFIC = {("config2", 16384): 43.4e6, ("config5", 2000000): 742e9}
 # Vector-ALU instructions per launch of the tile kernel (SQ_INSTS_VALU, wave-level) from the same kind of
 # run; the chip issues at most 256 CUs x 4 SIMDs x 2.4e9 / 4 = 6.14e11 wave-instructions per second
-VALU_INSTS = {("config2", 16384): 5.365e7}
+VALU_INSTS = {("config2", 16384): 3.964e7}
 VALU_ISSUE_PEAK = 256 * 4 * 2.4e9 / 4
 
 
