@@ -27,6 +27,33 @@ def softplus_inverse(theta):
     return theta + np.log(-np.expm1(-theta))
 
 
+class AdamState:
+    """Bias-corrected Adam ascent on raw = softplus^{-1}(theta) (Section 4, Appendix B); host scalars only."""
+
+    def __init__(self, theta0, lr=0.1, b1=0.9, b2=0.999, eps=1e-8):
+        self.raw = softplus_inverse(theta0)
+        self.m = np.zeros_like(self.raw)
+        self.v = np.zeros_like(self.raw)
+        self.k = 0
+        self.lr, self.b1, self.b2, self.eps = lr, b1, b2, eps
+
+    @property
+    def theta(self):
+        return softplus(self.raw)
+
+    def ascend(self, grad_theta):
+        """One step given dL/dtheta at the current theta (chain rule through the softplus applied here)."""
+        theta = self.theta
+        graw = np.asarray(grad_theta, dtype=np.float64) * (-np.expm1(-theta))
+        self.k += 1
+        self.m = self.b1 * self.m + (1 - self.b1) * graw
+        self.v = self.b2 * self.v + (1 - self.b2) * graw * graw
+        mhat = self.m / (1 - self.b1 ** self.k)
+        vhat = self.v / (1 - self.b2 ** self.k)
+        self.raw = self.raw + self.lr * mhat / (np.sqrt(vhat) + self.eps)
+        return self.theta
+
+
 @dataclass
 class StepRecord:
     theta: np.ndarray
@@ -61,11 +88,7 @@ class MllOptimizer:
         self.resample = resample
         self.tol = tol
         self.max_iters = max_iters
-        self.lr, self.b1, self.b2, self.eps = lr, 0.9, 0.999, 1e-8
-        self.raw = softplus_inverse(np.concatenate([np.asarray(ell0, dtype=np.float64), [a0, sigma0]]))
-        self.m = np.zeros_like(self.raw)
-        self.v = np.zeros_like(self.raw)
-        self.k = 0
+        self.adam = AdamState(np.concatenate([np.asarray(ell0, dtype=np.float64), [a0, sigma0]]), lr=lr)
         self.have_solution = False
         self.stream = torch.cuda.current_stream(self.dev)
         self.ctx = gp.gp_create(KIND_CODE[kind], self.n, self.d, self.X, self.stream.cuda_stream)
@@ -74,7 +97,11 @@ class MllOptimizer:
 
     @property
     def theta(self):
-        return softplus(self.raw)
+        return self.adam.theta
+
+    @property
+    def k(self):
+        return self.adam.k
 
     def close(self):
         if self.ctx is not None:
@@ -96,14 +123,7 @@ class MllOptimizer:
         g = gp.gp_mll_grad(self.ctx, self.V, self.t, self.B, self.t, self.t, self.d)
         t3 = time.perf_counter()
         self.have_solution = True
-        # chain rule through the softplus, then bias-corrected Adam ascent
-        graw = g * (-np.expm1(-theta))
-        self.k += 1
-        self.m = self.b1 * self.m + (1 - self.b1) * graw
-        self.v = self.b2 * self.v + (1 - self.b2) * graw * graw
-        mhat = self.m / (1 - self.b1 ** self.k)
-        vhat = self.v / (1 - self.b2 ** self.k)
-        self.raw = self.raw + self.lr * mhat / (np.sqrt(vhat) + self.eps)
+        self.adam.ascend(g)
         t4 = time.perf_counter()
         rec = StepRecord(theta, iters, kmv, rc, (t2 - t1) * 1e3, (t3 - t2) * 1e3, (t4 - t0) * 1e3,
                          float(relres.max()), g)
