@@ -47,6 +47,8 @@ int gp_create(gp_ctx** out, int kernel, int64_t n, int d, const float* dX, void*
   ctx->d = d;
   ctx->KS = gp_ks_bucket(d);
   ctx->KH = gp_kh_bucket(d, kernel);
+  ctx->f16_ok = ctx->KH > 0;
+  if (!ctx->f16_ok) ctx->KH = 8;   // operands are still allocated and packed, the product stays on the fp32 path
   ctx->path_forced = -1;
   if (const char* f = getenv("GPWS_PATH")) {      // testing aid: pin the product path
     if (!strcmp(f, "fp32")) ctx->path_forced = GP_PATH_FP32;
@@ -151,6 +153,7 @@ int gp_set_theta(gp_ctx* ctx, const double* h_lengthscale, double signal_scale, 
              : ctx->max_norm <= GP_NORM_X3_MAX ? GP_PATH_F16X3 : GP_PATH_FP32;
   if (ctx->path_forced >= 0 && !(ctx->path_forced != GP_PATH_FP32 && ctx->max_norm > GP_NORM_X3_MAX))
     path = ctx->path_forced;
+  if (!ctx->f16_ok) path = GP_PATH_FP32;
   ctx->path = path;
   ctx->XP = path == GP_PATH_F16X3 ? 3 : 2;
   ctx->theta_set = true;

@@ -57,6 +57,7 @@ struct gp_ctx {
   int XP;                 // pieces used per operand of the distance chain (2 or 3)
   int path;               // GP_PATH_* chosen by gp_set_theta
   int path_forced;        // -1, or a GP_PATH_* forced through the GPWS_PATH environment variable
+  bool f16_ok;            // false when d + 3 components do not fit the widest fp16 operand bucket (SE, d = 126)
   float max_norm;         // host copy of max_i |xs_i|^2
   double* dMean;          // d column means of X
   double* dTheta;         // device copy: 1/ell (d), then a, sigma

@@ -191,6 +191,7 @@ int gp_pack_rows(gp_ctx* ctx, const float* dXstar, int64_t m, void* buf, KmvRows
   if (ctx->max_norm > mx) mx = ctx->max_norm;
   int path = mx <= GP_NORM_X2_MAX ? GP_PATH_F16X2 : (mx <= GP_NORM_X3_MAX ? GP_PATH_F16X3 : GP_PATH_FP32);
   if (ctx->path_forced >= 0 && !(ctx->path_forced != GP_PATH_FP32 && mx > GP_NORM_X3_MAX)) path = ctx->path_forced;
+  if (!ctx->f16_ok) path = GP_PATH_FP32;
   rows->m = m;
   rows->XB = (const float*)(w + L.off_xb);
   for (int pc = 0; pc < 3; ++pc) rows->XBh[pc] = w + L.off_b[pc];

@@ -101,6 +101,28 @@ def test_kmv_every_product_path(monkeypatch, path, name, kw):
         dv.close()
 
 
+@pytest.mark.parametrize("kind", ["se", "matern32"])
+def test_kmv_and_gradient_at_the_largest_dimension(kind):
+    """d = 126 (the documented maximum): the SE operand set no longer fits the widest fp16 bucket and
+    the product must fall back to fp32; Matern-3/2 still fits."""
+    rng = np.random.default_rng(126)
+    n, d, t = 700, 126, 5
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    ell = np.full(d, np.sqrt(d)) * rng.uniform(0.8, 1.25, d)
+    V = rng.standard_normal((n, t)).astype(np.float32)
+    B = rng.standard_normal((n, t)).astype(np.float32)
+    dv = Dev(X, kind, ell, 1.2, 0.3)
+    try:
+        assert dv.gp.gp_product_path(dv.ctx) == (0 if kind == "se" else 1)
+        assert relerr(dv.kmv(V, 1), orc.kmv_dense(X, ell, 1.2, kind, V, sigma=0.3)) <= KMV_TOL
+        g = dv.grad(dv.to(V), dv.to(B))
+        assert relerr(g, orc.mll_grad_hutchinson(X, ell, 1.2, 0.3, kind, B, V=V)) <= GRAD_TOL
+        Xs = rng.standard_normal((40, d)).astype(np.float32)
+        assert relerr(dv.predict(Xs, V), orc.cross_kmv(Xs, X, ell, 1.2, kind, V)) <= KMV_TOL
+    finally:
+        dv.close()
+
+
 def test_kmv_path_selection_by_norm():
     """Small lengthscales blow up |x/ell|^2: the automatic choice must still meet the bar
     (three fp16 pieces, then the fp32 MFMA path beyond fp16's range)."""
