@@ -307,6 +307,44 @@ def test_cg_edge_cases():
         dv.close()
 
 
+@pytest.mark.parametrize("n,d,t", [(1, 1, 1), (2, 1, 3), (33, 2, 1), (257, 1, 1024), (300, 3, 200)])
+@pytest.mark.parametrize("kind", ["se", "matern32"])
+def test_extreme_shapes_all_entry_points(n, d, t, kind):
+    """Smallest problems, a single input dimension, the largest number of right-hand sides, and
+    leading dimensions larger than t, through every method entry point."""
+    rng = np.random.default_rng(1000 * n + t)
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    ell = rng.uniform(0.7, 1.5, d)
+    a, sigma = 1.1, 0.7
+    B = rng.standard_normal((n, t)).astype(np.float32)
+    V = rng.standard_normal((n, t)).astype(np.float32)
+    dv = Dev(X, kind, ell, a, sigma)
+    gp = dv.gp
+    try:
+        H = orc.coefficient_matrix(X, ell, a, sigma, kind)
+        assert relerr(dv.kmv(V, 1, ldv=t + 1, ldo=t + 2), H @ V.astype(np.float64)) <= KMV_TOL
+        # solve with padded leading dimensions, solution written in place of the initial guess
+        ldb, ldv = t + 3, t + 2
+        Bd = torch.full((n, ldb), float("nan"), device=dv.dev)
+        Bd[:, :t] = dv.to(B)
+        Vd = torch.full((n, ldv), 7.0, device=dv.dev)
+        Vd[:, :t] = 0.0
+        work = dv.work(t)
+        rc, iters, kmv, relres = gp.gp_cg_solve(dv.ctx, Bd, ldb, Vd, Vd, ldv, t, 1e-5, 500, work, work.numel())
+        assert rc == 0 and iters <= n + 2
+        got = Vd.cpu().numpy()
+        assert (got[:, t:] == 7.0).all(), "padding columns of dV were written"
+        ref = orc.chol_solve(H, B)
+        assert relerr(got[:, :t], ref) <= 1e-3
+        g = gp.gp_mll_grad(dv.ctx, Vd, ldv, Bd, ldb, t, d)
+        gref = orc.mll_grad_hutchinson(X, ell, a, sigma, kind, B, V=got[:, :t])
+        assert np.isfinite(g).all() and relerr(g, gref) <= GRAD_TOL
+        Xs = rng.standard_normal((5, d)).astype(np.float32)
+        assert relerr(dv.predict(Xs, V), orc.cross_kmv(Xs, X, ell, a, kind, V)) <= KMV_TOL
+    finally:
+        dv.close()
+
+
 def test_cg_sherman_morrison_at_scale():
     """ell -> inf makes H = sigma^2 I + a^2 11^T, whose inverse has a closed form at any n."""
     w = make("config3", n=150000, s=3)
