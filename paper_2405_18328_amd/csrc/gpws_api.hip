@@ -142,11 +142,20 @@ int gp_set_theta(gp_ctx* ctx, const double* h_lengthscale, double signal_scale, 
   GP_HIP(ctx, hipMemsetAsync(ctx->dMaxNorm, 0, sizeof(unsigned), ctx->stream));
   int rc = gp_launch_pack(ctx);
   if (rc < 0) return rc;
-  // the largest scaled squared norm decides which product path holds the error budget
-  float* hmax = (float*)((char*)ctx->hPinned + 4096);
-  GP_HIP(ctx, hipMemcpyAsync(hmax, ctx->dMaxNorm, sizeof(float), hipMemcpyDeviceToHost, ctx->stream));
-  GP_HIP(ctx, hipStreamSynchronize(ctx->stream));
-  ctx->max_norm = *hmax;
+  // The largest scaled squared norm decides which product path holds the error budget.  The host-side
+  // bound sum_k (xabs_k / ell_k)^2 >= max_i |xs_i|^2 settles the common case (two fp16 pieces) without a
+  // read-back; otherwise the exact maximum found by the packing kernel is fetched.
+  double bound = 0.0;
+  for (int k = 0; k < ctx->d; ++k) bound += (ctx->xabs[k] / ctx->ell[k]) * (ctx->xabs[k] / ctx->ell[k]);
+  bound *= 1.0 + 1e-5;   // fp32 rounding of the scaled inputs
+  if (bound <= (double)GP_NORM_X2_MAX && ctx->path_forced < 0) {
+    ctx->max_norm = (float)bound;
+  } else {
+    float* hmax = (float*)((char*)ctx->hPinned + 4096);
+    GP_HIP(ctx, hipMemcpyAsync(hmax, ctx->dMaxNorm, sizeof(float), hipMemcpyDeviceToHost, ctx->stream));
+    GP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->max_norm = *hmax;
+  }
   if (!std::isfinite(ctx->max_norm))
     return gp_fail(ctx, GP_ERR_ARG, "gp_set_theta: inputs scaled by the lengthscales are not finite");
   int path = ctx->max_norm <= GP_NORM_X2_MAX ? GP_PATH_F16X2

@@ -62,6 +62,7 @@ struct gp_ctx {
   double* dMean;          // d column means of X
   double* dTheta;         // device copy: 1/ell (d), then a, sigma
   bool theta_set;
+  double xabs[GP_MAX_D];  // max_i |x_ik - mean_k| per dimension (host copy, fixed at gp_create)
   double ell[GP_MAX_D];
   double a, sigma;
   // lazily grown scratch for split-column partial sums of gp_kmv / gp_mll_grad

@@ -23,6 +23,29 @@ __global__ void column_mean_kernel(const float* __restrict__ X, int64_t n, int d
   if (threadIdx.x == 0) mean[k] = red[0] / (double)n;
 }
 
+// one workgroup per input dimension: max_i |x_ik - mean_k| (max is order-independent, so exact and reproducible)
+__global__ void column_absdev_kernel(const float* __restrict__ X, int64_t n, int d, const double* __restrict__ mean,
+                                     double* __restrict__ out) {
+  const int k = blockIdx.x;
+  const double mu = mean[k];
+  double m = 0.0;
+  for (int64_t i = threadIdx.x; i < n; i += blockDim.x) {
+    const double v = fabs((double)X[i * d + k] - mu);
+    m = (v > m || v != v) ? v : m;      // a NaN input propagates
+  }
+  __shared__ double red[256];
+  red[threadIdx.x] = m;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) {
+      const double o = red[threadIdx.x + w];
+      if (o > red[threadIdx.x] || o != o) red[threadIdx.x] = o;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[k] = red[0];
+}
+
 // one thread per row: scaled centred row, its squared norm, and both packed operands
 __global__ void pack_kernel(const float* __restrict__ X, int64_t n, int64_t n_pad, int d, int KS,
                             const double* __restrict__ mean, const double* __restrict__ theta /* 1/ell (d) */,
@@ -120,6 +143,16 @@ int gp_launch_column_means(gp_ctx* ctx) {
   hipLaunchKernelGGL(column_mean_kernel, dim3(ctx->d), dim3(256), 0, ctx->stream, ctx->dX, ctx->n, ctx->d,
                      ctx->dMean);
   GP_HIP(ctx, hipGetLastError());
+  // per-dimension spread, kept on the host: sum_k (xabs_k / ell_k)^2 bounds every scaled squared norm, which
+  // lets gp_set_theta choose the product path without reading anything back in the common case
+  double* dabs = ctx->dRed;
+  hipLaunchKernelGGL(column_absdev_kernel, dim3(ctx->d), dim3(256), 0, ctx->stream, ctx->dX, ctx->n, ctx->d,
+                     (const double*)ctx->dMean, dabs);
+  GP_HIP(ctx, hipGetLastError());
+  double* h = (double*)ctx->hPinned;
+  GP_HIP(ctx, hipMemcpyAsync(h, dabs, sizeof(double) * ctx->d, hipMemcpyDeviceToHost, ctx->stream));
+  GP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  for (int k = 0; k < ctx->d; ++k) ctx->xabs[k] = h[k];
   return GP_OK;
 }
 
