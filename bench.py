@@ -244,7 +244,10 @@ def main():
             "metric": "matrix-free K.V TFLOP/s (% FP32 peak) + CG time per MLL step, warm vs cold",
             "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
             "ms_per_step": wall / steps * 1e3, "higher_is_better": True, "scaling": "weak",
-            "vs_baseline": None, "dtype": "f32" if path == 0 else "f32 (fp16x2-split matrix-core products, fp32 accumulate)",
+            "vs_baseline": None, "dtype": "f32",
+            "dtype_note": ("fp32 data, fp32 matrix-core products and accumulation" if path == 0 else
+                           "fp32 data and accumulation; every fp32 product formed from split-fp16 matrix-core "
+                           "products (relative error 2^-22), kernel function in fp32"),
             "data": "synthetic",
             "config": {"workload": desc, "n": n, "d": d, "t": t, "kernel": w.kind, "max_iters": max_iters,
                        "kmv_products_timed": int(n_kmv), "input_generation_s": round(t_gen, 1)},
