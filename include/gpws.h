@@ -17,7 +17,8 @@
  *     1..s are the probes z_j; t = s + 1.
  *   - All work is enqueued on the HIP stream given to gp_create.  Calls that
  *     return host results (gp_cg_solve, gp_mll_grad) synchronise that stream
- *     before returning; gp_set_theta and gp_kmv do not.
+ *     before returning; gp_set_theta waits for earlier work on the stream and
+ *     may synchronise once more (see there); gp_kmv is asynchronous.
  *   - theta = (ell_1..ell_d, a, sigma): lengthscales, signal scale (amplitude,
  *     K is proportional to a^2), noise scale (H = K + sigma^2 I).
  *   - No call aborts or throws.  Return value: 0 = GP_OK, > 0 = result usable
@@ -73,8 +74,14 @@ int gp_destroy(gp_ctx* ctx);
 /*
  * Set the hyperparameters theta (Section 2: theta = {vartheta, sigma}).
  * h_lengthscale: d positive doubles; signal_scale > 0; noise_scale >= 0.
- * Rebuilds the scaled copy of the inputs the tile kernels read (O(n d) device
- * work, asynchronous).  Must be called before any of the calls below.
+ * Rebuilds the scaled copies of the inputs the tile kernels read (O(n d) device
+ * work) and chooses the arithmetic of the tile pass (see gp_product_path) from
+ * the largest scaled squared norm.  Waits for earlier work on the stream (a
+ * pinned staging block is reused); the packing itself is left running unless
+ * the norm has to be read back, which happens only when a bound kept on the
+ * host does not already settle the choice.  Must be called before any of the
+ * calls below.  Errors: GP_ERR_ARG for non-positive or non-finite values, or
+ * inputs that are not finite after scaling.
  */
 int gp_set_theta(gp_ctx* ctx, const double* h_lengthscale, double signal_scale, double noise_scale);
 
