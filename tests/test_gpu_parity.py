@@ -101,10 +101,13 @@ def test_kmv_every_product_path(monkeypatch, path, name, kw):
         dv.close()
 
 
-@pytest.mark.parametrize("kind", ["se", "matern32"])
-def test_kmv_and_gradient_at_the_largest_dimension(kind):
+@pytest.mark.parametrize("kind,path", [("se", None), ("matern32", None), ("matern32", "f16x3"), ("se", "f16x3")])
+def test_kmv_and_gradient_at_the_largest_dimension(monkeypatch, kind, path):
     """d = 126 (the documented maximum): the SE operand set no longer fits the widest fp16 bucket and
-    the product must fall back to fp32; Matern-3/2 still fits."""
+    the product must fall back to fp32 (also when another path is asked for); Matern-3/2 still fits,
+    with two pieces by default and with three (the largest kernels of the library) when pinned."""
+    if path:
+        monkeypatch.setenv("GPWS_PATH", path)
     rng = np.random.default_rng(126)
     n, d, t = 700, 126, 5
     X = rng.standard_normal((n, d)).astype(np.float32)
@@ -113,7 +116,7 @@ def test_kmv_and_gradient_at_the_largest_dimension(kind):
     B = rng.standard_normal((n, t)).astype(np.float32)
     dv = Dev(X, kind, ell, 1.2, 0.3)
     try:
-        assert dv.gp.gp_product_path(dv.ctx) == (0 if kind == "se" else 1)
+        assert dv.gp.gp_product_path(dv.ctx) == (0 if kind == "se" else (2 if path else 1))
         assert relerr(dv.kmv(V, 1), orc.kmv_dense(X, ell, 1.2, kind, V, sigma=0.3)) <= KMV_TOL
         g = dv.grad(dv.to(V), dv.to(B))
         assert relerr(g, orc.mll_grad_hutchinson(X, ell, 1.2, 0.3, kind, B, V=V)) <= GRAD_TOL
