@@ -66,6 +66,17 @@ def test_config2_full_size_mll_steps_sampled_against_oracle():
         g_sigma = 2.0 * sigma * (0.5 * V[:, 0] @ V[:, 0] - 0.5 * np.sum(V[:, 1:] * B[:, 1:]) / w.s)
         assert abs(last.grad[w.d + 1] - g_sigma) <= 1e-3 * max(abs(g_sigma), sigma * (V[:, 0] @ V[:, 0]))
         assert np.isfinite(last.grad).all()
+        # gradient: amplitude component dH/da = 2K/a, formed from the product K [v_y, Z] of the K V tile
+        # kernel (checked against the oracle on the sampled rows above) -- a different kernel from the
+        # gradient pass, so this ties the two together at full size
+        C = opt.B.clone()
+        C[:, 0] = opt.V[:, 0]
+        KC = torch.empty_like(C)
+        gp.gp_kmv(opt.ctx, C, t, t, KC, t, 0)
+        torch.cuda.synchronize()
+        KC = KC.cpu().numpy().astype(np.float64)
+        g_a = (2.0 / a) * (0.5 * V[:, 0] @ KC[:, 0] - 0.5 * np.sum(V[:, 1:] * KC[:, 1:]) / w.s)
+        assert abs(last.grad[w.d] - g_a) <= 1e-3 * np.abs(last.grad).max()
     finally:
         opt.close()
 
