@@ -160,6 +160,7 @@ __global__ __launch_bounds__(VT) void cg_dot_kernel(const float* __restrict__ P,
     if (JS > 1) {
       hp = f32x4{0.f, 0.f, 0.f, 0.f};
       if (vec_ok && e + 4 <= valid) {
+#pragma unroll 4
         for (int k = 0; k < JS; ++k) hp += *reinterpret_cast<const f32x4*>(part_in + (int64_t)k * part_stride + e);
       } else {
 #pragma unroll
