@@ -86,16 +86,36 @@ __device__ __forceinline__ void thread_columns(int t, int64_t e0, int c[4]) {
   }
 }
 
+// H p (or H x0) at flat positions e..e+3 as the fixed-order sum of the JS column-split partials the
+// product left (flat index e = i t + c in every partial; positions at or past `valid` are padding: 0).
+__device__ __forceinline__ f32x4 sum_split_partials(const float* __restrict__ part_in, int64_t part_stride, int JS,
+                                                    int64_t e, int64_t valid) {
+  f32x4 hp = f32x4{0.f, 0.f, 0.f, 0.f};
+  if ((part_stride & 3) == 0 && e + 4 <= valid) {
+#pragma unroll 4
+    for (int k = 0; k < JS; ++k) hp += *reinterpret_cast<const f32x4*>(part_in + (int64_t)k * part_stride + e);
+  } else {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (e + q < valid)
+        for (int k = 0; k < JS; ++k) hp[q] += part_in[(int64_t)k * part_stride + e + q];
+  }
+  return hp;
+}
+
 // X <- X0 (or 0), R <- B, partial ||b||^2.  Rows >= n of the padded arrays are zeroed.
 __global__ __launch_bounds__(VT) void cg_load_kernel(const float* __restrict__ B, int64_t ldb,
                                                      const float* __restrict__ X0, int64_t ldx, int64_t n,
                                                      int64_t n4, int t, float* __restrict__ X,
-                                                     float* __restrict__ R, double* __restrict__ part) {
+                                                     float* __restrict__ R, double* __restrict__ part,
+                                                     unsigned* __restrict__ colmax) {
   __shared__ float sh[VW];
+  __shared__ unsigned smax[GP_MAX_T];
   const int64_t total = n4 * t;
-  const int64_t stride = (int64_t)gridDim.x * VW;
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int64_t e = ((int64_t)blockIdx.x * VT + threadIdx.x) * 4; e < total; e += stride) {
+  const int64_t stride = (int64_t)gridDim.x * VW;   // a multiple of t: a thread keeps its four columns
+  const int64_t e0 = ((int64_t)blockIdx.x * VT + threadIdx.x) * 4;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f}, mx[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int64_t e = e0; e < total; e += stride) {
     f32x4 b, x;
     int64_t i = e / t;
     int c = (int)(e - i * t);
@@ -105,17 +125,26 @@ __global__ __launch_bounds__(VT) void cg_load_kernel(const float* __restrict__ B
       b[q] = live ? B[i * ldb + c] : 0.0f;
       x[q] = (live && X0) ? X0[i * ldx + c] : 0.0f;
       acc[q] = fmaf(b[q], b[q], acc[q]);
+      mx[q] = fmaxf(mx[q], fabsf(x[q]));
       if (++c == t) { c = 0; ++i; }
     }
     *reinterpret_cast<f32x4*>(X + e) = x;
     *reinterpret_cast<f32x4*>(R + e) = b;
   }
   block_column_sums(acc, t, (int)(((int64_t)blockIdx.x * VW) % t), part + (int64_t)blockIdx.x * t, sh);
+  if (X0) {   // max |X0| per column for the warm start's product H x0
+    int cq[4];
+    thread_columns(t, e0, cq);
+    block_column_max(mx, cq, t, colmax, smax);
+  }
 }
 
-// R <- R - HX (warm start: initial residual), then (both cases) P <- R, partial r^T r
+// R <- R - HX (warm start: initial residual), then (both cases) P <- R, partial r^T r.  HX is read from
+// the product's column-split partials when it left them unsummed (JS > 1).
 __global__ __launch_bounds__(VT) void cg_resid_kernel(float* __restrict__ R, const float* __restrict__ HX,
-                                                      int subtract, float* __restrict__ P, int64_t total, int t,
+                                                      const float* __restrict__ part_in, int64_t part_stride,
+                                                      int JS, int64_t valid, int subtract,
+                                                      float* __restrict__ P, int64_t total, int t,
                                                       double* __restrict__ part, unsigned* __restrict__ colmax) {
   __shared__ float sh[VW];
   __shared__ unsigned smax[GP_MAX_T];
@@ -127,7 +156,8 @@ __global__ __launch_bounds__(VT) void cg_resid_kernel(float* __restrict__ R, con
   for (int64_t e = e0; e < total; e += stride) {
     f32x4 r = *reinterpret_cast<const f32x4*>(R + e);
     if (subtract) {
-      const f32x4 hx = *reinterpret_cast<const f32x4*>(HX + e);
+      const f32x4 hx = JS > 1 ? sum_split_partials(part_in, part_stride, JS, e, valid)
+                              : *reinterpret_cast<const f32x4*>(HX + e);
       r -= hx;
       *reinterpret_cast<f32x4*>(R + e) = r;
     }
@@ -152,22 +182,12 @@ __global__ __launch_bounds__(VT) void cg_dot_kernel(const float* __restrict__ P,
   __shared__ float sh[VW];
   if (flags->all_done) return;
   const int64_t stride = (int64_t)gridDim.x * VW;
-  const bool vec_ok = (part_stride & 3) == 0;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   for (int64_t e = ((int64_t)blockIdx.x * VT + threadIdx.x) * 4; e < total; e += stride) {
     const f32x4 p = *reinterpret_cast<const f32x4*>(P + e);
     f32x4 hp;
     if (JS > 1) {
-      hp = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (vec_ok && e + 4 <= valid) {
-#pragma unroll 4
-        for (int k = 0; k < JS; ++k) hp += *reinterpret_cast<const f32x4*>(part_in + (int64_t)k * part_stride + e);
-      } else {
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-          if (e + q < valid)
-            for (int k = 0; k < JS; ++k) hp[q] += part_in[(int64_t)k * part_stride + e + q];
-      }
+      hp = sum_split_partials(part_in, part_stride, JS, e, valid);
       *reinterpret_cast<f32x4*>(HP + e) = hp;
     } else {
       hp = *reinterpret_cast<const f32x4*>(HP + e);
@@ -479,15 +499,20 @@ int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
   };
 
   int kmv_count = 0;
-  hipLaunchKernelGGL(cg_load_kernel, grid, block, 0, st, dB, ldb, dX0, ldv, ctx->n, L.n4, t, X, R, s.part2);
+  // the load kernel leaves max |X0| per column for the warm start's product, whose column-split
+  // partials the residual kernel sums itself
+  KmvDeferred df0 = {nullptr, 0, 1};
+  if (dX0) GP_HIP(ctx, hipMemsetAsync(s.colmax, 0, sizeof(unsigned) * t, st));
+  hipLaunchKernelGGL(cg_load_kernel, grid, block, 0, st, dB, ldb, dX0, ldv, ctx->n, L.n4, t, X, R, s.part2, s.colmax);
   GP_HIP(ctx, hipGetLastError());
   if (dX0) {
-    int rc = gp_kmv_launch(ctx, X, t, t, HP, t, 1, kmv_scratch, L.kmv_bytes, nullptr);
+    int rc = gp_kmv_launch(ctx, X, t, t, HP, t, 1, kmv_scratch, L.kmv_bytes, s.colmax, nullptr, &df0);
     if (rc < 0) return rc;
     ++kmv_count;
   }
   GP_HIP(ctx, hipMemsetAsync(s.colmax, 0, sizeof(unsigned) * t, st));
-  hipLaunchKernelGGL(cg_resid_kernel, grid, block, 0, st, R, (const float*)HP, dX0 ? 1 : 0, P, total, t, s.part, s.colmax);
+  hipLaunchKernelGGL(cg_resid_kernel, grid, block, 0, st, R, (const float*)HP, df0.part, df0.stride, df0.JS,
+                     ctx->n * (int64_t)t, dX0 ? 1 : 0, P, total, t, s.part, s.colmax);
   hipLaunchKernelGGL(cg_fin_init_kernel, dim3(1), dim3(FT), 0, st, s, L.G, t, 1);
   GP_HIP(ctx, hipGetLastError());
   {

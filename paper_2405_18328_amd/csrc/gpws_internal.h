@@ -147,8 +147,10 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
                       int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax,
                       const KmvRows* rows, KmvDeferred* defer);
 
-// colmax[c] = bit pattern of max_i |V_ic| for c < t (cleared first); stream-ordered
-int gp_launch_colmax(gp_ctx* ctx, const float* dV, int64_t ldv, int t, unsigned* colmax);
+// colmax[c] = bit pattern of max_i |V_ic| for c < t, stream-ordered; optionally the same for a second
+// n x t matrix in the same launch.  cleared = true: the caller has already zeroed the output words.
+int gp_launch_colmax(gp_ctx* ctx, const float* dV, int64_t ldv, int t, unsigned* colmax, const float* dV2 = nullptr,
+                     int64_t ldv2 = 0, unsigned* colmax2 = nullptr, bool cleared = false);
 
 // ---- cg_kernels.hip
 int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv,

@@ -494,10 +494,8 @@ int gp_grad_run_f16(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, 
   int* scales = (int*)w;
   hipStream_t st = ctx->stream;
 
-  GP_HIP(ctx, hipMemsetAsync(acc, 0, acc_bytes, st));
-  rc = gp_launch_colmax(ctx, dV, ldv, t, cmV);
-  if (rc < 0) return rc;
-  rc = gp_launch_colmax(ctx, dB, ldb, t, cmB);
+  GP_HIP(ctx, hipMemsetAsync(acc, 0, acc_bytes + 2 * cm_bytes, st));   // acc, cmV, cmB lie back to back
+  rc = gp_launch_colmax(ctx, dV, ldv, t, cmV, dB, ldb, cmB, true);
   if (rc < 0) return rc;
 
   // Q' = 2^qshift Q with max |Q| = max(1, max_i |xs_i|^2) kept below 2^15

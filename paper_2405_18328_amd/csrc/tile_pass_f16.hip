@@ -395,8 +395,15 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 
 // ---- per-call operand preparation -------------------------------------------------------------
 // colmax[c] = max_i |V_ic| as a bit pattern (non-negative floats order like unsigned ints)
-__global__ __launch_bounds__(256) void colmax_kernel(const float* __restrict__ V, int64_t ldv, int64_t n, int t,
-                                                     unsigned* __restrict__ colmax) {
+// blockIdx.y = 1 does the same for a second matrix of the same shape.
+__global__ __launch_bounds__(256) void colmax_kernel(const float* __restrict__ V, int64_t ldv,
+                                                     const float* __restrict__ V2, int64_t ldv2, int64_t n, int t,
+                                                     unsigned* __restrict__ colmax, unsigned* __restrict__ colmax2) {
+  if (blockIdx.y) {
+    V = V2;
+    ldv = ldv2;
+    colmax = colmax2;
+  }
   // a thread keeps one column (per group of 256 columns) and walks rows: consecutive threads read
   // consecutive columns of a row, the running maximum stays in a register
   extern __shared__ unsigned smax[];   // [t]
@@ -568,13 +575,18 @@ KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx, int64_t rows) {
   return pl;
 }
 
-int gp_launch_colmax(gp_ctx* ctx, const float* dV, int64_t ldv, int t, unsigned* cm) {
-  GP_HIP(ctx, hipMemsetAsync(cm, 0, (size_t)t * sizeof(unsigned), ctx->stream));
+int gp_launch_colmax(gp_ctx* ctx, const float* dV, int64_t ldv, int t, unsigned* cm, const float* dV2, int64_t ldv2,
+                     unsigned* cm2, bool cleared) {
+  if (!cleared) {
+    GP_HIP(ctx, hipMemsetAsync(cm, 0, (size_t)t * sizeof(unsigned), ctx->stream));
+    if (dV2) GP_HIP(ctx, hipMemsetAsync(cm2, 0, (size_t)t * sizeof(unsigned), ctx->stream));
+  }
   // few workgroups: every one ends with t atomic maxima on the same t words
   int blocks = (int)((ctx->n * (int64_t)t + 8191) / 8192);
   if (blocks > 2 * ctx->num_cu) blocks = 2 * ctx->num_cu;
   if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(colmax_kernel, dim3(blocks), dim3(256), (size_t)t * sizeof(unsigned), ctx->stream, dV, ldv, ctx->n, t, cm);
+  hipLaunchKernelGGL(colmax_kernel, dim3(blocks, dV2 ? 2 : 1), dim3(256), (size_t)t * sizeof(unsigned), ctx->stream, dV,
+                     ldv, dV2, ldv2, ctx->n, t, cm, cm2);
   GP_HIP(ctx, hipGetLastError());
   return GP_OK;
 }
