@@ -28,8 +28,9 @@ formula, and never mentions the squared exponential):
 Pin status: every function below is pinned by tests/test_oracle_pins.py against
 something other than itself (scikit-learn / SciPy library routines, hand values,
 closed forms, finite differences, brute force).  The only unpinned quantity is
-the warm-vs-cold iteration *count* (the paper gives it only as stripped figures):
-"parity unpinned" for iteration numbers; the solutions themselves are pinned.
+the warm-vs-cold iteration *count* of either solver (the paper gives it only as
+stripped figures): "parity unpinned" for iteration numbers; the solutions
+themselves are pinned.
 """
 from __future__ import annotations
 
@@ -272,6 +273,71 @@ def cg_batched(matvec, B, X0=None, tol=0.01, max_iters=1000):
 def dense_matvec(H):
     H = _f64(H)
     return lambda P: H @ P
+
+
+# --------------------------------------------------------------------------
+# Alternating projections as the linear system solver (Section 2.1 names it and
+# cites Wu et al., 2024; Appendix B fixes the block size 2000 and the stopping
+# rule; the steps below are that published method as read here:
+#   - the n indices are cut into consecutive blocks of `block` indices (the last
+#     one may be shorter);
+#   - every step picks ONE block for the whole batch, the one whose residual
+#     rows have the largest squared norm summed over the columns still being
+#     updated (greedy rule), lowest index on a tie;
+#   - the block's sub-system H[I,I] d = R[I,:] is solved exactly through the
+#     Cholesky factor of H[I,I]; then V[I,:] += d and R -= H[:,I] d, so R stays
+#     the residual B - H V and the quadratic objective of Section 2.1 is
+#     minimised exactly over the coordinates I;
+#   - a column stops being updated once ||r_c|| / ||b_c|| < tol_c (strict), as
+#     in cg_batched; max_iters caps the number of block updates.)
+# --------------------------------------------------------------------------
+def ap_blocks(n, block):
+    """[(start, stop)] of the consecutive index blocks."""
+    return [(j, min(n, j + block)) for j in range(0, n, block)]
+
+
+def ap_batched(H, B, X0=None, tol=0.01, block=2000, max_iters=10000):
+    """Alternating projections on the dense coefficient matrix H (n x n).
+
+    Returns (V, iters, relres, picks): iters = block updates done, relres = final
+    relative residuals (R is updated, never recomputed, as in the method), picks =
+    the block index chosen at every step.
+    """
+    H = _f64(H)
+    B = _f64(B)
+    n, t = B.shape
+    tol = np.broadcast_to(np.asarray(tol, dtype=np.float64), (t,)).copy()
+    blocks = ap_blocks(n, block)
+    factors = [sla.cho_factor(H[j0:j1, j0:j1], lower=True) for (j0, j1) in blocks]
+    bnorm = np.sqrt(np.sum(B * B, axis=0))
+    if X0 is None:
+        V = np.zeros_like(B)
+        R = B.copy()
+    else:
+        V = _f64(X0).copy()
+        R = B - H @ V
+    zero_rhs = bnorm == 0.0
+    V[:, zero_rhs] = 0.0
+    R[:, zero_rhs] = 0.0
+    safe = np.where(zero_rhs, 1.0, bnorm)
+    relres = np.sqrt(np.sum(R * R, axis=0)) / safe
+    frozen = zero_rhs | (relres < tol)
+    iters = 0
+    picks = []
+    while not frozen.all() and iters < max_iters:
+        live = ~frozen
+        score = np.array([np.sum(R[j0:j1][:, live] ** 2) for (j0, j1) in blocks])
+        k = int(np.argmax(score))
+        j0, j1 = blocks[k]
+        D = np.zeros((j1 - j0, t))
+        D[:, live] = sla.cho_solve(factors[k], R[j0:j1][:, live])
+        V[j0:j1] += D
+        R -= H[:, j0:j1] @ D
+        iters += 1
+        picks.append(k)
+        relres = np.where(live, np.sqrt(np.sum(R * R, axis=0)) / safe, relres)
+        frozen = frozen | (relres < tol)
+    return V, iters, relres, picks
 
 
 # --------------------------------------------------------------------------

@@ -270,6 +270,122 @@ def test_cg_stopping_rule_freeze_and_warm_start():
     assert it_cap == 2 and (rr[:-1] > 1e-12).any()
 
 
+# ---------------------------------------------------------------- alternating projections
+def _objective(H, B, V):
+    """The quadratic of Section 2.1, one value per column."""
+    return 0.5 * np.einsum("ic,ij,jc->c", V, H, V) - np.einsum("ic,ic->c", V, B)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_ap_reaches_the_library_solution(kind):
+    n = 45
+    X, ell, a, sigma, y, Z = _problem(n, 2, 31)
+    H = orc.coefficient_matrix(X, ell, a, sigma, kind)
+    B = np.concatenate([y[:, None], Z], axis=1)
+    V, iters, relres, picks = orc.ap_batched(H, B, tol=1e-10, block=7, max_iters=5000)
+    assert len(picks) == iters and max(picks) == 6 and min(picks) == 0      # 45 = 6 * 7 + 3: seven blocks
+    np.testing.assert_allclose(V, np.linalg.solve(H, B), rtol=1e-7, atol=1e-9)
+    true_rel = np.linalg.norm(H @ V - B, axis=0) / np.linalg.norm(B, axis=0)
+    assert (true_rel < 1.0001e-10).all() and (relres < 1e-10).all()
+    # one block covering everything is a direct solve
+    V1, it1, _, _ = orc.ap_batched(H, B, tol=1e-10, block=n + 5)
+    assert it1 == 1
+    np.testing.assert_allclose(V1, np.linalg.solve(H, B), rtol=1e-9, atol=1e-11)
+
+
+def test_ap_block_diagonal_system_needs_one_visit_per_block_in_greedy_order():
+    rng = np.random.default_rng(32)
+    sizes = [5, 5, 5, 3]
+    mats = []
+    for m in sizes:
+        A = rng.standard_normal((m, m))
+        mats.append(A @ A.T + m * np.eye(m))
+    H = sla.block_diag(*mats)
+    B = rng.standard_normal((18, 3)) * np.repeat(np.array([1.0, 4.0, 2.0, 0.5]), sizes)[:, None]
+    V, iters, _, picks = orc.ap_batched(H, B, tol=1e-12, block=5)
+    assert iters == 4
+    norms = [np.sum(B[j0:j1] ** 2) for (j0, j1) in orc.ap_blocks(18, 5)]
+    assert picks == list(np.argsort(norms)[::-1])         # largest residual first, every block once
+    np.testing.assert_allclose(V, np.linalg.solve(H, B), rtol=1e-10, atol=1e-12)
+
+
+def test_ap_single_steps_are_exact_block_minimisations():
+    """After a step the residual vanishes on the chosen block, nothing outside the block moved, the
+    chosen block was the one with the largest residual, and the objective fell by
+    1/2 r_I^T H_II^{-1} r_I (the exact gain of minimising over the block's coordinates)."""
+    n, b = 33, 8
+    X, ell, a, sigma, y, Z = _problem(n, 3, 33)
+    H = orc.coefficient_matrix(X, ell, a, sigma, orc.MATERN32)
+    B = np.concatenate([y[:, None], Z], axis=1)
+    V = np.zeros_like(B)
+    last = None
+    for step in range(12):
+        R = B - H @ V
+        Vn, it, _, picks = orc.ap_batched(H, B, X0=V, tol=1e-14, block=b, max_iters=1)
+        assert it == 1
+        j0 = picks[0] * b
+        j1 = min(n, j0 + b)
+        scores = [np.sum(R[s:min(n, s + b)] ** 2) for s in range(0, n, b)]
+        assert picks[0] == int(np.argmax(scores)) and picks[0] != last
+        last = picks[0]
+        Rn = B - H @ Vn
+        assert np.abs(Rn[j0:j1]).max() < 1e-12 * np.abs(B).max()
+        outside = np.ones(n, bool)
+        outside[j0:j1] = False
+        assert np.array_equal(Vn[outside], V[outside])
+        gain = 0.5 * np.einsum("ic,ic->c", R[j0:j1], np.linalg.solve(H[j0:j1, j0:j1], R[j0:j1]))
+        np.testing.assert_allclose(_objective(H, B, V) - _objective(H, B, Vn), gain, rtol=1e-8)
+        V = Vn
+
+
+def test_ap_coordinate_case_against_a_scalar_loop():
+    """block = 1, one right-hand side: greedy coordinate descent, written out with scalars."""
+    n = 12
+    X, ell, a, sigma, y, _ = _problem(n, 2, 34)
+    H = orc.coefficient_matrix(X, ell, a, sigma, orc.SE)
+    v = [0.0] * n
+    r = [float(b) for b in y]
+    for _ in range(25):
+        i = max(range(n), key=lambda q: (r[q] * r[q], -q))
+        step = r[i] / H[i, i]
+        v[i] += step
+        for q in range(n):
+            r[q] -= H[q, i] * step
+    V, iters, _, _ = orc.ap_batched(H, y[:, None], tol=1e-300, block=1, max_iters=25)
+    assert iters == 25
+    np.testing.assert_allclose(V[:, 0], v, rtol=1e-12, atol=1e-14)
+
+
+def test_ap_stopping_rule_freeze_and_warm_start():
+    n = 40
+    X, ell, a, sigma, y, Z = _problem(n, 3, 35)
+    H = orc.coefficient_matrix(X, ell, a, sigma, orc.MATERN32)
+    B = np.concatenate([y[:, None], Z, np.zeros((n, 1))], axis=1)      # last column: b = 0
+    tol = np.array([0.01] + [0.1] * Z.shape[1] + [0.01])               # Appendix B tolerances
+    V, iters, relres, _ = orc.ap_batched(H, B, tol=tol, block=9, max_iters=5000)
+    assert (relres < tol).all() and np.all(V[:, -1] == 0.0)
+    true_rel = np.linalg.norm(H @ V[:, :-1] - B[:, :-1], axis=0) / np.linalg.norm(B[:, :-1], axis=0)
+    assert (true_rel < tol[:-1] * 1.0001).all()
+    # a column that meets its tolerance is no longer touched while the others go on
+    X0 = np.linalg.solve(H, B) * 1.2
+    X0[:, 0] = 0.0
+    loose = np.array([1e-6] + [0.5] * Z.shape[1] + [0.01])
+    Vf, it_f, _, _ = orc.ap_batched(H, B, X0=X0, tol=loose, block=9, max_iters=5000)
+    assert it_f > 0 and np.array_equal(Vf[:, 1:-1], X0[:, 1:-1]) and not np.array_equal(Vf[:, 0], X0[:, 0])
+    # x0 = an exact solution: zero steps, solution returned unchanged
+    Vstar = np.linalg.solve(H, B)
+    V2, it2, _, p2 = orc.ap_batched(H, B, X0=Vstar, tol=1e-8, block=9)
+    assert it2 == 0 and p2 == [] and np.array_equal(V2, Vstar)
+    # warm start from the solution at nearby hyperparameters needs fewer steps (Section 3)
+    H2 = orc.coefficient_matrix(X, ell * 1.02, a, sigma, orc.MATERN32)
+    _, it_cold, _, _ = orc.ap_batched(H2, B, tol=1e-3, block=9)
+    _, it_warm, _, _ = orc.ap_batched(H2, B, X0=Vstar, tol=1e-3, block=9)
+    assert it_warm < it_cold
+    # the cap on block updates is honoured
+    _, it_cap, rr, _ = orc.ap_batched(H, B, tol=1e-12, block=9, max_iters=3)
+    assert it_cap == 3 and (rr[:-1] > 1e-12).any()
+
+
 def test_warm_start_first_order_taylor_is_second_order_accurate():
     """Section 3: v(t+1) ~ v(t) - H_t^{-1} (H_{t+1} - H_t) v(t); halving the step
     in theta must quarter the error of that approximation."""
