@@ -125,6 +125,35 @@ int gp_cg_solve(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, flo
                 int* h_iters, int* h_kmv_count, float* h_relres);
 
 /*
+ * The same batched system solved by alternating projections (Section 2.1 names the method and cites
+ * Wu et al., 2024; Appendix B: block size 2000, the same stopping rule as for conjugate gradients).
+ * The n indices are cut into consecutive blocks of `block` indices (the last may be shorter).  Each
+ * step picks, for the whole batch, the block whose residual rows have the largest squared norm over
+ * the columns still being updated (lowest index on a tie), solves that block's sub-system
+ * H[I,I] d = R[I,:] exactly, adds d to V[I,:] and subtracts H[:,I] d from the residual, which is
+ * therefore tracked, never recomputed.  Column c is no longer updated once
+ * ||r_c|| / ||b_c|| < tol_c; a column with b_c = 0 gets the solution 0.
+ *   dB, dX0, dV, ldb, ldv, t, h_tol, h_relres: as for gp_cg_solve (dX0 != NULL is the warm start of
+ *          Section 3 and costs one full product for the initial residual).
+ *   block : 1 .. GP_AP_MAX_BLOCK.
+ *   max_iters >= 0: cap on the number of block updates.
+ *   dWork/work_bytes: device scratch, at least gp_ap_workspace_bytes(ctx, t, block), 256-byte
+ *          aligned.  It holds, besides the solver's vectors, the inverse of every diagonal block
+ *          (about 4 * n * block bytes), rebuilt by every call for the current theta.
+ *   h_iters     : out, block updates done.
+ *   h_kmv_count : out, full n x n products done (0, or 1 for a warm start).
+ *   h_picks     : out or NULL, max_iters ints: the block index chosen at every step.
+ * Returns GP_OK, GP_NOT_CONVERGED (dV holds the last iterate), GP_ERR_BREAKDOWN when a diagonal
+ * block is not numerically positive definite, or an argument/workspace/HIP error.
+ * Synchronises the stream.
+ */
+#define GP_AP_MAX_BLOCK 2048
+size_t gp_ap_workspace_bytes(const gp_ctx* ctx, int t, int block);
+int gp_ap_solve(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv,
+                int t, const float* h_tol, int block, int max_iters, void* dWork, size_t work_bytes,
+                int* h_iters, int* h_kmv_count, float* h_relres, int* h_picks);
+
+/*
  * Stochastic estimate of the gradient of the log marginal likelihood (Section 2
  * gradient equation with the trace replaced by the s-probe estimator of
  * Section 2.1, normalised by 1/s):

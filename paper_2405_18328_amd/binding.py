@@ -28,8 +28,10 @@ GP_MAX_T = 1024
 # GPWS_LIB names another build of the library (developer aid for side-by-side timing of two builds)
 LIB_PATH = os.environ.get("GPWS_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgpws.so")
 
+GP_AP_MAX_BLOCK = 2048
+
 EXPORTS = ["gp_create", "gp_destroy", "gp_set_theta", "gp_kmv", "gp_workspace_bytes", "gp_cg_solve",
-           "gp_mll_grad", "gp_predict", "gp_profile", "gp_profile_read", "gp_product_path", "gp_last_error"]
+           "gp_ap_workspace_bytes", "gp_ap_solve", "gp_mll_grad", "gp_predict", "gp_profile", "gp_profile_read", "gp_product_path", "gp_last_error"]
 
 
 def _load():
@@ -45,6 +47,10 @@ def _load():
     lib.gp_workspace_bytes.restype = sz
     lib.gp_cg_solve.argtypes = [p, p, i64, p, p, i64, i32, C.POINTER(C.c_float), i32, p, sz,
                                 C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_float)]
+    lib.gp_ap_workspace_bytes.argtypes = [p, i32, i32]
+    lib.gp_ap_workspace_bytes.restype = sz
+    lib.gp_ap_solve.argtypes = [p, p, i64, p, p, i64, i32, C.POINTER(C.c_float), i32, i32, p, sz,
+                                C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(i32)]
     lib.gp_mll_grad.argtypes = [p, p, i64, p, i64, i32, C.POINTER(dbl)]
     lib.gp_predict.argtypes = [p, p, i64, p, i64, i32, p, i64]
     lib.gp_profile.argtypes = [p, i32]
@@ -53,7 +59,7 @@ def _load():
     lib.gp_last_error.argtypes = [p]
     lib.gp_last_error.restype = C.c_char_p
     for name in EXPORTS:
-        if name not in ("gp_workspace_bytes", "gp_last_error"):
+        if name not in ("gp_workspace_bytes", "gp_ap_workspace_bytes", "gp_last_error"):
             getattr(lib, name).restype = i32
     return lib
 
@@ -127,6 +133,25 @@ def gp_cg_solve(ctx, dB, ldb, dX0, dV, ldv, t, tol, max_iters, dWork, work_bytes
                           relres.ctypes.data_as(C.POINTER(C.c_float)))
     _check(ctx, rc)
     return rc, iters.value, kmv.value, relres
+
+
+def gp_ap_workspace_bytes(ctx, t, block):
+    return int(_lib.gp_ap_workspace_bytes(ctx, int(t), int(block)))
+
+
+def gp_ap_solve(ctx, dB, ldb, dX0, dV, ldv, t, tol, block, max_iters, dWork, work_bytes, want_picks=False):
+    """Returns (rc, iters, kmv_count, relres[t], picks or None); raises GpError on rc < 0."""
+    tol_arr = np.ascontiguousarray(np.broadcast_to(np.asarray(tol, dtype=np.float32), (t,)))
+    iters, kmv = C.c_int(0), C.c_int(0)
+    relres = np.zeros(t, dtype=np.float32)
+    picks = np.full(max(int(max_iters), 1), -1, dtype=np.int32) if want_picks else None
+    rc = _lib.gp_ap_solve(ctx, _ptr(dB), int(ldb), _ptr(dX0), _ptr(dV), int(ldv), int(t),
+                          tol_arr.ctypes.data_as(C.POINTER(C.c_float)), int(block), int(max_iters), _ptr(dWork),
+                          int(work_bytes), C.byref(iters), C.byref(kmv),
+                          relres.ctypes.data_as(C.POINTER(C.c_float)),
+                          picks.ctypes.data_as(C.POINTER(C.c_int)) if want_picks else None)
+    _check(ctx, rc)
+    return rc, iters.value, kmv.value, relres, (picks[:iters.value] if want_picks else None)
 
 
 def gp_mll_grad(ctx, dV, ldv, dB, ldb, t, d):

@@ -1,0 +1,770 @@
+// Alternating projections as the linear system solver (Section 2.1 lists it beside conjugate
+// gradients, citing Wu et al., 2024; Appendix B fixes the block size 2000 and the stopping rule).
+//
+// The n indices are cut into consecutive blocks of `block` indices.  One step: pick the block I whose
+// residual rows are largest (summed over the columns still being updated), solve H[I,I] d = R[I,:]
+// exactly, V[I,:] += d, R -= H[:,I] d.  R stays B - H V throughout.
+//
+// How the step is laid out for this chip:
+//   - set-up (once per solve, i.e. once per theta): every H[I,I] is built, factorised (Cholesky, fp64,
+//     64 x 64 tiles, many blocks side by side in one launch), and turned into its explicit inverse
+//     (triangular inverse, then L^-T L^-1), stored in fp32.  The block solve of every later step is
+//     then one dense product H[I,I]^-1 R[I,:] spread over all compute units instead of two
+//     triangular solves that a few workgroups would have to walk through row tile by row tile;
+//   - H[:,I] d is the matrix-free tile pass restricted to the block's columns (KmvWindow);
+//   - one streaming kernel applies the update and leaves per-block squared residual norms, one small
+//     kernel turns those into the stopping test and the next block, and posts both to pinned host
+//     memory for the host loop (as the CG loop does).
+// All reductions have a fixed order; the only atomics are integer maxima.
+#include <math.h>
+#include <stdint.h>
+
+#include "gpws_internal.h"
+
+namespace {
+
+constexpr int TS = 64;              // tile edge of the factorisation kernels
+constexpr int AP_SLICES = 8;        // row slices per block in the residual-norm partials
+constexpr int AP_BATCH = 32;        // blocks factorised side by side
+constexpr int SOLVE_ROWS = 8;       // rows of the inverse one workgroup of the block solve handles
+constexpr int SOLVE_PIECE = 512;    // columns of the inverse staged in LDS at a time
+
+typedef double fac_t;
+
+struct ApFlags {
+  int all_done;
+  int breakdown;
+  int iters;
+  int sel;          // block chosen for the next step
+  int seq;          // host mirror only: finalise steps posted so far (written last)
+  int pad[3];
+};
+
+struct ApDev {
+  ApFlags* flags;
+  ApFlags* post;    // pinned host memory
+  double* bn2;      // [t]
+  float* tol;       // [t]
+  float* relres;    // [t]
+  int* frozen;      // [t]
+  int* zero_rhs;    // [t]
+  unsigned* colmax; // [t] bit patterns of max |d| per column for the split-fp16 product
+  double* norms;    // [nb][AP_SLICES][t] squared residual norms per block slice
+  double* normsB;   // [nb][AP_SLICES][t] the same for B (init only)
+  double* bnorm;    // [nb][t] squared residual norms per block (finalise kernel's scratch)
+};
+
+// ---- 64 x 64 tile products in LDS -----------------------------------------------------------------
+// Operands are held contraction-index-major: out[r][c] += sum_m TA[m][r] * TB[m][c]; thread
+// (tx, ty) = (tid % 16, tid / 16) owns rows 4 ty .. 4 ty + 3 and columns 4 tx .. 4 tx + 3.
+struct Tile {
+  fac_t v[TS][TS + 1];
+};
+
+// source element (row, col) = src[row * ld + col].  by_col = false: the source row is the contraction
+// index, T[row][col] = src(row, col); by_col = true: the source column is, T[col][row] = src(row, col)
+__device__ __forceinline__ void load_tile(Tile& T, const fac_t* __restrict__ src, int64_t ld, bool by_col) {
+  for (int e = threadIdx.x; e < TS * TS; e += 256) {
+    const int rr = e / TS, cc = e % TS;
+    const fac_t v = src[(int64_t)rr * ld + cc];
+    if (by_col) T.v[cc][rr] = v;
+    else T.v[rr][cc] = v;
+  }
+}
+
+__device__ __forceinline__ void mac_tile(const Tile& TA, const Tile& TB, fac_t acc[4][4]) {
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll 4
+  for (int m = 0; m < TS; ++m) {
+    fac_t a[4], b[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      a[q] = TA.v[m][4 * ty + q];
+      b[q] = TB.v[m][4 * tx + q];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = fma(a[i], b[j], acc[i][j]);
+  }
+}
+
+__device__ __forceinline__ void clear_acc(fac_t acc[4][4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+}
+
+// ---- set-up: H[I,I], Cholesky, inverse ------------------------------------------------------------
+// A[z] (BP x BP, row-major, fp64) = H[I,I] for block blk0 + z, identity on the padding rows/columns
+__global__ __launch_bounds__(256) void ap_build_kernel(const float* __restrict__ X, int d, int64_t n,
+                                                       const double* __restrict__ theta, int kind, int block, int BP,
+                                                       int blk0, fac_t* __restrict__ A) {
+  const int64_t j0 = (int64_t)(blk0 + blockIdx.z) * block;
+  const int64_t left = n - j0;
+  const int bs = (int)(left < block ? left : block);
+  const int i = blockIdx.y * 16 + threadIdx.y, j = blockIdx.x * 16 + threadIdx.x;
+  if (i >= BP || j >= BP) return;
+  fac_t v;
+  if (i < bs && j < bs) {
+    const float* xi = X + (j0 + i) * d;
+    const float* xj = X + (j0 + j) * d;
+    double r2 = 0.0;
+    for (int k = 0; k < d; ++k) {
+      const double df = ((double)xi[k] - (double)xj[k]) * theta[k];   // theta[k] = 1 / ell_k
+      r2 = fma(df, df, r2);
+    }
+    const double a = theta[d], sg = theta[d + 1];
+    if (kind == GP_SE_ARD) {
+      v = a * a * exp(-0.5 * r2);
+    } else {
+      const double u = sqrt(3.0 * r2);
+      v = a * a * (1.0 + u) * exp(-u);
+    }
+    if (i == j) v += sg * sg;
+  } else {
+    v = (i == j) ? 1.0 : 0.0;
+  }
+  A[(int64_t)blockIdx.z * BP * BP + (int64_t)i * BP + j] = v;
+}
+
+// diagonal tile k of every block in the batch: L_kk in place (upper part zeroed), its inverse to DI
+__global__ __launch_bounds__(256) void ap_chol_diag_kernel(fac_t* __restrict__ A, int BP, int k,
+                                                           fac_t* __restrict__ DI, int* __restrict__ breakdown) {
+  __shared__ Tile T, Li;
+  fac_t* Ab = A + (int64_t)blockIdx.x * BP * BP + (int64_t)k * TS * BP + k * TS;
+  fac_t* DIb = DI + (int64_t)blockIdx.x * BP * TS + (int64_t)k * TS * TS;
+  const int tid = threadIdx.x;
+  load_tile(T, Ab, BP, false);
+  __syncthreads();
+  for (int c = 0; c < TS; ++c) {
+    const fac_t piv = T.v[c][c];
+    const bool bad = !(piv > 0.0);          // also catches NaN
+    const fac_t dg = bad ? 1.0 : sqrt(piv);
+    __syncthreads();                        // everyone holds the pivot before it is overwritten
+    if (tid == 0) {
+      T.v[c][c] = dg;
+      if (bad) *breakdown = 1;
+    }
+    if (tid > c && tid < TS) T.v[tid][c] /= dg;
+    __syncthreads();
+    for (int e = tid; e < TS * TS; e += 256) {
+      const int i = e / TS, j = e % TS;
+      if (j > c && i >= j) T.v[i][j] -= T.v[i][c] * T.v[j][c];
+    }
+    __syncthreads();
+  }
+  // column j of L_kk^-1 by forward substitution, one thread per column
+  if (tid < TS) {
+    const int j = tid;
+    for (int i = 0; i < TS; ++i) {
+      if (i < j) {
+        Li.v[i][j] = 0.0;
+      } else {
+        fac_t s = (i == j) ? 1.0 : 0.0;
+        for (int m = j; m < i; ++m) s -= T.v[i][m] * Li.v[m][j];
+        Li.v[i][j] = s / T.v[i][i];
+      }
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < TS * TS; e += 256) {
+    const int i = e / TS, j = e % TS;
+    Ab[(int64_t)i * BP + j] = (j <= i) ? T.v[i][j] : 0.0;
+    DIb[i * TS + j] = Li.v[i][j];
+  }
+}
+
+// panel below the diagonal tile: L_ik = A_ik L_kk^-T, row tile i = k + 1 + blockIdx.x
+__global__ __launch_bounds__(256) void ap_chol_panel_kernel(fac_t* __restrict__ A, int BP, int k,
+                                                            const fac_t* __restrict__ DI) {
+  __shared__ Tile TA, TB;
+  const int it = k + 1 + blockIdx.x;
+  fac_t* Aik = A + (int64_t)blockIdx.y * BP * BP + (int64_t)it * TS * BP + k * TS;
+  const fac_t* DIb = DI + (int64_t)blockIdx.y * BP * TS + (int64_t)k * TS * TS;
+  load_tile(TA, Aik, BP, true);     // A_ik(r, m)
+  load_tile(TB, DIb, TS, true);     // L_kk^-1(c, m)
+  __syncthreads();
+  fac_t acc[4][4];
+  clear_acc(acc);
+  mac_tile(TA, TB, acc);
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) Aik[(int64_t)(4 * ty + i) * BP + 4 * tx + j] = acc[i][j];
+}
+
+// trailing update A_IJ -= L_Ik L_Jk^T for the tiles I >= J > k (I = k + 1 + blockIdx.y, J = k + 1 + blockIdx.x)
+__global__ __launch_bounds__(256) void ap_chol_update_kernel(fac_t* __restrict__ A, int BP, int k) {
+  __shared__ Tile TA, TB;
+  if (blockIdx.x > blockIdx.y) return;
+  const int I = k + 1 + blockIdx.y, J = k + 1 + blockIdx.x;
+  fac_t* Ab = A + (int64_t)blockIdx.z * BP * BP;
+  load_tile(TA, Ab + (int64_t)I * TS * BP + k * TS, BP, true);   // L_Ik(r, m)
+  load_tile(TB, Ab + (int64_t)J * TS * BP + k * TS, BP, true);   // L_Jk(c, m)
+  __syncthreads();
+  fac_t acc[4][4];
+  clear_acc(acc);
+  mac_tile(TA, TB, acc);
+  fac_t* Aij = Ab + (int64_t)I * TS * BP + J * TS;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) Aij[(int64_t)(4 * ty + i) * BP + 4 * tx + j] -= acc[i][j];
+}
+
+// column panel k of X = L^-1: X_kk = L_kk^-1, X_ik = -L_ii^-1 sum_{k <= j < i} L_ij X_jk.  One workgroup
+// walks down its panel; the tiles it reads back are the ones it wrote itself.
+__global__ __launch_bounds__(256) void ap_trtri_kernel(const fac_t* __restrict__ A, int BP,
+                                                       const fac_t* __restrict__ DI, fac_t* W) {
+  __shared__ Tile TA, TB;
+  const int k = blockIdx.x, nt = BP / TS;
+  const fac_t* Ab = A + (int64_t)blockIdx.y * BP * BP;
+  const fac_t* DIb = DI + (int64_t)blockIdx.y * BP * TS;
+  fac_t* Wb = W + (int64_t)blockIdx.y * BP * BP;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  for (int e = threadIdx.x; e < TS * TS; e += 256) {
+    const int i = e / TS, j = e % TS;
+    Wb[(int64_t)(k * TS + i) * BP + k * TS + j] = DIb[(int64_t)k * TS * TS + i * TS + j];
+  }
+  __threadfence();
+  __syncthreads();
+  for (int i = k + 1; i < nt; ++i) {
+    fac_t acc[4][4];
+    clear_acc(acc);
+    for (int j = k; j < i; ++j) {
+      load_tile(TA, Ab + (int64_t)i * TS * BP + j * TS, BP, true);    // L_ij(r, m)
+      load_tile(TB, Wb + (int64_t)j * TS * BP + k * TS, BP, false);   // X_jk(m, c)
+      __syncthreads();
+      mac_tile(TA, TB, acc);
+      __syncthreads();
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) TB.v[4 * ty + a][4 * tx + b] = acc[a][b];   // S(m, c)
+    load_tile(TA, DIb + (int64_t)i * TS * TS, TS, true);                      // L_ii^-1(r, m)
+    __syncthreads();
+    fac_t out[4][4];
+    clear_acc(out);
+    mac_tile(TA, TB, out);
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) Wb[(int64_t)(i * TS + 4 * ty + a) * BP + k * TS + 4 * tx + b] = -out[a][b];
+    __threadfence();
+    __syncthreads();
+  }
+}
+
+// H[I,I]^-1 = X^T X, tiles (ti >= tj) and their mirror images, rounded to fp32
+__global__ __launch_bounds__(256) void ap_lauum_kernel(const fac_t* __restrict__ W, int BP, float* __restrict__ Hinv) {
+  __shared__ Tile TA, TB;
+  if (blockIdx.x > blockIdx.y) return;
+  const int ti = blockIdx.y, tj = blockIdx.x, nt = BP / TS;
+  const fac_t* Wb = W + (int64_t)blockIdx.z * BP * BP;
+  fac_t acc[4][4];
+  clear_acc(acc);
+  for (int m = ti; m < nt; ++m) {
+    load_tile(TA, Wb + (int64_t)m * TS * BP + ti * TS, BP, false);   // X_m,ti(q, r)
+    load_tile(TB, Wb + (int64_t)m * TS * BP + tj * TS, BP, false);   // X_m,tj(q, c)
+    __syncthreads();
+    mac_tile(TA, TB, acc);
+    __syncthreads();
+  }
+  float* Hb = Hinv + (int64_t)blockIdx.z * BP * BP;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int r = ti * TS + 4 * ty + i, c = tj * TS + 4 * tx + j;
+      const float v = (float)acc[i][j];
+      Hb[(int64_t)r * BP + c] = v;
+      Hb[(int64_t)c * BP + r] = v;
+    }
+}
+
+// ---- the iteration -------------------------------------------------------------------------------
+// Column c of thread groups: tw = min(t, 256) columns side by side, 256 / tw rows side by side.
+struct ColMap {
+  int tw, lanes, cl, rl;
+};
+__device__ __forceinline__ ColMap col_map(int t) {
+  ColMap m;
+  m.tw = t < 256 ? t : 256;
+  m.lanes = 256 / m.tw;
+  m.cl = threadIdx.x % m.tw;
+  m.rl = threadIdx.x / m.tw;
+  return m;
+}
+
+// sum the per-row-lane values of every column in a fixed order and store them as doubles
+__device__ __forceinline__ void store_column_sums(const ColMap& m, bool valid, float v, int cg, int t, float* red,
+                                                  double* __restrict__ out) {
+  if (m.rl < m.lanes) red[m.rl * m.tw + m.cl] = valid ? v : 0.0f;
+  __syncthreads();
+  if ((int)threadIdx.x < m.tw && cg + (int)threadIdx.x < t) {
+    double s = 0.0;
+    for (int l = 0; l < m.lanes; ++l) s += (double)red[l * m.tw + threadIdx.x];
+    out[cg + threadIdx.x] = s;
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ void slice_rows(int64_t n, int block, int64_t* r0, int64_t* r1) {
+  const int64_t k = blockIdx.x / AP_SLICES;
+  const int s = blockIdx.x % AP_SLICES;
+  const int64_t b0 = k * block;
+  const int64_t b1 = b0 + block < n ? b0 + block : n;
+  const int64_t per = (b1 - b0 + AP_SLICES - 1) / AP_SLICES;
+  *r0 = b0 + s * per;
+  const int64_t e = *r0 + per;
+  *r1 = e < b1 ? e : b1;
+}
+
+// V <- X0 (or 0), R <- B - HX0 (HX0 given when X0 is), D <- 0, squared norms of B and R per block slice.
+// Grid: nb * AP_SLICES workgroups, workgroup (k, s) owns slice s of block k.
+__global__ __launch_bounds__(256) void ap_init_kernel(const float* __restrict__ B, int64_t ldb,
+                                                      const float* __restrict__ X0, int64_t ldx,
+                                                      const float* __restrict__ HX0, int64_t n, int t, int block,
+                                                      float* __restrict__ V, float* __restrict__ R,
+                                                      float* __restrict__ D, double* __restrict__ norms,
+                                                      double* __restrict__ normsB) {
+  __shared__ float red[256];
+  int64_t r0, r1;
+  slice_rows(n, block, &r0, &r1);
+  const ColMap m = col_map(t);
+  for (int cg = 0; cg < t; cg += m.tw) {
+    const int c = cg + m.cl;
+    const bool valid = c < t && m.rl < m.lanes;
+    float accb = 0.0f, accr = 0.0f;
+    if (valid) {
+      for (int64_t i = r0 + m.rl; i < r1; i += m.lanes) {
+        const int64_t e = i * t + c;
+        const float b = B[i * ldb + c];
+        const float x = X0 ? X0[i * ldx + c] : 0.0f;
+        const float r = X0 ? b - HX0[e] : b;
+        V[e] = x;
+        R[e] = r;
+        D[e] = 0.0f;
+        accb = fmaf(b, b, accb);
+        accr = fmaf(r, r, accr);
+      }
+    }
+    store_column_sums(m, valid, accb, cg, t, red, normsB + (int64_t)blockIdx.x * t);
+    store_column_sums(m, valid, accr, cg, t, red, norms + (int64_t)blockIdx.x * t);
+  }
+}
+
+// d = H[I,I]^-1 R[I,:] for the columns still being updated (0 for the others), written to rows
+// j0 .. j0 + bs - 1 of D; the columns' largest |d| go to colmax (zero on entry).
+__global__ __launch_bounds__(256) void ap_solve_kernel(const float* __restrict__ Hinv, int BP, int bs,
+                                                       const float* __restrict__ R, int64_t j0, int t,
+                                                       const int* __restrict__ frozen, float* __restrict__ D,
+                                                       unsigned* __restrict__ colmax) {
+  __shared__ float hrow[SOLVE_ROWS * SOLVE_PIECE];
+  __shared__ unsigned smax[GP_MAX_T];
+  const int tid = threadIdx.x;
+  const int row0 = blockIdx.x * SOLVE_ROWS;
+  const int cl = tid & 31, rl = tid >> 5;
+  const int npass = (t + 31) / 32;
+  for (int c = tid; c < t; c += 256) smax[c] = 0u;
+  // every pass over 32 columns re-reads the staged rows; passes are few (t <= 64 in the paper's use)
+  for (int pass = 0; pass < npass; ++pass) {
+    const int c = pass * 32 + cl;
+    const bool cok = c < t;
+    const float* Rc = R + j0 * t + (cok ? c : 0);
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    for (int m0 = 0; m0 < bs; m0 += SOLVE_PIECE) {
+      const int len = bs - m0 < SOLVE_PIECE ? bs - m0 : SOLVE_PIECE;
+      __syncthreads();
+      for (int e = tid; e < SOLVE_ROWS * SOLVE_PIECE; e += 256) {
+        const int rr = e / SOLVE_PIECE, mm = e % SOLVE_PIECE;
+        hrow[e] = (row0 + rr < bs && mm < len) ? Hinv[(int64_t)(row0 + rr) * BP + m0 + mm] : 0.0f;
+      }
+      __syncthreads();
+      const float* h = hrow + rl * SOLVE_PIECE;
+      const float* rp = Rc + (int64_t)m0 * t;
+      int mm = 0;
+      for (; mm + 3 < len; mm += 4) {
+        a0 = fmaf(h[mm], rp[(int64_t)mm * t], a0);
+        a1 = fmaf(h[mm + 1], rp[(int64_t)(mm + 1) * t], a1);
+        a2 = fmaf(h[mm + 2], rp[(int64_t)(mm + 2) * t], a2);
+        a3 = fmaf(h[mm + 3], rp[(int64_t)(mm + 3) * t], a3);
+      }
+      for (; mm < len; ++mm) a0 = fmaf(h[mm], rp[(int64_t)mm * t], a0);
+    }
+    if (cok && row0 + rl < bs) {
+      const float dv = frozen[c] ? 0.0f : (a0 + a1) + (a2 + a3);
+      D[(j0 + row0 + rl) * t + c] = dv;
+      atomicMax(&smax[c], __float_as_uint(fabsf(dv)));
+    }
+  }
+  __syncthreads();
+  for (int c = tid; c < t; c += 256)
+    if (smax[c]) atomicMax(&colmax[c], smax[c]);
+}
+
+// R -= H[:,I] d (the product's result, column-split partials summed here when JS > 1, plus sigma^2 d
+// on the block's own rows), V[I,:] += d, D[I,:] <- 0, squared residual norms per block slice.
+__global__ __launch_bounds__(256) void ap_update_kernel(float* __restrict__ R, float* __restrict__ V,
+                                                        float* __restrict__ D, const float* __restrict__ OUT,
+                                                        const float* __restrict__ part, int64_t stride, int JS,
+                                                        int64_t n, int t, int block, int64_t j0, int64_t j1,
+                                                        float sigma2, double* __restrict__ norms) {
+  __shared__ float red[256];
+  int64_t r0, r1;
+  slice_rows(n, block, &r0, &r1);
+  const ColMap m = col_map(t);
+  for (int cg = 0; cg < t; cg += m.tw) {
+    const int c = cg + m.cl;
+    const bool valid = c < t && m.rl < m.lanes;
+    float acc = 0.0f;
+    if (valid) {
+      for (int64_t i = r0 + m.rl; i < r1; i += m.lanes) {
+        const int64_t e = i * t + c;
+        float hx;
+        if (JS > 1) {
+          hx = 0.0f;
+          for (int q = 0; q < JS; ++q) hx += part[(int64_t)q * stride + e];
+        } else {
+          hx = OUT[e];
+        }
+        if (i >= j0 && i < j1) {
+          const float dl = D[e];
+          hx = fmaf(sigma2, dl, hx);
+          V[e] += dl;
+          D[e] = 0.0f;
+        }
+        const float r = R[e] - hx;
+        R[e] = r;
+        acc = fmaf(r, r, acc);
+      }
+    }
+    store_column_sums(m, valid, acc, cg, t, red, norms + (int64_t)blockIdx.x * t);
+  }
+}
+
+// Stopping test per column, choice of the next block, post to the host.  One workgroup of 1024.
+// The slice partials are first summed per (block, column) into bnorm, then per column over the blocks
+// (in 1024 / t segments, combined in a fixed order), so that no thread walks all the partials alone.
+__device__ void ap_column_totals(const double* __restrict__ src, double* bnorm, int nb, int t, double* spart,
+                                 double* scol) {
+  const int tid = threadIdx.x;
+  for (int idx = tid; idx < nb * t; idx += 1024) {
+    const int k = idx / t, c = idx - k * t;
+    double v = 0.0;
+    for (int q = 0; q < AP_SLICES; ++q) v += src[((int64_t)k * AP_SLICES + q) * t + c];
+    bnorm[idx] = v;
+  }
+  __threadfence();
+  __syncthreads();
+  const int nseg = 1024 / t;                 // t <= 1024
+  const int per = (nb + nseg - 1) / nseg;
+  const int seg = tid / t, c = tid - seg * t;
+  if (seg < nseg) {
+    double v = 0.0;
+    const int k1 = (seg + 1) * per < nb ? (seg + 1) * per : nb;
+    for (int k = seg * per; k < k1; ++k) v += bnorm[(int64_t)k * t + c];
+    spart[seg * t + c] = v;
+  }
+  __syncthreads();
+  if (tid < t) {
+    double v = 0.0;
+    for (int g = 0; g < nseg; ++g) v += spart[g * t + tid];
+    scol[tid] = v;
+  }
+  __syncthreads();
+}
+
+__global__ __launch_bounds__(1024) void ap_finalise_kernel(ApDev s, int nb, int t, int init,
+                                                           const int* __restrict__ fac_breakdown) {
+  __shared__ double sscore[1024];
+  __shared__ double scol[GP_MAX_T];
+  __shared__ int sidx[1024];
+  __shared__ int sfrozen[GP_MAX_T];
+  __shared__ int s_any, s_bad;
+  const int tid = threadIdx.x;
+  if (tid == 0) {
+    s_any = 0;
+    s_bad = *fac_breakdown ? 1 : 0;
+  }
+  if (init) {
+    ap_column_totals(s.normsB, s.bnorm, nb, t, sscore, scol);
+    if (tid < t) {
+      s.bn2[tid] = scol[tid];
+      s.zero_rhs[tid] = (scol[tid] == 0.0) ? 1 : 0;
+    }
+    __threadfence();
+    __syncthreads();
+  }
+  ap_column_totals(s.norms, s.bnorm, nb, t, sscore, scol);
+  if (tid < t) {
+    const int c = tid;
+    const double bn2 = s.bn2[c];
+    const int zero = s.zero_rhs[c];
+    int fr = init ? zero : s.frozen[c];
+    if (init && zero) s.relres[c] = 0.0f;
+    if (!fr) {
+      const double rel = sqrt(scol[c] / bn2);
+      if (!(rel == rel) || rel > 3.0e38) atomicOr(&s_bad, 1);
+      s.relres[c] = (float)rel;
+      if ((float)rel < s.tol[c]) fr = 1;
+    }
+    s.frozen[c] = fr;
+    sfrozen[c] = fr;
+    if (!fr) atomicOr(&s_any, 1);
+    s.colmax[c] = 0u;
+  }
+  __syncthreads();
+  // block with the largest residual over the live columns, lowest index on a tie
+  double best = -1.0;
+  int bi = 0x7fffffff;
+  for (int k = tid; k < nb; k += 1024) {
+    double sc = 0.0;
+    for (int c = 0; c < t; ++c)
+      if (!sfrozen[c]) sc += s.bnorm[(int64_t)k * t + c];
+    if (sc > best) {
+      best = sc;
+      bi = k;
+    }
+  }
+  sscore[tid] = best;
+  sidx[tid] = bi;
+  __syncthreads();
+  for (int off = 512; off > 0; off >>= 1) {
+    if (tid < off) {
+      const double o = sscore[tid + off];
+      const int oi = sidx[tid + off];
+      if (o > sscore[tid] || (o == sscore[tid] && oi < sidx[tid])) {
+        sscore[tid] = o;
+        sidx[tid] = oi;
+      }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    ApFlags f = *s.flags;
+    if (!init) f.iters += 1;
+    if (s_bad) f.breakdown = 1;
+    f.all_done = (!s_any || f.breakdown) ? 1 : 0;
+    f.sel = sidx[0] < nb ? sidx[0] : 0;
+    *s.flags = f;
+    s.post->all_done = f.all_done;
+    s.post->breakdown = f.breakdown;
+    s.post->iters = f.iters;
+    s.post->sel = f.sel;
+    __threadfence_system();
+    s.post->seq = f.iters + 1;
+    __threadfence_system();
+  }
+}
+
+__global__ __launch_bounds__(256) void ap_store_kernel(const float* __restrict__ V, int64_t n, int t,
+                                                       const int* __restrict__ zero_rhs, float* __restrict__ out,
+                                                       int64_t ldo) {
+  const int64_t total = n * t;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+    const int64_t i = e / t;
+    const int c = (int)(e - i * t);
+    out[i * ldo + c] = zero_rhs[c] ? 0.0f : V[e];
+  }
+}
+
+// ---- host ------------------------------------------------------------------------------------------
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct ApLayout {
+  int nb, BP, batch, win_chunks;
+  size_t off_hinv, off_A, off_W, off_DI, off_V, off_R, off_D, off_HP, off_norms, off_normsB, off_bnorm, off_state, off_kmv, total;
+  size_t kmv_bytes;
+};
+
+ApLayout ap_layout(const gp_ctx* ctx, int t, int block) {
+  ApLayout L;
+  L.nb = (int)((ctx->n + block - 1) / block);
+  L.BP = (block + TS - 1) / TS * TS;
+  L.batch = L.nb < AP_BATCH ? L.nb : AP_BATCH;
+  L.win_chunks = (block + 31) / 32 + 1;   // a block that starts inside a chunk touches one more
+  const int64_t all_chunks = (ctx->n + 31) / 32;
+  if (L.win_chunks > all_chunks) L.win_chunks = (int)all_chunks;
+  const size_t bp2 = (size_t)L.BP * L.BP;
+  const size_t arr = align_up((size_t)ctx->n * t * sizeof(float), 256);
+  const size_t nrm = align_up((size_t)L.nb * AP_SLICES * t * sizeof(double), 256);
+  size_t o = 0;
+  L.off_hinv = o; o += align_up((size_t)L.nb * bp2 * sizeof(float), 256);
+  L.off_A = o; o += align_up((size_t)L.batch * bp2 * sizeof(fac_t), 256);
+  L.off_W = o; o += align_up((size_t)L.batch * bp2 * sizeof(fac_t), 256);
+  L.off_DI = o; o += align_up((size_t)L.batch * L.BP * TS * sizeof(fac_t), 256);
+  L.off_V = o; o += arr;
+  L.off_R = o; o += arr;
+  L.off_D = o; o += arr;
+  L.off_HP = o; o += arr;
+  L.off_norms = o; o += nrm;
+  L.off_normsB = o; o += nrm;
+  L.off_bnorm = o; o += align_up((size_t)L.nb * t * sizeof(double), 256);
+  L.off_state = o; o += align_up(sizeof(ApFlags) + 64 + (size_t)t * (sizeof(double) + 2 * sizeof(float) + 3 * sizeof(int)) + 256, 256);
+  L.off_kmv = o;
+  size_t kb = gp_kmv_scratch_bytes(ctx, t);
+  const size_t wb = gp_kmv_window_scratch_bytes(ctx, t, L.win_chunks);
+  if (wb > kb) kb = wb;
+  L.kmv_bytes = align_up(kb, 256);
+  o += L.kmv_bytes;
+  L.total = o;
+  return L;
+}
+
+}  // namespace
+
+size_t gp_ap_workspace_bytes_impl(const gp_ctx* ctx, int t, int block) { return ap_layout(ctx, t, block).total; }
+
+int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv, int t,
+              const float* h_tol, int block, int max_iters, void* dWork, size_t work_bytes, int* h_iters,
+              int* h_kmv_count, float* h_relres, int* h_picks) {
+  const ApLayout L = ap_layout(ctx, t, block);
+  if (work_bytes < L.total) return gp_fail(ctx, GP_ERR_WORKSPACE, "gp_ap_solve: workspace %zu < %zu bytes", work_bytes, L.total);
+  if ((uintptr_t)dWork % 256) return gp_fail(ctx, GP_ERR_WORKSPACE, "gp_ap_solve: workspace not 256-byte aligned");
+  hipStream_t st = ctx->stream;
+  const int64_t n = ctx->n;
+  char* w = (char*)dWork;
+  float* Hinv = (float*)(w + L.off_hinv);
+  fac_t* A = (fac_t*)(w + L.off_A);
+  fac_t* W = (fac_t*)(w + L.off_W);
+  fac_t* DI = (fac_t*)(w + L.off_DI);
+  float* V = (float*)(w + L.off_V);
+  float* R = (float*)(w + L.off_R);
+  float* D = (float*)(w + L.off_D);
+  float* HP = (float*)(w + L.off_HP);
+  ApDev s;
+  int* fac_breakdown;
+  {
+    char* q = w + L.off_state;
+    s.flags = (ApFlags*)q; q += sizeof(ApFlags);
+    fac_breakdown = (int*)q; q += 64;
+    s.bn2 = (double*)q; q += sizeof(double) * t;
+    s.tol = (float*)q; q += sizeof(float) * t;
+    s.relres = (float*)q; q += sizeof(float) * t;
+    s.frozen = (int*)q; q += sizeof(int) * t;
+    s.zero_rhs = (int*)q; q += sizeof(int) * t;
+    s.colmax = (unsigned*)q; q += sizeof(unsigned) * t;
+  }
+  s.norms = (double*)(w + L.off_norms);
+  s.normsB = (double*)(w + L.off_normsB);
+  s.bnorm = (double*)(w + L.off_bnorm);
+  void* kmv_scratch = w + L.off_kmv;
+
+  const size_t need_pinned = sizeof(ApFlags) + sizeof(float) * t * 2;
+  if (ctx->pinned_bytes < 32768 + sizeof(ApFlags) || need_pinned > 32768)
+    return gp_fail(ctx, GP_ERR_ARG, "gp_ap_solve: t too large for the pinned staging block");
+  ApFlags* hflags = (ApFlags*)ctx->hPinned;
+  float* htol = (float*)((char*)ctx->hPinned + sizeof(ApFlags));
+  float* hrel = htol + t;
+  GP_HIP(ctx, hipStreamSynchronize(st));   // the pinned block may still be in use by an earlier call
+  for (int c = 0; c < t; ++c) htol[c] = h_tol[c];
+  GP_HIP(ctx, hipMemsetAsync(w + L.off_state, 0, L.off_kmv - L.off_state, st));
+  GP_HIP(ctx, hipMemcpyAsync(s.tol, htol, sizeof(float) * t, hipMemcpyHostToDevice, st));
+
+  ApFlags* hpost = (ApFlags*)((char*)ctx->hPinned + 32768);
+  s.post = (ApFlags*)((char*)ctx->dPinned + 32768);
+  hpost->seq = 0;
+  auto wait_seq = [&](int want) -> int {
+    volatile ApFlags* h = hpost;
+    for (unsigned spins = 1;; ++spins) {
+      if (h->seq >= want) break;
+      if ((spins & 4095u) == 0) {
+        const hipError_t q = hipStreamQuery(st);
+        if (q == hipSuccess) {          // nothing left to run: the post must be there by now
+          if (h->seq >= want) break;
+          return gp_fail(ctx, GP_ERR_HIP, "gp_ap_solve: the solver kernels did not report their state");
+        }
+        if (q != hipErrorNotReady) return gp_fail(ctx, GP_ERR_HIP, "gp_ap_solve: %s", hipGetErrorString(q));
+      }
+    }
+    __atomic_thread_fence(__ATOMIC_ACQUIRE);
+    return GP_OK;
+  };
+
+  // ---- set-up: the inverse of every diagonal block, AP_BATCH blocks per round of launches
+  const int BP = L.BP, nt = BP / TS;
+  for (int blk0 = 0; blk0 < L.nb; blk0 += L.batch) {
+    const int cnt = L.nb - blk0 < L.batch ? L.nb - blk0 : L.batch;
+    hipLaunchKernelGGL(ap_build_kernel, dim3(BP / 16, BP / 16, cnt), dim3(16, 16), 0, st, ctx->dX, ctx->d, n,
+                       (const double*)ctx->dTheta, ctx->kernel, block, BP, blk0, A);
+    for (int k = 0; k < nt; ++k) {
+      hipLaunchKernelGGL(ap_chol_diag_kernel, dim3(cnt), dim3(256), 0, st, A, BP, k, DI, fac_breakdown);
+      const int below = nt - k - 1;
+      if (below > 0) {
+        hipLaunchKernelGGL(ap_chol_panel_kernel, dim3(below, cnt), dim3(256), 0, st, A, BP, k, (const fac_t*)DI);
+        hipLaunchKernelGGL(ap_chol_update_kernel, dim3(below, below, cnt), dim3(256), 0, st, A, BP, k);
+      }
+    }
+    hipLaunchKernelGGL(ap_trtri_kernel, dim3(nt, cnt), dim3(256), 0, st, (const fac_t*)A, BP, (const fac_t*)DI, W);
+    hipLaunchKernelGGL(ap_lauum_kernel, dim3(nt, nt, cnt), dim3(256), 0, st, (const fac_t*)W, BP,
+                       Hinv + (size_t)blk0 * BP * BP);
+    GP_HIP(ctx, hipGetLastError());
+  }
+
+  // ---- initial residual
+  int kmv_count = 0;
+  if (dX0) {
+    const int rc = gp_kmv_launch(ctx, dX0, ldv, t, HP, t, 1, kmv_scratch, L.kmv_bytes, nullptr);
+    if (rc < 0) return rc;
+    ++kmv_count;
+  }
+  const dim3 sgrid(L.nb * AP_SLICES), sblock(256);
+  hipLaunchKernelGGL(ap_init_kernel, sgrid, sblock, 0, st, dB, ldb, dX0, ldv, (const float*)HP, n, t, block, V, R, D,
+                     s.norms, s.normsB);
+  hipLaunchKernelGGL(ap_finalise_kernel, dim3(1), dim3(1024), 0, st, s, L.nb, t, 1, (const int*)fac_breakdown);
+  GP_HIP(ctx, hipGetLastError());
+  {
+    const int rc = wait_seq(1);
+    if (rc < 0) return rc;
+  }
+
+  const float sigma2 = (float)(ctx->sigma * ctx->sigma);
+  int it = 0;
+  while (!hpost->all_done && it < max_iters) {
+    const int k = hpost->sel;
+    if (k < 0 || k >= L.nb) return gp_fail(ctx, GP_ERR_HIP, "gp_ap_solve: block choice %d out of range", k);
+    if (h_picks) h_picks[it] = k;
+    const int64_t j0 = (int64_t)k * block;
+    const int64_t j1 = j0 + block < n ? j0 + block : n;
+    const int bs = (int)(j1 - j0);
+    hipLaunchKernelGGL(ap_solve_kernel, dim3((bs + SOLVE_ROWS - 1) / SOLVE_ROWS), dim3(256), 0, st,
+                       (const float*)(Hinv + (size_t)k * BP * BP), BP, bs, (const float*)R, j0, t, (const int*)s.frozen, D,
+                       s.colmax);
+    GP_HIP(ctx, hipGetLastError());
+    KmvWindow win;
+    win.chunk0 = (int)(j0 / 32);
+    win.nchunks = (int)((j1 + 31) / 32) - win.chunk0;
+    KmvDeferred df = {nullptr, 0, 1};
+    const int rc = gp_kmv_launch(ctx, D, t, t, HP, t, 0, kmv_scratch, L.kmv_bytes, s.colmax, nullptr, &df, &win);
+    if (rc < 0) return rc;
+    hipLaunchKernelGGL(ap_update_kernel, sgrid, sblock, 0, st, R, V, D, (const float*)HP, df.part, df.stride, df.JS, n, t,
+                       block, j0, j1, sigma2, s.norms);
+    hipLaunchKernelGGL(ap_finalise_kernel, dim3(1), dim3(1024), 0, st, s, L.nb, t, 0, (const int*)fac_breakdown);
+    GP_HIP(ctx, hipGetLastError());
+    const int rc2 = wait_seq(it + 2);
+    if (rc2 < 0) return rc2;
+    ++it;
+  }
+
+  int sblocks = (int)((n * (int64_t)t + 255) / 256);
+  if (sblocks > 8 * ctx->num_cu) sblocks = 8 * ctx->num_cu;
+  hipLaunchKernelGGL(ap_store_kernel, dim3(sblocks), dim3(256), 0, st, (const float*)V, n, t, (const int*)s.zero_rhs, dV, ldv);
+  GP_HIP(ctx, hipGetLastError());
+  GP_HIP(ctx, hipMemcpyAsync(hrel, s.relres, sizeof(float) * t, hipMemcpyDeviceToHost, st));
+  GP_HIP(ctx, hipMemcpyAsync(hflags, s.flags, sizeof(ApFlags), hipMemcpyDeviceToHost, st));
+  GP_HIP(ctx, hipStreamSynchronize(st));
+  if (h_iters) *h_iters = hflags->iters;
+  if (h_kmv_count) *h_kmv_count = kmv_count;
+  if (h_relres)
+    for (int c = 0; c < t; ++c) h_relres[c] = hrel[c];
+  if (hflags->breakdown)
+    return gp_fail(ctx, GP_ERR_BREAKDOWN, "gp_ap_solve: a diagonal block is not positive definite in fp64, or a non-finite residual (step %d)", hflags->iters);
+  return hflags->all_done ? GP_OK : GP_NOT_CONVERGED;
+}

@@ -230,6 +230,34 @@ int gp_cg_solve(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, flo
                    h_relres);
 }
 
+size_t gp_ap_workspace_bytes(const gp_ctx* ctx, int t, int block) {
+  if (!ctx || t < 1 || t > GP_MAX_T || block < 1 || block > GP_AP_MAX_BLOCK) return 0;
+  return gp_ap_workspace_bytes_impl(ctx, t, block);
+}
+
+int gp_ap_solve(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv, int t,
+                const float* h_tol, int block, int max_iters, void* dWork, size_t work_bytes, int* h_iters,
+                int* h_kmv_count, float* h_relres, int* h_picks) {
+  if (!ctx) return GP_ERR_ARG;
+  if (!ctx->theta_set) return gp_fail(ctx, GP_ERR_ARG, "gp_ap_solve: gp_set_theta has not been called");
+  if (t < 1 || t > GP_MAX_T) return gp_fail(ctx, GP_ERR_ARG, "gp_ap_solve: t = %d outside [1, %d]", t, GP_MAX_T);
+  if (block < 1 || block > GP_AP_MAX_BLOCK)
+    return gp_fail(ctx, GP_ERR_ARG, "gp_ap_solve: block = %d outside [1, %d]", block, GP_AP_MAX_BLOCK);
+  if ((ctx->n + block - 1) / block > (1 << 20))
+    return gp_fail(ctx, GP_ERR_ARG, "gp_ap_solve: more than 2^20 blocks");
+  int rc;
+  if ((rc = check_block(ctx, "gp_ap_solve(dB)", dB, ldb, t)) < 0) return rc;
+  if ((rc = check_block(ctx, "gp_ap_solve(dV)", dV, ldv, t)) < 0) return rc;
+  if (!h_tol) return gp_fail(ctx, GP_ERR_ARG, "gp_ap_solve: NULL tolerances");
+  for (int c = 0; c < t; ++c)
+    if (!(h_tol[c] > 0.0f) || !std::isfinite(h_tol[c]))
+      return gp_fail(ctx, GP_ERR_ARG, "gp_ap_solve: tolerance %d = %g is not positive and finite", c, (double)h_tol[c]);
+  if (max_iters < 0) return gp_fail(ctx, GP_ERR_ARG, "gp_ap_solve: max_iters < 0");
+  if (!dWork) return gp_fail(ctx, GP_ERR_WORKSPACE, "gp_ap_solve: NULL workspace");
+  return gp_ap_run(ctx, dB, ldb, dX0, dV, ldv, t, h_tol, block, max_iters, dWork, work_bytes, h_iters, h_kmv_count,
+                   h_relres, h_picks);
+}
+
 int gp_mll_grad(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int64_t ldb, int t, double* h_grad) {
   if (!ctx) return GP_ERR_ARG;
   if (!ctx->theta_set) return gp_fail(ctx, GP_ERR_ARG, "gp_mll_grad: gp_set_theta has not been called");

@@ -100,6 +100,15 @@ struct KmvDeferred {
   int JS;
 };
 
+// Contraction restricted to the context's points 32 chunk0 .. min(n, 32 (chunk0 + nchunks)) - 1 (a
+// column block of K): OUT = K[:, window] V[window, :].  V is still the full-height n x t array; only
+// the window's rows are read.  Coincident pairs get no special treatment (as in a rectangular product)
+// and no noise term can be asked for.
+struct KmvWindow {
+  int chunk0;
+  int nchunks;
+};
+
 int gp_fail(gp_ctx* ctx, int code, const char* fmt, ...);
 #define GP_HIP(ctx, call)                                                              \
   do {                                                                                 \
@@ -128,29 +137,36 @@ struct KmvPlan {
   int row_blocks;
   int cps;       // chunks per split
 };
-KmvPlan gp_plan_kmv(const gp_ctx* ctx, int64_t rows);
+KmvPlan gp_plan_kmv(const gp_ctx* ctx, int64_t rows, int64_t col_chunks = 0);   // col_chunks = 0: all of the context's
 size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t);   // square product, worst case over the paths gp_set_theta may choose
 size_t gp_kmv_rect_scratch_bytes(const gp_ctx* ctx, int t, int64_t rows);
+size_t gp_kmv_window_scratch_bytes(const gp_ctx* ctx, int t, int col_chunks);   // product over a column window of that many chunks
 // OUT = K V (+ sigma^2 V).  colmax: optional device array of t bit patterns of max_i |V_ic| that the
 // caller already holds (the split-fp16 path then skips its own reduction over V); NULL otherwise.
 // rows: NULL, or the row side of a rectangular product (add_noise must then be 0).
 // defer: NULL, or where to report column-split partials instead of summing them into OUT.
 int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
                   int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax,
-                  const KmvRows* rows = nullptr, KmvDeferred* defer = nullptr);
+                  const KmvRows* rows = nullptr, KmvDeferred* defer = nullptr, const KmvWindow* win = nullptr);
 
 // ---- tile_pass_f16.hip
 int gp_kh_bucket(int d, int kernel);
-KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx, int64_t rows);
-size_t gp_kmv_f16_scratch_bytes(const gp_ctx* ctx, int t, int64_t rows);
+KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx, int64_t rows, int64_t col_chunks = 0);
+size_t gp_kmv_f16_scratch_bytes(const gp_ctx* ctx, int t, int64_t rows, int64_t col_chunks = 0);
 int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
                       int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax,
-                      const KmvRows* rows, KmvDeferred* defer);
+                      const KmvRows* rows, KmvDeferred* defer, const KmvWindow* win);
 
 // colmax[c] = bit pattern of max_i |V_ic| for c < t, stream-ordered; optionally the same for a second
 // n x t matrix in the same launch.  cleared = true: the caller has already zeroed the output words.
 int gp_launch_colmax(gp_ctx* ctx, const float* dV, int64_t ldv, int t, unsigned* colmax, const float* dV2 = nullptr,
                      int64_t ldv2 = 0, unsigned* colmax2 = nullptr, bool cleared = false);
+
+// ---- ap_kernels.hip
+size_t gp_ap_workspace_bytes_impl(const gp_ctx* ctx, int t, int block);
+int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv, int t,
+              const float* h_tol, int block, int max_iters, void* dWork, size_t work_bytes, int* h_iters,
+              int* h_kmv_count, float* h_relres, int* h_picks);
 
 // ---- cg_kernels.hip
 int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv,

@@ -287,9 +287,9 @@ int gp_ks_bucket(int d) {
   return -1;
 }
 
-KmvPlan gp_plan_kmv(const gp_ctx* ctx, int64_t rows) {
+KmvPlan gp_plan_kmv(const gp_ctx* ctx, int64_t rows, int64_t col_chunks) {
   KmvPlan pl;
-  const int64_t chunks = (ctx->n + 31) / 32;
+  const int64_t chunks = col_chunks > 0 ? col_chunks : (ctx->n + 31) / 32;
   // two sub-tiles per wave once there are enough rows to fill the chip that way
   pl.MI = (ctx->KS <= 24 && rows >= 8192) ? 2 : 1;
   const int rows_per_wg = 32 * GP_WAVES * pl.MI;
@@ -316,14 +316,24 @@ size_t gp_kmv_rect_scratch_bytes(const gp_ctx* ctx, int t, int64_t rows) {
 
 size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t) { return gp_kmv_rect_scratch_bytes(ctx, t, ctx->n); }
 
+size_t gp_kmv_window_scratch_bytes(const gp_ctx* ctx, int t, int col_chunks) {
+  KmvPlan pl = gp_plan_kmv(ctx, ctx->n, col_chunks);
+  const size_t fp32_bytes = pl.JS <= 1 ? 0 : (size_t)pl.JS * (size_t)ctx->n * (size_t)t * sizeof(float);
+  const size_t f16_bytes = gp_kmv_f16_scratch_bytes(ctx, t, ctx->n, col_chunks);
+  return fp32_bytes > f16_bytes ? fp32_bytes : f16_bytes;
+}
+
 int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,
                   int add_noise, void* scratch, size_t scratch_bytes, const unsigned* colmax, const KmvRows* rows,
-                  KmvDeferred* defer) {
+                  KmvDeferred* defer, const KmvWindow* win) {
   if (rows && add_noise) return gp_fail(ctx, GP_ERR_ARG, "rectangular product with a noise term");
+  const int64_t all_chunks = (ctx->n + 31) / 32;
+  if (win && (add_noise || rows || win->chunk0 < 0 || win->nchunks < 1 || (int64_t)win->chunk0 + win->nchunks > all_chunks))
+    return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: bad column window");
   if ((rows ? rows->path : ctx->path) != GP_PATH_FP32)
-    return gp_kmv_launch_f16(ctx, dV, ldv, t, dOut, ldo, add_noise, scratch, scratch_bytes, colmax, rows, defer);
+    return gp_kmv_launch_f16(ctx, dV, ldv, t, dOut, ldo, add_noise, scratch, scratch_bytes, colmax, rows, defer, win);
   const int64_t nrows = rows ? rows->m : ctx->n;
-  const KmvPlan pl = gp_plan_kmv(ctx, nrows);
+  const KmvPlan pl = gp_plan_kmv(ctx, nrows, win ? win->nchunks : 0);
   const bool split = pl.JS > 1;
   if (split && scratch_bytes < (size_t)pl.JS * (size_t)nrows * (size_t)t * sizeof(float))
     return gp_fail(ctx, GP_ERR_WORKSPACE, "gp_kmv: scratch too small for %d column splits", pl.JS);
@@ -339,7 +349,16 @@ int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut,
   a.n = ctx->n;
   a.nrows = nrows;
   a.diag = rows ? 0 : 1;
-  a.nchunks = (int)((ctx->n + 31) / 32);
+  a.nchunks = (int)all_chunks;
+  if (win) {   // the kernel sees the window as a point set of its own, starting at chunk 0
+    const int64_t first = (int64_t)win->chunk0 * 32;
+    const int64_t stop = first + (int64_t)win->nchunks * 32;
+    a.XA = ctx->dXA + (int64_t)win->chunk0 * ctx->KS * 64;
+    a.V = dV + first * ldv;
+    a.n = (stop < ctx->n ? stop : ctx->n) - first;
+    a.nchunks = win->nchunks;
+    a.diag = 0;
+  }
   a.JS = pl.JS;
   a.cps = pl.cps;
   a.a2 = (float)(ctx->a * ctx->a);

@@ -551,9 +551,9 @@ int gp_kh_bucket(int d, int kernel) {
   return -1;
 }
 
-KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx, int64_t rows) {
+KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx, int64_t rows, int64_t col_chunks) {
   KmvPlan pl;
-  const int64_t chunks = (ctx->n + 31) / 32;
+  const int64_t chunks = col_chunks > 0 ? col_chunks : (ctx->n + 31) / 32;
   // two sub-tiles per wave halve the LDS operand traffic; past one k-step of distance operands the
   // second sub-tile no longer fits the register file without spills
   pl.MI = (ctx->KH == 1 && rows >= 8192) ? 2 : 1;
@@ -591,16 +591,16 @@ int gp_launch_colmax(gp_ctx* ctx, const float* dV, int64_t ldv, int t, unsigned*
   return GP_OK;
 }
 
-size_t gp_kmv_f16_scratch_bytes(const gp_ctx* ctx, int t, int64_t rows) {
-  return scratch_layout(ctx, t, gp_plan_kmv_f16(ctx, rows).JS, rows).total;
+size_t gp_kmv_f16_scratch_bytes(const gp_ctx* ctx, int t, int64_t rows, int64_t col_chunks) {
+  return scratch_layout(ctx, t, gp_plan_kmv_f16(ctx, rows, col_chunks).JS, rows).total;
 }
 
 int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo, int add_noise,
                       void* scratch, size_t scratch_bytes, const unsigned* colmax_ready, const KmvRows* rows,
-                      KmvDeferred* defer) {
+                      KmvDeferred* defer, const KmvWindow* win) {
   const int64_t nrows = rows ? rows->m : ctx->n;
   const int XP = rows ? (rows->path == GP_PATH_F16X3 ? 3 : 2) : ctx->XP;
-  const KmvPlan pl = gp_plan_kmv_f16(ctx, nrows);
+  const KmvPlan pl = gp_plan_kmv_f16(ctx, nrows, win ? win->nchunks : 0);
   const ScratchH L = scratch_layout(ctx, t, pl.JS, nrows);
   if (scratch_bytes < L.total || !scratch)
     return gp_fail(ctx, GP_ERR_WORKSPACE, "gp_kmv: scratch %zu < %zu bytes", scratch_bytes, L.total);
@@ -611,7 +611,12 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
   u32x4* VP = (u32x4*)(w + L.off_vp);
   float* part = (float*)(w + L.off_part);
   const bool split = pl.JS > 1;
-  const int nchunks = (int)((ctx->n + 31) / 32);
+  // a column window is handed to the kernels as a point set of its own that starts at chunk 0
+  const int nchunks = win ? win->nchunks : (int)((ctx->n + 31) / 32);
+  const int64_t first = win ? (int64_t)win->chunk0 * 32 : 0;
+  const int64_t ncontr = win ? ((first + (int64_t)nchunks * 32 < ctx->n ? first + (int64_t)nchunks * 32 : ctx->n) - first) : ctx->n;
+  if (win && !colmax_ready) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: a column window needs the column maxima");
+  const float* dVw = dV + first * ldv;
 
   if (!colmax_ready) {
     const int rc = gp_launch_colmax(ctx, dV, ldv, t, (unsigned*)(w + L.off_colmax));
@@ -620,7 +625,7 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
 
   TileArgsH a;
   for (int pc = 0; pc < 3; ++pc) {
-    a.XA[pc] = (const u32x4*)ctx->dXAh[pc];
+    a.XA[pc] = (const u32x4*)ctx->dXAh[pc] + (win ? (int64_t)win->chunk0 * ctx->KH * 64 : 0);
     a.XB[pc] = (const u32x4*)(rows ? rows->XBh[pc] : ctx->dXBh[pc]);
   }
   a.VP = VP;
@@ -632,7 +637,7 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
   a.ldo = split ? t : ldo;
   a.split_stride = split ? nrows * (int64_t)t : 0;
   a.n = nrows;
-  a.diag = rows ? 0 : 1;
+  a.diag = (rows || win) ? 0 : 1;
   a.nchunks = nchunks;
   a.JS = pl.JS;
   a.cps = pl.cps;
@@ -652,7 +657,7 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
     {
       const int64_t threads = (int64_t)nchunks * 2 * NT * 64;
       const int64_t need = threads > (int64_t)nchunks * 32 ? threads : (int64_t)nchunks * 32;
-      hipLaunchKernelGGL(pack_v_kernel, dim3((unsigned)((need + 255) / 256)), dim3(256), 0, st, dV, ldv, ctx->n, nchunks, NT,
+      hipLaunchKernelGGL(pack_v_kernel, dim3((unsigned)((need + 255) / 256)), dim3(256), 0, st, dVw, ldv, ncontr, nchunks, NT,
                          a.col0, a.ncols, vcol, (const unsigned*)colmax, VP, VY);
       GP_HIP(ctx, hipGetLastError());
     }

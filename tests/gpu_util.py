@@ -17,6 +17,7 @@ class Dev:
         self.ctx = gp.gp_create(KIND_CODE[kind], self.n, self.d, self.X, torch.cuda.current_stream().cuda_stream)
         self.set_theta(ell, a, sigma)
         self._work = None
+        self._apwork = None
 
     def set_theta(self, ell, a, sigma):
         self.gp.gp_set_theta(self.ctx, ell, a, sigma)
@@ -66,6 +67,21 @@ class Dev:
         w = self.work(t)
         rc, iters, kmv, relres = self.gp.gp_cg_solve(self.ctx, Bd, t, X0, Vd, t, t, tol, max_iters, w, w.numel())
         return rc, iters, kmv, relres, Vd
+
+    def ap_solve(self, B, tol, block, max_iters=100000, X0=None, Vd=None, picks=False):
+        """Returns (rc, iters, kmv_count, relres, picks, V device tensor)."""
+        n, t = B.shape
+        Bd = B if isinstance(B, torch.Tensor) else self.to(B)
+        if Vd is None:
+            Vd = torch.zeros((n, t), device=self.dev)
+        need = self.gp.gp_ap_workspace_bytes(self.ctx, t, block)
+        if self._apwork is None or self._apwork.numel() < need:
+            self._apwork = None
+            self._apwork = torch.empty(need, dtype=torch.uint8, device=self.dev)
+        w = self._apwork
+        rc, iters, kmv, relres, pk = self.gp.gp_ap_solve(self.ctx, Bd, t, X0, Vd, t, t, tol, block, max_iters, w,
+                                                         w.numel(), want_picks=picks)
+        return rc, iters, kmv, relres, pk, Vd
 
     def grad(self, Vd, Bd):
         t = Bd.shape[1]
