@@ -92,6 +92,10 @@ def main():
     ap.add_argument("--probe-tol", type=float, default=None,
                     help="tolerance of the probe systems when it differs from the workload's (Appendix B of the "
                          "paper solves y to 0.01 and the probes to 0.1); default: the workload's tolerance for all")
+    ap.add_argument("--solver", default="cg", choices=["cg", "ap"],
+                    help="linear system solver of the MLL steps: conjugate gradients (the headline path) or "
+                         "alternating projections (then iterations are block updates and a product is H[:, I] d)")
+    ap.add_argument("--block", type=int, default=2000, help="block size of --solver ap (the paper's is 2000)")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
                     help="also run three plain device copies of MIB MiB (reads MIB, writes MIB): the known-size "
                          "kernel that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -111,6 +115,8 @@ def main():
     steps = args.steps if args.steps is not None else (2 if big else 20)
     warmup = args.warmup if args.warmup is not None else (1 if big else 5)
     max_iters = args.max_iters if args.max_iters is not None else (6 if args.workload == "config5" else (30 if big else 1000))
+    if args.solver == "ap" and args.max_iters is None:
+        max_iters = 100000
 
     kw = {"n": args.n} if args.n else {}
     t_gen = time.perf_counter()
@@ -126,7 +132,22 @@ def main():
         tol = np.full(t, args.probe_tol, dtype=np.float32)
         tol[0] = w.tol
         desc += f", probe systems to {args.probe_tol:g}"
-    opt = MllOptimizer(w.X, w.y, w.Z, w.kind, w.ell, w.a, w.sigma, tol, warm=True, max_iters=max_iters)
+    if args.solver == "ap":
+        desc = desc.replace("CG rel tol", f"alternating projections (block {args.block}) rel tol")
+    opt = MllOptimizer(w.X, w.y, w.Z, w.kind, w.ell, w.a, w.sigma, tol, warm=True, max_iters=max_iters,
+                       solver=args.solver, block=args.block)
+
+    def solve(B, x0, V):
+        if args.solver == "cg":
+            return gp.gp_cg_solve(opt.ctx, B, t, x0, V, t, t, tol, max_iters, opt.work, opt.work.numel())
+        return gp.gp_ap_solve(opt.ctx, B, t, x0, V, t, t, tol, args.block, max_iters, opt.work, opt.work.numel())[:4]
+
+    # algorithmic flops of the products of one solve: full products, plus (alternating projections) one
+    # product over a block's columns per step
+    window_frac = min(args.block, n) / n if args.solver == "ap" else 1.0
+
+    def products(rec_kmv, rec_iters):
+        return rec_kmv + (rec_iters * window_frac if args.solver == "ap" else 0.0)
     result = {}
     try:
         if args.calib_copy:
@@ -191,7 +212,7 @@ def main():
             launches, kern_ms = gp.gp_profile_read(opt.ctx)
             gp.gp_profile(opt.ctx, 0)
             timed = opt.history[warmup:]
-            n_kmv = sum(r.kmv_count for r in timed)
+            n_kmv = sum(products(r.kmv_count, r.iters) for r in timed)
             warm_stats = {"cg_ms_per_step": float(np.mean([r.solve_ms for r in timed])),
                           "grad_ms_per_step": float(np.mean([r.grad_ms for r in timed])),
                           "iters_per_step": float(np.mean([r.iters for r in timed])),
@@ -199,6 +220,10 @@ def main():
                           "max_relres": [round(r.max_relres, 6) for r in opt.history],
                           "not_converged_steps": int(sum(r.rc != 0 for r in timed))}
             extra = {"warm": warm_stats}
+            if args.solver == "ap":
+                extra["solver"] = {"name": "alternating projections", "block": args.block,
+                                   "note": "iters = block updates; cg_ms_per_step = solver time per step, which "
+                                           "includes rebuilding the inverse of every diagonal block for the new theta"}
             if not args.no_cold:
                 # cold arm on the same theta sequence: zero initialisation and freshly drawn probes
                 gen = torch.Generator(device=opt.dev)
@@ -214,8 +239,7 @@ def main():
                     Bc[:, 1:] = Zc
                     torch.cuda.synchronize()
                     c0 = time.perf_counter()
-                    rc, it, _, rel = gp.gp_cg_solve(opt.ctx, Bc, t, None, Vc, t, t, tol, max_iters, opt.work,
-                                                    opt.work.numel())
+                    rc, it, _, rel = solve(Bc, None, Vc)
                     cold_ms.append((time.perf_counter() - c0) * 1e3)
                     cold_it.append(it)
                     cold_rel.append(round(float(rel.max()), 6))
@@ -250,7 +274,7 @@ def main():
                            "products (relative error 2^-22), kernel function in fp32"),
             "data": "synthetic",
             "config": {"workload": desc, "n": n, "d": d, "t": t, "kernel": w.kind, "max_iters": max_iters,
-                       "kmv_products_timed": int(n_kmv), "input_generation_s": round(t_gen, 1)},
+                       "kmv_products_timed": float(n_kmv), "input_generation_s": round(t_gen, 1)},
             "pct_fp32_peak": 100.0 * value / FP32_PEAK_TFLOPS,
             "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                          "frac": achieved / peak, "traffic": TRAFFIC.get((args.workload, n)),

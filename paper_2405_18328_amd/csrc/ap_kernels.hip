@@ -24,10 +24,8 @@
 namespace {
 
 constexpr int TS = 64;              // tile edge of the factorisation kernels
-constexpr int AP_SLICES = 8;        // row slices per block in the residual-norm partials
-constexpr int AP_BATCH = 32;        // blocks factorised side by side
-constexpr int SOLVE_ROWS = 8;       // rows of the inverse one workgroup of the block solve handles
-constexpr int SOLVE_PIECE = 512;    // columns of the inverse staged in LDS at a time
+constexpr int AP_BATCH = 16;        // blocks factorised side by side
+constexpr int SOLVE_KSPLIT = 16;    // ranges of the contraction index in the block solve
 
 typedef double fac_t;
 
@@ -49,16 +47,24 @@ struct ApDev {
   int* frozen;      // [t]
   int* zero_rhs;    // [t]
   unsigned* colmax; // [t] bit patterns of max |d| per column for the split-fp16 product
-  double* norms;    // [nb][AP_SLICES][t] squared residual norms per block slice
-  double* normsB;   // [nb][AP_SLICES][t] the same for B (init only)
+  double* norms;    // [nb][S][t] squared residual norms per block slice
+  double* normsB;   // [nb][S][t] the same for B (init only)
   double* bnorm;    // [nb][t] squared residual norms per block (finalise kernel's scratch)
 };
 
-// ---- 64 x 64 tile products in LDS -----------------------------------------------------------------
-// Operands are held contraction-index-major: out[r][c] += sum_m TA[m][r] * TB[m][c]; thread
-// (tx, ty) = (tid % 16, tid / 16) owns rows 4 ty .. 4 ty + 3 and columns 4 tx .. 4 tx + 3.
+// ---- 64 x 64 tile products on the fp64 matrix cores ---------------------------------------------
+// Operands sit in LDS contraction-index-major: out[r][c] += sum_m TA[m][r] * TB[m][c].  A workgroup is
+// 4 waves; wave w owns rows 16 w .. 16 w + 15 of the output tile and all 64 columns, as four
+// 16 x 16 blocks of v_mfma_f64_16x16x4_f64 (A operand: lane l holds A[l % 16][l / 16]; B operand:
+// B[l / 16][l % 16]; result register v of lane l: D[4 v + l / 16][l % 16]).
+typedef double d4 __attribute__((ext_vector_type(4)));
+
 struct Tile {
   fac_t v[TS][TS + 1];
+};
+
+struct Acc {
+  d4 b[4];   // column block cb: rows 16 w + 4 v + l / 16, column 16 cb + l % 16
 };
 
 // source element (row, col) = src[row * ld + col].  by_col = false: the source row is the contraction
@@ -72,29 +78,26 @@ __device__ __forceinline__ void load_tile(Tile& T, const fac_t* __restrict__ src
   }
 }
 
-__device__ __forceinline__ void mac_tile(const Tile& TA, const Tile& TB, fac_t acc[4][4]) {
-  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+__device__ __forceinline__ void clear_acc(Acc& acc) {
+#pragma unroll
+  for (int cb = 0; cb < 4; ++cb) acc.b[cb] = d4{0.0, 0.0, 0.0, 0.0};
+}
+
+__device__ __forceinline__ void mac_tile(const Tile& TA, const Tile& TB, Acc& acc) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int lo = lane & 15, hi = lane >> 4;
 #pragma unroll 4
-  for (int m = 0; m < TS; ++m) {
-    fac_t a[4], b[4];
+  for (int m0 = 0; m0 < TS; m0 += 4) {
+    const fac_t a = TA.v[m0 + hi][16 * w + lo];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      a[q] = TA.v[m][4 * ty + q];
-      b[q] = TB.v[m][4 * tx + q];
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) acc[i][j] = fma(a[i], b[j], acc[i][j]);
+    for (int cb = 0; cb < 4; ++cb)
+      acc.b[cb] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, TB.v[m0 + hi][16 * cb + lo], acc.b[cb], 0, 0, 0);
   }
 }
 
-__device__ __forceinline__ void clear_acc(fac_t acc[4][4]) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
-}
+// row and column (inside the 64 x 64 tile) of element v of column block cb held by this thread
+__device__ __forceinline__ int acc_row(int v) { return 16 * (threadIdx.x >> 6) + 4 * v + ((threadIdx.x & 63) >> 4); }
+__device__ __forceinline__ int acc_col(int cb) { return 16 * cb + (threadIdx.x & 15); }
 
 // ---- set-up: H[I,I], Cholesky, inverse ------------------------------------------------------------
 // A[z] (BP x BP, row-major, fp64) = H[I,I] for block blk0 + z, identity on the padding rows/columns
@@ -129,11 +132,15 @@ __global__ __launch_bounds__(256) void ap_build_kernel(const float* __restrict__
   A[(int64_t)blockIdx.z * BP * BP + (int64_t)i * BP + j] = v;
 }
 
-// diagonal tile k of every block in the batch: L_kk in place (upper part zeroed), its inverse to DI
+// diagonal tile k of every block in the batch: L_kk in place (upper part zeroed); its inverse goes to
+// DI and to the diagonal tile of X (the matrix that becomes L^-1)
 __global__ __launch_bounds__(256) void ap_chol_diag_kernel(fac_t* __restrict__ A, int BP, int k,
-                                                           fac_t* __restrict__ DI, int* __restrict__ breakdown) {
+                                                           fac_t* __restrict__ DI, fac_t* __restrict__ X,
+                                                           int* __restrict__ breakdown) {
   __shared__ Tile T, Li;
-  fac_t* Ab = A + (int64_t)blockIdx.x * BP * BP + (int64_t)k * TS * BP + k * TS;
+  const int64_t tile_off = (int64_t)blockIdx.x * BP * BP + (int64_t)k * TS * BP + k * TS;
+  fac_t* Ab = A + tile_off;
+  fac_t* Xb = X + tile_off;
   fac_t* DIb = DI + (int64_t)blockIdx.x * BP * TS + (int64_t)k * TS * TS;
   const int tid = threadIdx.x;
   load_tile(T, Ab, BP, false);
@@ -162,9 +169,16 @@ __global__ __launch_bounds__(256) void ap_chol_diag_kernel(fac_t* __restrict__ A
       if (i < j) {
         Li.v[i][j] = 0.0;
       } else {
-        fac_t s = (i == j) ? 1.0 : 0.0;
-        for (int m = j; m < i; ++m) s -= T.v[i][m] * Li.v[m][j];
-        Li.v[i][j] = s / T.v[i][i];
+        fac_t s0 = (i == j) ? 1.0 : 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;   // four chains: the loads overlap
+        int m = j;
+        for (; m + 3 < i; m += 4) {
+          s0 -= T.v[i][m] * Li.v[m][j];
+          s1 -= T.v[i][m + 1] * Li.v[m + 1][j];
+          s2 -= T.v[i][m + 2] * Li.v[m + 2][j];
+          s3 -= T.v[i][m + 3] * Li.v[m + 3][j];
+        }
+        for (; m < i; ++m) s0 -= T.v[i][m] * Li.v[m][j];
+        Li.v[i][j] = ((s0 + s1) + (s2 + s3)) / T.v[i][i];
       }
     }
   }
@@ -173,6 +187,7 @@ __global__ __launch_bounds__(256) void ap_chol_diag_kernel(fac_t* __restrict__ A
     const int i = e / TS, j = e % TS;
     Ab[(int64_t)i * BP + j] = (j <= i) ? T.v[i][j] : 0.0;
     DIb[i * TS + j] = Li.v[i][j];
+    Xb[(int64_t)i * BP + j] = Li.v[i][j];
   }
 }
 
@@ -186,14 +201,13 @@ __global__ __launch_bounds__(256) void ap_chol_panel_kernel(fac_t* __restrict__ 
   load_tile(TA, Aik, BP, true);     // A_ik(r, m)
   load_tile(TB, DIb, TS, true);     // L_kk^-1(c, m)
   __syncthreads();
-  fac_t acc[4][4];
+  Acc acc;
   clear_acc(acc);
   mac_tile(TA, TB, acc);
-  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) Aik[(int64_t)(4 * ty + i) * BP + 4 * tx + j] = acc[i][j];
+    for (int v = 0; v < 4; ++v) Aik[(int64_t)acc_row(v) * BP + acc_col(cb)] = acc.b[cb][v];
 }
 
 // trailing update A_IJ -= L_Ik L_Jk^T for the tiles I >= J > k (I = k + 1 + blockIdx.y, J = k + 1 + blockIdx.x)
@@ -205,59 +219,63 @@ __global__ __launch_bounds__(256) void ap_chol_update_kernel(fac_t* __restrict__
   load_tile(TA, Ab + (int64_t)I * TS * BP + k * TS, BP, true);   // L_Ik(r, m)
   load_tile(TB, Ab + (int64_t)J * TS * BP + k * TS, BP, true);   // L_Jk(c, m)
   __syncthreads();
-  fac_t acc[4][4];
+  Acc acc;
   clear_acc(acc);
   mac_tile(TA, TB, acc);
   fac_t* Aij = Ab + (int64_t)I * TS * BP + J * TS;
-  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) Aij[(int64_t)(4 * ty + i) * BP + 4 * tx + j] -= acc[i][j];
+    for (int v = 0; v < 4; ++v) Aij[(int64_t)acc_row(v) * BP + acc_col(cb)] -= acc.b[cb][v];
 }
 
-// column panel k of X = L^-1: X_kk = L_kk^-1, X_ik = -L_ii^-1 sum_{k <= j < i} L_ij X_jk.  One workgroup
-// walks down its panel; the tiles it reads back are the ones it wrote itself.
-__global__ __launch_bounds__(256) void ap_trtri_kernel(const fac_t* __restrict__ A, int BP,
-                                                       const fac_t* __restrict__ DI, fac_t* W) {
+// X = L^-1 by merging diagonal blocks pairwise, level by level (s = 1, 2, 4, .. tiles): for the pair
+// [[L11, 0], [L21, L22]] whose halves X11 = L11^-1 and X22 = L22^-1 are complete,
+//   X21 = -X22 (L21 X11).
+// Every level is two launches, each a set of independent tile products whose chains are at most s
+// tiles long.  Pair p of a level covers tiles [2 s p, 2 s p + s) and [2 s p + s, min(2 s p + 2 s, nt)).
+// step 0: T = L21 X11, tile (ti, tj) = sum_{m = tj}^{s - 1} L21(ti, m) X11(m, tj)   (X11 is lower triangular)
+// step 1: X21 = -X22 T, tile (ti, tj) = -sum_{m = 0}^{ti} X22(ti, m) T(m, tj)       (X22 is lower triangular)
+// Grid (s, s, pairs * batch).
+__global__ __launch_bounds__(256) void ap_trinv_merge_kernel(const fac_t* __restrict__ A, fac_t* X, fac_t* T, int BP,
+                                                             int s, int pairs, int step) {
   __shared__ Tile TA, TB;
-  const int k = blockIdx.x, nt = BP / TS;
-  const fac_t* Ab = A + (int64_t)blockIdx.y * BP * BP;
-  const fac_t* DIb = DI + (int64_t)blockIdx.y * BP * TS;
-  fac_t* Wb = W + (int64_t)blockIdx.y * BP * BP;
-  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-  for (int e = threadIdx.x; e < TS * TS; e += 256) {
-    const int i = e / TS, j = e % TS;
-    Wb[(int64_t)(k * TS + i) * BP + k * TS + j] = DIb[(int64_t)k * TS * TS + i * TS + j];
+  const int nt = BP / TS;
+  const int pr = blockIdx.z % pairs, z = blockIdx.z / pairs;
+  const int o1 = 2 * s * pr, o2 = o1 + s;
+  const int s2 = nt - o2 < s ? nt - o2 : s;         // tiles in the second half (may be short or empty)
+  const int ti = blockIdx.y, tj = blockIdx.x;
+  if (ti >= s2) return;
+  const int64_t zo = (int64_t)z * BP * BP;
+  const fac_t* P;      // left factor, tile (ti, m) at P + (ti * TS * BP + m * TS)
+  const fac_t* Q;      // right factor, tile (m, tj)
+  int mlo, mhi;
+  if (step == 0) {
+    P = A + zo + (int64_t)o2 * TS * BP + o1 * TS;
+    Q = X + zo + (int64_t)o1 * TS * BP + o1 * TS;
+    mlo = tj;
+    mhi = s - 1;
+  } else {
+    P = X + zo + (int64_t)o2 * TS * BP + o2 * TS;
+    Q = T + zo + (int64_t)o2 * TS * BP + o1 * TS;
+    mlo = 0;
+    mhi = ti;
   }
-  __threadfence();
-  __syncthreads();
-  for (int i = k + 1; i < nt; ++i) {
-    fac_t acc[4][4];
-    clear_acc(acc);
-    for (int j = k; j < i; ++j) {
-      load_tile(TA, Ab + (int64_t)i * TS * BP + j * TS, BP, true);    // L_ij(r, m)
-      load_tile(TB, Wb + (int64_t)j * TS * BP + k * TS, BP, false);   // X_jk(m, c)
-      __syncthreads();
-      mac_tile(TA, TB, acc);
-      __syncthreads();
-    }
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-      for (int b = 0; b < 4; ++b) TB.v[4 * ty + a][4 * tx + b] = acc[a][b];   // S(m, c)
-    load_tile(TA, DIb + (int64_t)i * TS * TS, TS, true);                      // L_ii^-1(r, m)
+  Acc acc;
+  clear_acc(acc);
+  for (int m = mlo; m <= mhi; ++m) {
+    load_tile(TA, P + (int64_t)ti * TS * BP + m * TS, BP, true);    // P(r, q): the source column is the contraction index
+    load_tile(TB, Q + (int64_t)m * TS * BP + tj * TS, BP, false);   // Q(q, c)
     __syncthreads();
-    fac_t out[4][4];
-    clear_acc(out);
-    mac_tile(TA, TB, out);
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-      for (int b = 0; b < 4; ++b) Wb[(int64_t)(i * TS + 4 * ty + a) * BP + k * TS + 4 * tx + b] = -out[a][b];
-    __threadfence();
+    mac_tile(TA, TB, acc);
     __syncthreads();
   }
+  fac_t* out = (step == 0 ? T : X) + zo + (int64_t)(o2 + ti) * TS * BP + (o1 + tj) * TS;
+  const fac_t sign = step == 0 ? 1.0 : -1.0;
+#pragma unroll
+  for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) out[(int64_t)acc_row(v) * BP + acc_col(cb)] = sign * acc.b[cb][v];
 }
 
 // H[I,I]^-1 = X^T X, tiles (ti >= tj) and their mirror images, rounded to fp32
@@ -266,7 +284,7 @@ __global__ __launch_bounds__(256) void ap_lauum_kernel(const fac_t* __restrict__
   if (blockIdx.x > blockIdx.y) return;
   const int ti = blockIdx.y, tj = blockIdx.x, nt = BP / TS;
   const fac_t* Wb = W + (int64_t)blockIdx.z * BP * BP;
-  fac_t acc[4][4];
+  Acc acc;
   clear_acc(acc);
   for (int m = ti; m < nt; ++m) {
     load_tile(TA, Wb + (int64_t)m * TS * BP + ti * TS, BP, false);   // X_m,ti(q, r)
@@ -276,15 +294,14 @@ __global__ __launch_bounds__(256) void ap_lauum_kernel(const fac_t* __restrict__
     __syncthreads();
   }
   float* Hb = Hinv + (int64_t)blockIdx.z * BP * BP;
-  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int r = ti * TS + 4 * ty + i, c = tj * TS + 4 * tx + j;
-      const float v = (float)acc[i][j];
-      Hb[(int64_t)r * BP + c] = v;
-      Hb[(int64_t)c * BP + r] = v;
+    for (int v = 0; v < 4; ++v) {
+      const int r = ti * TS + acc_row(v), c = tj * TS + acc_col(cb);
+      const float val = (float)acc.b[cb][v];
+      Hb[(int64_t)r * BP + c] = val;
+      Hb[(int64_t)c * BP + r] = val;
     }
 }
 
@@ -315,28 +332,29 @@ __device__ __forceinline__ void store_column_sums(const ColMap& m, bool valid, f
   __syncthreads();
 }
 
-__device__ __forceinline__ void slice_rows(int64_t n, int block, int64_t* r0, int64_t* r1) {
-  const int64_t k = blockIdx.x / AP_SLICES;
-  const int s = blockIdx.x % AP_SLICES;
+// workgroup blockIdx.x = k S + s owns slice s (of S) of block k
+__device__ __forceinline__ void slice_rows(int64_t n, int block, int S, int64_t* r0, int64_t* r1) {
+  const int64_t k = blockIdx.x / S;
+  const int s = blockIdx.x % S;
   const int64_t b0 = k * block;
   const int64_t b1 = b0 + block < n ? b0 + block : n;
-  const int64_t per = (b1 - b0 + AP_SLICES - 1) / AP_SLICES;
+  const int64_t per = (b1 - b0 + S - 1) / S;
   *r0 = b0 + s * per;
   const int64_t e = *r0 + per;
   *r1 = e < b1 ? e : b1;
 }
 
 // V <- X0 (or 0), R <- B - HX0 (HX0 given when X0 is), D <- 0, squared norms of B and R per block slice.
-// Grid: nb * AP_SLICES workgroups, workgroup (k, s) owns slice s of block k.
+// Grid: nb * S workgroups, workgroup (k, s) owns slice s of block k.
 __global__ __launch_bounds__(256) void ap_init_kernel(const float* __restrict__ B, int64_t ldb,
                                                       const float* __restrict__ X0, int64_t ldx,
-                                                      const float* __restrict__ HX0, int64_t n, int t, int block,
+                                                      const float* __restrict__ HX0, int64_t n, int t, int block, int S,
                                                       float* __restrict__ V, float* __restrict__ R,
                                                       float* __restrict__ D, double* __restrict__ norms,
                                                       double* __restrict__ normsB) {
   __shared__ float red[256];
   int64_t r0, r1;
-  slice_rows(n, block, &r0, &r1);
+  slice_rows(n, block, S, &r0, &r1);
   const ColMap m = col_map(t);
   for (int cg = 0; cg < t; cg += m.tw) {
     const int c = cg + m.cl;
@@ -360,52 +378,76 @@ __global__ __launch_bounds__(256) void ap_init_kernel(const float* __restrict__ 
   }
 }
 
-// d = H[I,I]^-1 R[I,:] for the columns still being updated (0 for the others), written to rows
-// j0 .. j0 + bs - 1 of D; the columns' largest |d| go to colmax (zero on entry).
-__global__ __launch_bounds__(256) void ap_solve_kernel(const float* __restrict__ Hinv, int BP, int bs,
-                                                       const float* __restrict__ R, int64_t j0, int t,
-                                                       const int* __restrict__ frozen, float* __restrict__ D,
-                                                       unsigned* __restrict__ colmax) {
-  __shared__ float hrow[SOLVE_ROWS * SOLVE_PIECE];
-  __shared__ unsigned smax[GP_MAX_T];
-  const int tid = threadIdx.x;
-  const int row0 = blockIdx.x * SOLVE_ROWS;
-  const int cl = tid & 31, rl = tid >> 5;
-  const int npass = (t + 31) / 32;
-  for (int c = tid; c < t; c += 256) smax[c] = 0u;
-  // every pass over 32 columns re-reads the staged rows; passes are few (t <= 64 in the paper's use)
-  for (int pass = 0; pass < npass; ++pass) {
-    const int c = pass * 32 + cl;
-    const bool cok = c < t;
-    const float* Rc = R + j0 * t + (cok ? c : 0);
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-    for (int m0 = 0; m0 < bs; m0 += SOLVE_PIECE) {
-      const int len = bs - m0 < SOLVE_PIECE ? bs - m0 : SOLVE_PIECE;
-      __syncthreads();
-      for (int e = tid; e < SOLVE_ROWS * SOLVE_PIECE; e += 256) {
-        const int rr = e / SOLVE_PIECE, mm = e % SOLVE_PIECE;
-        hrow[e] = (row0 + rr < bs && mm < len) ? Hinv[(int64_t)(row0 + rr) * BP + m0 + mm] : 0.0f;
-      }
-      __syncthreads();
-      const float* h = hrow + rl * SOLVE_PIECE;
-      const float* rp = Rc + (int64_t)m0 * t;
-      int mm = 0;
-      for (; mm + 3 < len; mm += 4) {
-        a0 = fmaf(h[mm], rp[(int64_t)mm * t], a0);
-        a1 = fmaf(h[mm + 1], rp[(int64_t)(mm + 1) * t], a1);
-        a2 = fmaf(h[mm + 2], rp[(int64_t)(mm + 2) * t], a2);
-        a3 = fmaf(h[mm + 3], rp[(int64_t)(mm + 3) * t], a3);
-      }
-      for (; mm < len; ++mm) a0 = fmaf(h[mm], rp[(int64_t)mm * t], a0);
+// d = H[I,I]^-1 R[I,:] in two launches.  First, partial products over SOLVE_KSPLIT ranges of the
+// contraction index m: the inverse is symmetric, so row i of it is read as column i, lane = row, one
+// coalesced load per m, while the R values of a wave's 16 columns are the same for all its lanes
+// (scalar loads).  Grid (BP / 64 row tiles, SOLVE_KSPLIT, ceil(t / 256)); a workgroup has one wave per
+// 16 columns, up to 16 waves.  A wave whose 16 columns would run past t moves its window left (the
+// overlap is computed twice and stored once); t < 16 takes the guarded loop.
+__global__ __launch_bounds__(1024) void ap_solve_partial_kernel(const float* __restrict__ Hinv, int BP, int bs,
+                                                                const float* __restrict__ R, int64_t j0, int t,
+                                                                int kper, float* __restrict__ part) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int i = blockIdx.x * 64 + lane;
+  const int c_first = blockIdx.z * 256 + wave * 16;      // first column this wave has to deliver
+  if (c_first >= t) return;
+  const int c0 = (t >= 16 && c_first + 16 > t) ? t - 16 : c_first;   // first column it computes
+  const int skip = c_first - c0;
+  const int ncol = t - c0 < 16 ? t - c0 : 16;
+  const int m0 = blockIdx.y * kper;
+  const int m1 = m0 + kper < bs ? m0 + kper : bs;
+  float acc[16];
+#pragma unroll
+  for (int q = 0; q < 16; ++q) acc[q] = 0.0f;
+  const float* hp = Hinv + (int64_t)m0 * BP + i;
+  const float* rp = R + (j0 + m0) * t + c0;
+  if (ncol == 16) {
+#pragma unroll 4
+    for (int m = m0; m < m1; ++m) {
+      const float h = *hp;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[q] = fmaf(h, rp[q], acc[q]);
+      hp += BP;
+      rp += t;
     }
-    if (cok && row0 + rl < bs) {
-      const float dv = frozen[c] ? 0.0f : (a0 + a1) + (a2 + a3);
-      D[(j0 + row0 + rl) * t + c] = dv;
-      atomicMax(&smax[c], __float_as_uint(fabsf(dv)));
+  } else {
+    for (int m = m0; m < m1; ++m) {
+      const float h = *hp;
+#pragma unroll
+      for (int q = 0; q < 16; ++q)
+        if (q < ncol) acc[q] = fmaf(h, rp[q], acc[q]);
+      hp += BP;
+      rp += t;
     }
   }
+  if (i < bs) {
+    float* out = part + ((int64_t)blockIdx.y * bs + i) * t + c0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q)
+      if (q >= skip && q < ncol) out[q] = acc[q];
+  }
+}
+
+// Second, the partials summed in a fixed order, columns no longer updated set to 0, the result written
+// to rows j0 .. j0 + bs - 1 of D, and the columns' largest |d| to colmax (zero on entry).
+__global__ __launch_bounds__(256) void ap_solve_reduce_kernel(const float* __restrict__ part, int ksplit, int bs, int t,
+                                                              const int* __restrict__ frozen, int64_t j0,
+                                                              float* __restrict__ D, unsigned* __restrict__ colmax) {
+  __shared__ unsigned smax[GP_MAX_T];
+  for (int c = threadIdx.x; c < t; c += 256) smax[c] = 0u;
   __syncthreads();
-  for (int c = tid; c < t; c += 256)
+  const int64_t total = (int64_t)bs * t;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+    const int c = (int)(e % t);
+    float v = 0.0f;
+    for (int k = 0; k < ksplit; ++k) v += part[(int64_t)k * total + e];
+    if (frozen[c]) v = 0.0f;
+    D[j0 * t + e] = v;
+    atomicMax(&smax[c], __float_as_uint(fabsf(v)));
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < t; c += 256)
     if (smax[c]) atomicMax(&colmax[c], smax[c]);
 }
 
@@ -414,11 +456,11 @@ __global__ __launch_bounds__(256) void ap_solve_kernel(const float* __restrict__
 __global__ __launch_bounds__(256) void ap_update_kernel(float* __restrict__ R, float* __restrict__ V,
                                                         float* __restrict__ D, const float* __restrict__ OUT,
                                                         const float* __restrict__ part, int64_t stride, int JS,
-                                                        int64_t n, int t, int block, int64_t j0, int64_t j1,
+                                                        int64_t n, int t, int block, int S, int64_t j0, int64_t j1,
                                                         float sigma2, double* __restrict__ norms) {
   __shared__ float red[256];
   int64_t r0, r1;
-  slice_rows(n, block, &r0, &r1);
+  slice_rows(n, block, S, &r0, &r1);
   const ColMap m = col_map(t);
   for (int cg = 0; cg < t; cg += m.tw) {
     const int c = cg + m.cl;
@@ -452,13 +494,13 @@ __global__ __launch_bounds__(256) void ap_update_kernel(float* __restrict__ R, f
 // Stopping test per column, choice of the next block, post to the host.  One workgroup of 1024.
 // The slice partials are first summed per (block, column) into bnorm, then per column over the blocks
 // (in 1024 / t segments, combined in a fixed order), so that no thread walks all the partials alone.
-__device__ void ap_column_totals(const double* __restrict__ src, double* bnorm, int nb, int t, double* spart,
+__device__ void ap_column_totals(const double* __restrict__ src, double* bnorm, int nb, int S, int t, double* spart,
                                  double* scol) {
   const int tid = threadIdx.x;
   for (int idx = tid; idx < nb * t; idx += 1024) {
     const int k = idx / t, c = idx - k * t;
     double v = 0.0;
-    for (int q = 0; q < AP_SLICES; ++q) v += src[((int64_t)k * AP_SLICES + q) * t + c];
+    for (int q = 0; q < S; ++q) v += src[((int64_t)k * S + q) * t + c];
     bnorm[idx] = v;
   }
   __threadfence();
@@ -481,7 +523,7 @@ __device__ void ap_column_totals(const double* __restrict__ src, double* bnorm, 
   __syncthreads();
 }
 
-__global__ __launch_bounds__(1024) void ap_finalise_kernel(ApDev s, int nb, int t, int init,
+__global__ __launch_bounds__(1024) void ap_finalise_kernel(ApDev s, int nb, int S, int t, int init,
                                                            const int* __restrict__ fac_breakdown) {
   __shared__ double sscore[1024];
   __shared__ double scol[GP_MAX_T];
@@ -494,7 +536,7 @@ __global__ __launch_bounds__(1024) void ap_finalise_kernel(ApDev s, int nb, int 
     s_bad = *fac_breakdown ? 1 : 0;
   }
   if (init) {
-    ap_column_totals(s.normsB, s.bnorm, nb, t, sscore, scol);
+    ap_column_totals(s.normsB, s.bnorm, nb, S, t, sscore, scol);
     if (tid < t) {
       s.bn2[tid] = scol[tid];
       s.zero_rhs[tid] = (scol[tid] == 0.0) ? 1 : 0;
@@ -502,7 +544,7 @@ __global__ __launch_bounds__(1024) void ap_finalise_kernel(ApDev s, int nb, int 
     __threadfence();
     __syncthreads();
   }
-  ap_column_totals(s.norms, s.bnorm, nb, t, sscore, scol);
+  ap_column_totals(s.norms, s.bnorm, nb, S, t, sscore, scol);
   if (tid < t) {
     const int c = tid;
     const double bn2 = s.bn2[c];
@@ -579,8 +621,8 @@ __global__ __launch_bounds__(256) void ap_store_kernel(const float* __restrict__
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct ApLayout {
-  int nb, BP, batch, win_chunks;
-  size_t off_hinv, off_A, off_W, off_DI, off_V, off_R, off_D, off_HP, off_norms, off_normsB, off_bnorm, off_state, off_kmv, total;
+  int nb, BP, batch, win_chunks, S;
+  size_t off_hinv, off_A, off_W, off_T, off_DI, off_V, off_R, off_D, off_HP, off_SP, off_norms, off_normsB, off_bnorm, off_state, off_kmv, total;
   size_t kmv_bytes;
 };
 
@@ -594,16 +636,22 @@ ApLayout ap_layout(const gp_ctx* ctx, int t, int block) {
   if (L.win_chunks > all_chunks) L.win_chunks = (int)all_chunks;
   const size_t bp2 = (size_t)L.BP * L.BP;
   const size_t arr = align_up((size_t)ctx->n * t * sizeof(float), 256);
-  const size_t nrm = align_up((size_t)L.nb * AP_SLICES * t * sizeof(double), 256);
+  // row slices per block in the streaming kernels: enough workgroups to fill the chip when blocks are few
+  L.S = (4 * ctx->num_cu + L.nb - 1) / L.nb;
+  if (L.S > 256) L.S = 256;
+  if (L.S < 1) L.S = 1;
+  const size_t nrm = align_up((size_t)L.nb * L.S * t * sizeof(double), 256);
   size_t o = 0;
   L.off_hinv = o; o += align_up((size_t)L.nb * bp2 * sizeof(float), 256);
   L.off_A = o; o += align_up((size_t)L.batch * bp2 * sizeof(fac_t), 256);
   L.off_W = o; o += align_up((size_t)L.batch * bp2 * sizeof(fac_t), 256);
+  L.off_T = o; o += align_up((size_t)L.batch * bp2 * sizeof(fac_t), 256);
   L.off_DI = o; o += align_up((size_t)L.batch * L.BP * TS * sizeof(fac_t), 256);
   L.off_V = o; o += arr;
   L.off_R = o; o += arr;
   L.off_D = o; o += arr;
   L.off_HP = o; o += arr;
+  L.off_SP = o; o += align_up((size_t)SOLVE_KSPLIT * L.BP * t * sizeof(float), 256);
   L.off_norms = o; o += nrm;
   L.off_normsB = o; o += nrm;
   L.off_bnorm = o; o += align_up((size_t)L.nb * t * sizeof(double), 256);
@@ -634,11 +682,13 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
   float* Hinv = (float*)(w + L.off_hinv);
   fac_t* A = (fac_t*)(w + L.off_A);
   fac_t* W = (fac_t*)(w + L.off_W);
+  fac_t* TT = (fac_t*)(w + L.off_T);
   fac_t* DI = (fac_t*)(w + L.off_DI);
   float* V = (float*)(w + L.off_V);
   float* R = (float*)(w + L.off_R);
   float* D = (float*)(w + L.off_D);
   float* HP = (float*)(w + L.off_HP);
+  float* SP = (float*)(w + L.off_SP);
   ApDev s;
   int* fac_breakdown;
   {
@@ -695,14 +745,19 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     hipLaunchKernelGGL(ap_build_kernel, dim3(BP / 16, BP / 16, cnt), dim3(16, 16), 0, st, ctx->dX, ctx->d, n,
                        (const double*)ctx->dTheta, ctx->kernel, block, BP, blk0, A);
     for (int k = 0; k < nt; ++k) {
-      hipLaunchKernelGGL(ap_chol_diag_kernel, dim3(cnt), dim3(256), 0, st, A, BP, k, DI, fac_breakdown);
+      hipLaunchKernelGGL(ap_chol_diag_kernel, dim3(cnt), dim3(256), 0, st, A, BP, k, DI, W, fac_breakdown);
       const int below = nt - k - 1;
       if (below > 0) {
         hipLaunchKernelGGL(ap_chol_panel_kernel, dim3(below, cnt), dim3(256), 0, st, A, BP, k, (const fac_t*)DI);
         hipLaunchKernelGGL(ap_chol_update_kernel, dim3(below, below, cnt), dim3(256), 0, st, A, BP, k);
       }
     }
-    hipLaunchKernelGGL(ap_trtri_kernel, dim3(nt, cnt), dim3(256), 0, st, (const fac_t*)A, BP, (const fac_t*)DI, W);
+    for (int sz = 1; sz < nt; sz *= 2) {
+      const int pairs = (nt + 2 * sz - 1) / (2 * sz);
+      for (int step = 0; step < 2; ++step)
+        hipLaunchKernelGGL(ap_trinv_merge_kernel, dim3(sz, sz, pairs * cnt), dim3(256), 0, st, (const fac_t*)A, W, TT, BP, sz,
+                           pairs, step);
+    }
     hipLaunchKernelGGL(ap_lauum_kernel, dim3(nt, nt, cnt), dim3(256), 0, st, (const fac_t*)W, BP,
                        Hinv + (size_t)blk0 * BP * BP);
     GP_HIP(ctx, hipGetLastError());
@@ -715,10 +770,10 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     if (rc < 0) return rc;
     ++kmv_count;
   }
-  const dim3 sgrid(L.nb * AP_SLICES), sblock(256);
-  hipLaunchKernelGGL(ap_init_kernel, sgrid, sblock, 0, st, dB, ldb, dX0, ldv, (const float*)HP, n, t, block, V, R, D,
+  const dim3 sgrid(L.nb * L.S), sblock(256);
+  hipLaunchKernelGGL(ap_init_kernel, sgrid, sblock, 0, st, dB, ldb, dX0, ldv, (const float*)HP, n, t, block, L.S, V, R, D,
                      s.norms, s.normsB);
-  hipLaunchKernelGGL(ap_finalise_kernel, dim3(1), dim3(1024), 0, st, s, L.nb, t, 1, (const int*)fac_breakdown);
+  hipLaunchKernelGGL(ap_finalise_kernel, dim3(1), dim3(1024), 0, st, s, L.nb, L.S, t, 1, (const int*)fac_breakdown);
   GP_HIP(ctx, hipGetLastError());
   {
     const int rc = wait_seq(1);
@@ -734,10 +789,17 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     const int64_t j0 = (int64_t)k * block;
     const int64_t j1 = j0 + block < n ? j0 + block : n;
     const int bs = (int)(j1 - j0);
-    hipLaunchKernelGGL(ap_solve_kernel, dim3((bs + SOLVE_ROWS - 1) / SOLVE_ROWS), dim3(256), 0, st,
-                       (const float*)(Hinv + (size_t)k * BP * BP), BP, bs, (const float*)R, j0, t, (const int*)s.frozen, D,
-                       s.colmax);
-    GP_HIP(ctx, hipGetLastError());
+    {
+      const int kper = (bs + SOLVE_KSPLIT - 1) / SOLVE_KSPLIT;
+      hipLaunchKernelGGL(ap_solve_partial_kernel, dim3((bs + 63) / 64, SOLVE_KSPLIT, (t + 255) / 256),
+                         dim3(64 * (((t < 256 ? t : 256) + 15) / 16)), 0, st,
+                         (const float*)(Hinv + (size_t)k * BP * BP), BP, bs, (const float*)R, j0, t, kper, SP);
+      int rblocks = (int)(((int64_t)bs * t + 255) / 256);
+      if (rblocks > 2 * ctx->num_cu) rblocks = 2 * ctx->num_cu;
+      hipLaunchKernelGGL(ap_solve_reduce_kernel, dim3(rblocks), dim3(256), 0, st, (const float*)SP, SOLVE_KSPLIT, bs, t,
+                         (const int*)s.frozen, j0, D, s.colmax);
+      GP_HIP(ctx, hipGetLastError());
+    }
     KmvWindow win;
     win.chunk0 = (int)(j0 / 32);
     win.nchunks = (int)((j1 + 31) / 32) - win.chunk0;
@@ -745,8 +807,8 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     const int rc = gp_kmv_launch(ctx, D, t, t, HP, t, 0, kmv_scratch, L.kmv_bytes, s.colmax, nullptr, &df, &win);
     if (rc < 0) return rc;
     hipLaunchKernelGGL(ap_update_kernel, sgrid, sblock, 0, st, R, V, D, (const float*)HP, df.part, df.stride, df.JS, n, t,
-                       block, j0, j1, sigma2, s.norms);
-    hipLaunchKernelGGL(ap_finalise_kernel, dim3(1), dim3(1024), 0, st, s, L.nb, t, 0, (const int*)fac_breakdown);
+                       block, L.S, j0, j1, sigma2, s.norms);
+    hipLaunchKernelGGL(ap_finalise_kernel, dim3(1), dim3(1024), 0, st, s, L.nb, L.S, t, 0, (const int*)fac_breakdown);
     GP_HIP(ctx, hipGetLastError());
     const int rc2 = wait_seq(it + 2);
     if (rc2 < 0) return rc2;

@@ -1,6 +1,7 @@
 """Outer loop of marginal-likelihood optimisation (paper Section 2.1 hierarchy, Section 4 and
 Appendix B settings): Adam on softplus-constrained hyperparameters, each step one batched
-CG solve (warm-started or cold) followed by the stochastic gradient.
+linear solve (conjugate gradients or alternating projections, warm-started or cold) followed by
+the stochastic gradient.
 
 Host-side glue only: theta lives in a handful of fp64 scalars, every n-sized array stays on the
 device and every n-sized operation is a libgpws call.
@@ -68,7 +69,8 @@ class StepRecord:
 
 
 class MllOptimizer:
-    """Adam ascent on L(theta) with the linear solves done by gp_cg_solve.
+    """Adam ascent on L(theta) with the linear solves done by gp_cg_solve (solver="cg") or
+    gp_ap_solve (solver="ap", blocks of `block` indices; iters then counts block updates).
 
     warm=True keeps the probes Z fixed and passes the previous step's V as x0 (Section 3);
     warm=False starts every solve from zero and, if resample is given, redraws the probes
@@ -76,7 +78,7 @@ class MllOptimizer:
     """
 
     def __init__(self, X, y, Z, kind, ell0, a0, sigma0, tol, warm=True, lr=0.1, max_iters=1000,
-                 resample=None, device="cuda:0"):
+                 resample=None, device="cuda:0", solver="cg", block=2000):
         self.dev = torch.device(device)
         self.X = torch.as_tensor(np.ascontiguousarray(X, dtype=np.float32)).to(self.dev)
         self.n, self.d = self.X.shape
@@ -92,7 +94,15 @@ class MllOptimizer:
         self.have_solution = False
         self.stream = torch.cuda.current_stream(self.dev)
         self.ctx = gp.gp_create(KIND_CODE[kind], self.n, self.d, self.X, self.stream.cuda_stream)
-        self.work = torch.empty(gp.gp_workspace_bytes(self.ctx, self.t), dtype=torch.uint8, device=self.dev)
+        if solver not in ("cg", "ap"):
+            raise ValueError(f"unknown solver {solver!r}")
+        self.solver = solver
+        self.block = int(block)
+        need = (gp.gp_workspace_bytes(self.ctx, self.t) if solver == "cg"
+                else gp.gp_ap_workspace_bytes(self.ctx, self.t, self.block))
+        if need == 0:
+            raise ValueError("workspace size query failed (t or block out of range)")
+        self.work = torch.empty(need, dtype=torch.uint8, device=self.dev)
         self.history = []
 
     @property
@@ -117,8 +127,12 @@ class MllOptimizer:
             self.B[:, 1:] = self.resample(self.k)
         x0 = self.V if (self.warm and self.have_solution) else None
         t1 = time.perf_counter()
-        rc, iters, kmv, relres = gp.gp_cg_solve(self.ctx, self.B, self.t, x0, self.V, self.t, self.t, self.tol,
-                                                self.max_iters, self.work, self.work.numel())
+        if self.solver == "cg":
+            rc, iters, kmv, relres = gp.gp_cg_solve(self.ctx, self.B, self.t, x0, self.V, self.t, self.t, self.tol,
+                                                    self.max_iters, self.work, self.work.numel())
+        else:
+            rc, iters, kmv, relres, _ = gp.gp_ap_solve(self.ctx, self.B, self.t, x0, self.V, self.t, self.t, self.tol,
+                                                       self.block, self.max_iters, self.work, self.work.numel())
         t2 = time.perf_counter()
         g = gp.gp_mll_grad(self.ctx, self.V, self.t, self.B, self.t, self.t, self.d)
         t3 = time.perf_counter()

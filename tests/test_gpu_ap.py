@@ -6,8 +6,9 @@ fixed number of steps, the stopping decision.  Tolerances:
   iterate after k steps   normwise relative error <= 2e-4 per column: the block solve multiplies the
                           residual by an fp32 copy of H[I,I]^-1, error ~ eps32 * kappa(H[I,I]) per step
                           (kappa <= 1 + block * a^2 / sigma^2, a few thousand in these cases);
-  converged solve         recursive residual < tol (reported), true residual recomputed in fp64
-                          <= tol * (1 + 1e-3) + 2e-5 (fp32 drift of the tracked residual);
+  converged solve         tracked residual < tol (reported); the true residual recomputed in fp64 may exceed
+                          it by the fp32 drift of the tracked residual, one rounding of size
+                          ~eps32 |H[:,I] d| per step: <= tol * (1 + 1e-3) + 5e-7 * max(steps, 40);
   step counts             within 10% (or 2 steps) of the oracle's: after a near-tie flips a block choice
                           the two runs follow different but equally valid greedy paths.
 """
@@ -27,6 +28,10 @@ STEP_TOL = 2e-4
 def _announce(request):
     print(f"\n[gpu-case] {request.node.nodeid}", flush=True)
     yield
+
+
+def _drift(steps):
+    return 5e-7 * max(steps, 40)
 
 
 def _colrel(got, ref):
@@ -106,7 +111,7 @@ def test_ap_converged_solve_two_tolerances(name, kw, block):
         assert rc == 0 and kmv == 0 and len(pk) == it
         assert (rr[:-1] < tol[:-1]).all() and rr[-1] == 0.0 and (got[:, -1] == 0.0).all()
         true_rel = np.linalg.norm(H @ got[:, :-1] - B[:, :-1], axis=0) / np.linalg.norm(B[:, :-1], axis=0)
-        assert (true_rel <= tol[:-1] * 1.001 + 2e-5).all(), true_rel
+        assert (true_rel <= tol[:-1] * 1.001 + _drift(it)).all(), (true_rel, it)
         assert abs(it - ito) <= max(2, 0.1 * ito), (it, ito)
         assert list(pk[:3]) == pko[:3]
         # every step picked a different block from the one before (its residual was just zeroed)
@@ -132,7 +137,7 @@ def test_ap_paper_block_size_and_warm_start():
         got = Vd.cpu().numpy().astype(np.float64)
         assert rc == 0 and (rr < tol).all()
         true_rel = np.linalg.norm(H @ got - B, axis=0) / np.linalg.norm(B, axis=0)
-        assert (true_rel <= tol * 1.001 + 2e-5).all(), true_rel
+        assert (true_rel <= tol * 1.001 + _drift(it)).all(), true_rel
         assert abs(it - ito) <= max(2, 0.1 * ito), (it, ito)
         assert list(pk[:2]) == pko[:2]
         # one step from a random start against the oracle: the 2000 x 2000 inverse at work
@@ -155,7 +160,7 @@ def test_ap_paper_block_size_and_warm_start():
         assert abs(it_warm - ito_warm) <= max(2, 0.1 * ito_warm) and abs(it_cold - ito_cold) <= max(2, 0.1 * ito_cold)
         gw = Vw.cpu().numpy().astype(np.float64)
         true_rel = np.linalg.norm(H2 @ gw - B, axis=0) / np.linalg.norm(B, axis=0)
-        assert (true_rel <= tol * 1.001 + 2e-5).all()
+        assert (true_rel <= tol * 1.001 + _drift(it_warm)).all()
         # x0 = the solution itself (in place): nothing to do
         Vs = dv.to(np.linalg.solve(H2, B))
         keep = Vs.clone()
@@ -182,7 +187,7 @@ def test_ap_every_product_path(monkeypatch, path):
         rc, it, _, rr, _, Vd = dv.ap_solve(w.B, 0.01, 150)
         got = Vd.cpu().numpy().astype(np.float64)
         true_rel = np.linalg.norm(H @ got - B, axis=0) / np.linalg.norm(B, axis=0)
-        assert rc == 0 and (true_rel <= 0.01 * 1.001 + 2e-5).all()
+        assert rc == 0 and (true_rel <= 0.01 * 1.001 + _drift(it)).all(), (true_rel, it)
     finally:
         dv.close()
 
