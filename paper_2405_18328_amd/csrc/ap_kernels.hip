@@ -24,7 +24,7 @@
 namespace {
 
 constexpr int TS = 64;              // tile edge of the factorisation kernels
-constexpr int AP_BATCH = 16;        // blocks factorised side by side
+constexpr int AP_BATCH = 64;        // blocks factorised side by side (3 x 32 MiB of fp64 scratch each at block 2000)
 constexpr int SOLVE_KSPLIT = 16;    // ranges of the contraction index in the block solve
 
 typedef double fac_t;
@@ -133,61 +133,71 @@ __global__ __launch_bounds__(256) void ap_build_kernel(const float* __restrict__
 }
 
 // diagonal tile k of every block in the batch: L_kk in place (upper part zeroed); its inverse goes to
-// DI and to the diagonal tile of X (the matrix that becomes L^-1)
-__global__ __launch_bounds__(256) void ap_chol_diag_kernel(fac_t* __restrict__ A, int BP, int k,
-                                                           fac_t* __restrict__ DI, fac_t* __restrict__ X,
-                                                           int* __restrict__ breakdown) {
-  __shared__ Tile T, Li;
+// DI and to the diagonal tile of X (the matrix that becomes L^-1).  One wave per tile, so that no
+// barrier is needed between the 64 column steps: lane i owns row i of the tile in LDS, the rank-1
+// update of the right-looking factorisation reads the other rows' column entries at wave-uniform
+// addresses, and LDS operations of one wave complete in order.  The inverse is then formed column by
+// column (lane j owns column j) by forward substitution.
+__global__ __launch_bounds__(64) void ap_chol_diag_kernel(fac_t* __restrict__ A, int BP, int k,
+                                                          fac_t* __restrict__ DI, fac_t* __restrict__ X,
+                                                          int* __restrict__ breakdown) {
+  __shared__ fac_t T[TS][TS + 1];
+  __shared__ fac_t Xi[TS][TS + 1];
   const int64_t tile_off = (int64_t)blockIdx.x * BP * BP + (int64_t)k * TS * BP + k * TS;
   fac_t* Ab = A + tile_off;
   fac_t* Xb = X + tile_off;
   fac_t* DIb = DI + (int64_t)blockIdx.x * BP * TS + (int64_t)k * TS * TS;
-  const int tid = threadIdx.x;
-  load_tile(T, Ab, BP, false);
+  const int lane = threadIdx.x;
+  for (int i = 0; i < TS; ++i) T[i][lane] = Ab[(int64_t)i * BP + lane];
   __syncthreads();
+  bool any_bad = false;
   for (int c = 0; c < TS; ++c) {
-    const fac_t piv = T.v[c][c];
+    const fac_t piv = T[c][c];
     const bool bad = !(piv > 0.0);          // also catches NaN
+    any_bad = any_bad || bad;
     const fac_t dg = bad ? 1.0 : sqrt(piv);
-    __syncthreads();                        // everyone holds the pivot before it is overwritten
-    if (tid == 0) {
-      T.v[c][c] = dg;
-      if (bad) *breakdown = 1;
-    }
-    if (tid > c && tid < TS) T.v[tid][c] /= dg;
-    __syncthreads();
-    for (int e = tid; e < TS * TS; e += 256) {
-      const int i = e / TS, j = e % TS;
-      if (j > c && i >= j) T.v[i][j] -= T.v[i][c] * T.v[j][c];
-    }
-    __syncthreads();
-  }
-  // column j of L_kk^-1 by forward substitution, one thread per column
-  if (tid < TS) {
-    const int j = tid;
-    for (int i = 0; i < TS; ++i) {
-      if (i < j) {
-        Li.v[i][j] = 0.0;
-      } else {
-        fac_t s0 = (i == j) ? 1.0 : 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;   // four chains: the loads overlap
-        int m = j;
-        for (; m + 3 < i; m += 4) {
-          s0 -= T.v[i][m] * Li.v[m][j];
-          s1 -= T.v[i][m + 1] * Li.v[m + 1][j];
-          s2 -= T.v[i][m + 2] * Li.v[m + 2][j];
-          s3 -= T.v[i][m + 3] * Li.v[m + 3][j];
-        }
-        for (; m < i; ++m) s0 -= T.v[i][m] * Li.v[m][j];
-        Li.v[i][j] = ((s0 + s1) + (s2 + s3)) / T.v[i][i];
+    const fac_t lc = lane > c ? T[lane][c] / dg : (lane == c ? dg : 0.0);   // column c of L, this lane's row
+    T[lane][c] = lc;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // eight columns at a time, all reads before the writes: the column-c entries are not written in
+    // this loop and a lane writes only its own row, so the loads of a group can be in flight together
+    for (int j0 = c + 1; j0 < TS; j0 += 8) {
+      fac_t col[8], row[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int jj = j0 + q < TS ? j0 + q : TS - 1;
+        col[q] = T[jj][c];
+        row[q] = T[lane][jj];
       }
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        if (j0 + q < TS) T[lane][j0 + q] = fma(-lc, col[q], row[q]);   // meaningful for rows >= j0 + q
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+  if (any_bad && lane == 0) *breakdown = 1;
+  // column `lane` of L^-1: x_i = (delta_i,lane - sum_{m < i} L[i][m] x_m) / L[i][i]; x_m = 0 for m < lane
+  for (int i = 0; i < TS; ++i) {
+    fac_t s0 = lane == i ? 1.0 : 0.0, s1 = 0.0;
+    int m = 0;
+#pragma unroll 4
+    for (; m + 1 < i; m += 2) {
+      s0 = fma(-T[i][m], Xi[m][lane], s0);
+      s1 = fma(-T[i][m + 1], Xi[m + 1][lane], s1);
+    }
+    if (m < i) s0 = fma(-T[i][m], Xi[m][lane], s0);
+    Xi[i][lane] = (s0 + s1) / T[i][i];
   }
   __syncthreads();
-  for (int e = tid; e < TS * TS; e += 256) {
-    const int i = e / TS, j = e % TS;
-    Ab[(int64_t)i * BP + j] = (j <= i) ? T.v[i][j] : 0.0;
-    DIb[i * TS + j] = Li.v[i][j];
-    Xb[(int64_t)i * BP + j] = Li.v[i][j];
+  for (int i = 0; i < TS; ++i) {
+    Ab[(int64_t)i * BP + lane] = lane <= i ? T[i][lane] : 0.0;
+    const fac_t v = Xi[i][lane];
+    DIb[i * TS + lane] = v;
+    Xb[(int64_t)i * BP + lane] = v;
   }
 }
 
@@ -499,9 +509,17 @@ __device__ void ap_column_totals(const double* __restrict__ src, double* bnorm, 
   const int tid = threadIdx.x;
   for (int idx = tid; idx < nb * t; idx += 1024) {
     const int k = idx / t, c = idx - k * t;
-    double v = 0.0;
-    for (int q = 0; q < S; ++q) v += src[((int64_t)k * S + q) * t + c];
-    bnorm[idx] = v;
+    const double* sp = src + (int64_t)k * S * t + c;
+    double v0 = 0.0, v1 = 0.0, v2 = 0.0, v3 = 0.0;      // four chains so that the loads overlap
+    int q = 0;
+    for (; q + 3 < S; q += 4) {
+      v0 += sp[(int64_t)q * t];
+      v1 += sp[(int64_t)(q + 1) * t];
+      v2 += sp[(int64_t)(q + 2) * t];
+      v3 += sp[(int64_t)(q + 3) * t];
+    }
+    for (; q < S; ++q) v0 += sp[(int64_t)q * t];
+    bnorm[idx] = (v0 + v1) + (v2 + v3);
   }
   __threadfence();
   __syncthreads();
@@ -637,7 +655,7 @@ ApLayout ap_layout(const gp_ctx* ctx, int t, int block) {
   const size_t bp2 = (size_t)L.BP * L.BP;
   const size_t arr = align_up((size_t)ctx->n * t * sizeof(float), 256);
   // row slices per block in the streaming kernels: enough workgroups to fill the chip when blocks are few
-  L.S = (4 * ctx->num_cu + L.nb - 1) / L.nb;
+  L.S = (2 * ctx->num_cu + L.nb - 1) / L.nb;
   if (L.S > 256) L.S = 256;
   if (L.S < 1) L.S = 1;
   const size_t nrm = align_up((size_t)L.nb * L.S * t * sizeof(double), 256);
@@ -745,7 +763,7 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     hipLaunchKernelGGL(ap_build_kernel, dim3(BP / 16, BP / 16, cnt), dim3(16, 16), 0, st, ctx->dX, ctx->d, n,
                        (const double*)ctx->dTheta, ctx->kernel, block, BP, blk0, A);
     for (int k = 0; k < nt; ++k) {
-      hipLaunchKernelGGL(ap_chol_diag_kernel, dim3(cnt), dim3(256), 0, st, A, BP, k, DI, W, fac_breakdown);
+      hipLaunchKernelGGL(ap_chol_diag_kernel, dim3(cnt), dim3(64), 0, st, A, BP, k, DI, W, fac_breakdown);
       const int below = nt - k - 1;
       if (below > 0) {
         hipLaunchKernelGGL(ap_chol_panel_kernel, dim3(below, cnt), dim3(256), 0, st, A, BP, k, (const fac_t*)DI);
