@@ -120,3 +120,53 @@ def test_config5_two_million_rows_sampled_against_oracle():
         assert abs(b2 @ k1 - b1 @ k2) <= 1e-5 * np.linalg.norm(b2) * np.linalg.norm(k1)
     finally:
         dv.close()
+
+
+def test_config2_full_size_alternating_projections_sampled_against_oracle():
+    """n=16384, t=65, block size 2000 (Appendix B): nine blocks, the last of 384 rows.  The solver as
+    bench.py --solver ap runs it: two warm-started optimiser steps, then at the last theta the true
+    residual of the solution on sampled rows (exact rows from the oracle), the first block choice
+    against the oracle's (largest ||B[I,:]||), and the inverse of one diagonal block at work: a single
+    step from zero must leave V[I,:] = H[I,I]^-1 B[I,:], which the oracle computes for that block alone."""
+    w = make("config2")
+    assert (w.n, w.d, w.s) == (16384, 26, 64)
+    block = 2000
+    opt = MllOptimizer(w.X, w.y, w.Z, w.kind, w.ell, w.a, w.sigma, w.tol, warm=True, max_iters=100000,
+                       solver="ap", block=block)
+    try:
+        recs = [opt.step() for _ in range(3)]
+        _note(f"block updates per step {[r.iters for r in recs]}")
+        assert all(r.rc == 0 for r in recs)
+        assert recs[-1].iters < recs[0].iters and recs[1].kmv_count == 1 and recs[0].kmv_count == 0
+        last = recs[-1]
+        ell, a, sigma = last.theta[: w.d], last.theta[w.d], last.theta[w.d + 1]
+        t = w.s + 1
+        V = opt.V.cpu().numpy().astype(np.float64)
+        B = opt.B.cpu().numpy().astype(np.float64)
+        rows = np.sort(np.random.default_rng(12).choice(w.n, size=1024, replace=False))
+        rows[0], rows[-1] = 0, w.n - 1
+        HV = orc.kmv_rows(w.X, ell, a, w.kind, V, rows, sigma=sigma)
+        res = np.linalg.norm(HV - B[rows], axis=0) * np.sqrt(w.n / rows.size)
+        rel = res / np.linalg.norm(B, axis=0)
+        _note(f"sampled true relative residual max {rel.max():.3e} (tol {w.tol})")
+        assert rel.max() <= 1.5 * w.tol
+
+        # one step from zero at the same theta
+        V1 = torch.zeros_like(opt.B)
+        rc, it, kmv, rr, pk = gp.gp_ap_solve(opt.ctx, opt.B, t, None, V1, t, t, 1e-12, block, 1, opt.work,
+                                             opt.work.numel(), want_picks=True)
+        assert rc == 1 and it == 1 and kmv == 0
+        scores = [np.sum(B[j0:j1] ** 2) for (j0, j1) in orc.ap_blocks(w.n, block)]
+        assert int(pk[0]) == int(np.argmax(scores))
+        j0, j1 = orc.ap_blocks(w.n, block)[int(pk[0])]
+        Hii = orc.coefficient_matrix(w.X[j0:j1], ell, a, sigma, w.kind)
+        ref = orc.chol_solve(Hii, B[j0:j1])
+        got = V1.cpu().numpy().astype(np.float64)
+        err = np.linalg.norm(got[j0:j1] - ref, axis=0) / np.linalg.norm(ref, axis=0)
+        _note(f"block solve relative error max {err.max():.2e}")
+        assert err.max() <= 2e-4
+        outside = np.ones(w.n, bool)
+        outside[j0:j1] = False
+        assert (got[outside] == 0.0).all()
+    finally:
+        opt.close()
