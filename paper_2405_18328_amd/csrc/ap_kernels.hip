@@ -68,14 +68,41 @@ struct Acc {
 };
 
 // source element (row, col) = src[row * ld + col].  by_col = false: the source row is the contraction
-// index, T[row][col] = src(row, col); by_col = true: the source column is, T[col][row] = src(row, col)
-__device__ __forceinline__ void load_tile(Tile& T, const fac_t* __restrict__ src, int64_t ld, bool by_col) {
-  for (int e = threadIdx.x; e < TS * TS; e += 256) {
-    const int rr = e / TS, cc = e % TS;
-    const fac_t v = src[(int64_t)rr * ld + cc];
-    if (by_col) T.v[cc][rr] = v;
-    else T.v[rr][cc] = v;
+// index, T[row][col] = src(row, col); by_col = true: the source column is, T[col][row] = src(row, col).
+// All global loads of a tile (16 per thread) are issued before the first LDS store, so that their
+// latencies overlap.
+struct TileRegs {
+  fac_t v[16];
+};
+__device__ __forceinline__ void fetch_tile(TileRegs& g, const fac_t* __restrict__ src, int64_t ld) {
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    const int e = threadIdx.x + 256 * q;
+    g.v[q] = src[(int64_t)(e / TS) * ld + (e % TS)];
   }
+}
+__device__ __forceinline__ void stash_tile(Tile& T, const TileRegs& g, bool by_col) {
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    const int e = threadIdx.x + 256 * q;
+    const int rr = e / TS, cc = e % TS;
+    if (by_col) T.v[cc][rr] = g.v[q];
+    else T.v[rr][cc] = g.v[q];
+  }
+}
+__device__ __forceinline__ void load_tile(Tile& T, const fac_t* __restrict__ src, int64_t ld, bool by_col) {
+  TileRegs g;
+  fetch_tile(g, src, ld);
+  stash_tile(T, g, by_col);
+}
+// both operand tiles of a product: 32 loads in flight, then the stores
+__device__ __forceinline__ void load_tiles(Tile& TA, const fac_t* __restrict__ srcA, int64_t ldA, bool by_colA,
+                                           Tile& TB, const fac_t* __restrict__ srcB, int64_t ldB, bool by_colB) {
+  TileRegs ga, gb;
+  fetch_tile(ga, srcA, ldA);
+  fetch_tile(gb, srcB, ldB);
+  stash_tile(TA, ga, by_colA);
+  stash_tile(TB, gb, by_colB);
 }
 
 __device__ __forceinline__ void clear_acc(Acc& acc) {
@@ -148,7 +175,13 @@ __global__ __launch_bounds__(64) void ap_chol_diag_kernel(fac_t* __restrict__ A,
   fac_t* Xb = X + tile_off;
   fac_t* DIb = DI + (int64_t)blockIdx.x * BP * TS + (int64_t)k * TS * TS;
   const int lane = threadIdx.x;
-  for (int i = 0; i < TS; ++i) T[i][lane] = Ab[(int64_t)i * BP + lane];
+  for (int i0 = 0; i0 < TS; i0 += 16) {     // 16 loads in flight at a time
+    fac_t g[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) g[q] = Ab[(int64_t)(i0 + q) * BP + lane];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) T[i0 + q][lane] = g[q];
+  }
   __syncthreads();
   bool any_bad = false;
   for (int c = 0; c < TS; ++c) {
@@ -208,8 +241,8 @@ __global__ __launch_bounds__(256) void ap_chol_panel_kernel(fac_t* __restrict__ 
   const int it = k + 1 + blockIdx.x;
   fac_t* Aik = A + (int64_t)blockIdx.y * BP * BP + (int64_t)it * TS * BP + k * TS;
   const fac_t* DIb = DI + (int64_t)blockIdx.y * BP * TS + (int64_t)k * TS * TS;
-  load_tile(TA, Aik, BP, true);     // A_ik(r, m)
-  load_tile(TB, DIb, TS, true);     // L_kk^-1(c, m)
+  load_tiles(TA, Aik, BP, true,     // A_ik(r, m)
+             TB, DIb, TS, true);    // L_kk^-1(c, m)
   __syncthreads();
   Acc acc;
   clear_acc(acc);
@@ -226,8 +259,8 @@ __global__ __launch_bounds__(256) void ap_chol_update_kernel(fac_t* __restrict__
   if (blockIdx.x > blockIdx.y) return;
   const int I = k + 1 + blockIdx.y, J = k + 1 + blockIdx.x;
   fac_t* Ab = A + (int64_t)blockIdx.z * BP * BP;
-  load_tile(TA, Ab + (int64_t)I * TS * BP + k * TS, BP, true);   // L_Ik(r, m)
-  load_tile(TB, Ab + (int64_t)J * TS * BP + k * TS, BP, true);   // L_Jk(c, m)
+  load_tiles(TA, Ab + (int64_t)I * TS * BP + k * TS, BP, true,    // L_Ik(r, m)
+             TB, Ab + (int64_t)J * TS * BP + k * TS, BP, true);   // L_Jk(c, m)
   __syncthreads();
   Acc acc;
   clear_acc(acc);
@@ -273,10 +306,20 @@ __global__ __launch_bounds__(256) void ap_trinv_merge_kernel(const fac_t* __rest
   }
   Acc acc;
   clear_acc(acc);
+  // the next pair of tiles is fetched into registers while the matrix cores work on the current one
+  TileRegs ga, gb;
+  if (mlo <= mhi) {
+    fetch_tile(ga, P + (int64_t)ti * TS * BP + mlo * TS, BP);   // P(r, q): the source column is the contraction index
+    fetch_tile(gb, Q + (int64_t)mlo * TS * BP + tj * TS, BP);   // Q(q, c)
+  }
   for (int m = mlo; m <= mhi; ++m) {
-    load_tile(TA, P + (int64_t)ti * TS * BP + m * TS, BP, true);    // P(r, q): the source column is the contraction index
-    load_tile(TB, Q + (int64_t)m * TS * BP + tj * TS, BP, false);   // Q(q, c)
+    stash_tile(TA, ga, true);
+    stash_tile(TB, gb, false);
     __syncthreads();
+    if (m < mhi) {
+      fetch_tile(ga, P + (int64_t)ti * TS * BP + (m + 1) * TS, BP);
+      fetch_tile(gb, Q + (int64_t)(m + 1) * TS * BP + tj * TS, BP);
+    }
     mac_tile(TA, TB, acc);
     __syncthreads();
   }
@@ -296,10 +339,17 @@ __global__ __launch_bounds__(256) void ap_lauum_kernel(const fac_t* __restrict__
   const fac_t* Wb = W + (int64_t)blockIdx.z * BP * BP;
   Acc acc;
   clear_acc(acc);
+  TileRegs ga, gb;
+  fetch_tile(ga, Wb + (int64_t)ti * TS * BP + ti * TS, BP);   // X_m,ti(q, r)
+  fetch_tile(gb, Wb + (int64_t)ti * TS * BP + tj * TS, BP);   // X_m,tj(q, c)
   for (int m = ti; m < nt; ++m) {
-    load_tile(TA, Wb + (int64_t)m * TS * BP + ti * TS, BP, false);   // X_m,ti(q, r)
-    load_tile(TB, Wb + (int64_t)m * TS * BP + tj * TS, BP, false);   // X_m,tj(q, c)
+    stash_tile(TA, ga, false);
+    stash_tile(TB, gb, false);
     __syncthreads();
+    if (m + 1 < nt) {      // fetched while the matrix cores work on tile m
+      fetch_tile(ga, Wb + (int64_t)(m + 1) * TS * BP + ti * TS, BP);
+      fetch_tile(gb, Wb + (int64_t)(m + 1) * TS * BP + tj * TS, BP);
+    }
     mac_tile(TA, TB, acc);
     __syncthreads();
   }
