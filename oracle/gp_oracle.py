@@ -28,7 +28,7 @@ formula, and never mentions the squared exponential):
 Pin status: every function below is pinned by tests/test_oracle_pins.py against
 something other than itself (scikit-learn / SciPy library routines, hand values,
 closed forms, finite differences, brute force).  The only unpinned quantity is
-the warm-vs-cold iteration *count* of either solver (the paper gives it only as
+the warm-vs-cold iteration *count* of the solvers (the paper gives it only as
 stripped figures): "parity unpinned" for iteration numbers; the solutions
 themselves are pinned.
 """
@@ -338,6 +338,61 @@ def ap_batched(H, B, X0=None, tol=0.01, block=2000, max_iters=10000):
         relres = np.where(live, np.sqrt(np.sum(R * R, axis=0)) / safe, relres)
         frozen = frozen | (relres < tol)
     return V, iters, relres, picks
+
+
+# --------------------------------------------------------------------------
+# Stochastic gradient descent as the linear system solver (Section 2.1 lists it,
+# citing Lin et al.; Appendix B gives what is fixed: mini-batches of 1000 data
+# points, momentum 0.9, no iterate averaging, a residual vector kept in memory
+# and refreshed on the mini-batch rows only, "the gradient is equal to the
+# residual").  The steps as read here, one recurrence per column, all columns
+# sharing each mini-batch I (distinct row indices, given by the caller):
+#   G      = H[I,:] U - B[I,:]        gradient of the quadratic of Section 2.1 on the rows I
+#   R[I,:] = -G                       the residual estimate, refreshed on I only
+#   M      = rho M ;  M[I,:] -= (lr / |I|) G        (momentum; lr / |I| is the step on a sampled row:
+#   U     += M                         Appendix B's rates 20..100 with |I| = 1000 are steps of 0.02..0.1)
+# Column c stops being updated (its momentum is dropped) once the ESTIMATED
+# residual satisfies ||R_c|| / ||b_c|| < tol_c; the test is made after every step.
+# --------------------------------------------------------------------------
+def sgd_batched(H, B, batches, X0=None, tol=0.01, lr=50.0, momentum=0.9, max_iters=None):
+    """batches: sequence of 1-D integer arrays (distinct indices each); step k uses batches[k].
+
+    Returns (U, iters, relres_est): iters = steps done (at most len(batches) or max_iters),
+    relres_est = the final estimated relative residuals.
+    """
+    H = _f64(H)
+    B = _f64(B)
+    n, t = B.shape
+    tol = np.broadcast_to(np.asarray(tol, dtype=np.float64), (t,)).copy()
+    bnorm = np.sqrt(np.sum(B * B, axis=0))
+    if X0 is None:
+        U = np.zeros_like(B)
+        R = B.copy()
+    else:
+        U = _f64(X0).copy()
+        R = B - H @ U
+    zero_rhs = bnorm == 0.0
+    U[:, zero_rhs] = 0.0
+    R[:, zero_rhs] = 0.0
+    safe = np.where(zero_rhs, 1.0, bnorm)
+    relres = np.sqrt(np.sum(R * R, axis=0)) / safe
+    frozen = zero_rhs | (relres < tol)
+    M = np.zeros_like(B)
+    limit = len(batches) if max_iters is None else min(max_iters, len(batches))
+    iters = 0
+    while not frozen.all() and iters < limit:
+        I = np.asarray(batches[iters], dtype=np.int64)
+        live = ~frozen
+        G = H[I, :] @ U - B[I, :]
+        R[np.ix_(I, live)] = -G[:, live]
+        M[:, live] *= momentum
+        M[np.ix_(I, live)] -= (lr / I.size) * G[:, live]
+        M[:, frozen] = 0.0
+        U += M
+        iters += 1
+        relres = np.where(live, np.sqrt(np.sum(R * R, axis=0)) / safe, relres)
+        frozen = frozen | (relres < tol)
+    return U, iters, relres
 
 
 # --------------------------------------------------------------------------

@@ -386,6 +386,84 @@ def test_ap_stopping_rule_freeze_and_warm_start():
     assert it_cap == 3 and (rr[:-1] > 1e-12).any()
 
 
+# ---------------------------------------------------------------- stochastic gradient descent solver
+def _batches(n, b, steps, seed):
+    rng = np.random.default_rng(seed)
+    return [rng.permutation(n)[:b] for _ in range(steps)]
+
+
+def test_sgd_full_batch_is_heavy_ball_gradient_descent_with_known_rate():
+    """|I| = n: deterministic heavy-ball descent, e_{k+1} = e_k + rho (e_k - e_{k-1}) - (lr/n) H e_k.  In the
+    eigenbasis of H every error component follows a scalar three-term recurrence, written out here."""
+    n = 30
+    X, ell, a, sigma, y, Z = _problem(n, 2, 41)
+    H = orc.coefficient_matrix(X, ell, a, sigma, orc.SE)
+    lam, Q = np.linalg.eigh(H)
+    lr, rho, steps = 0.8 * n / lam.max(), 0.9, 60
+    full = [np.arange(n)] * steps
+    U, iters, _ = orc.sgd_batched(H, y[:, None], full, tol=1e-300, lr=lr, momentum=rho)
+    assert iters == steps
+    e_prev = e = Q.T @ (0.0 - np.linalg.solve(H, y))        # error of the zero start in the eigenbasis
+    for _ in range(steps):
+        e, e_prev = e + rho * (e - e_prev) - (lr / n) * lam * e, e
+    np.testing.assert_allclose(U[:, 0], np.linalg.solve(H, y) + Q @ e, rtol=1e-9, atol=1e-12)
+
+
+def test_sgd_single_step_by_hand_and_sparse_residual():
+    n, b = 20, 5
+    X, ell, a, sigma, y, Z = _problem(n, 2, 42)
+    H = orc.coefficient_matrix(X, ell, a, sigma, orc.MATERN32)
+    B = np.concatenate([y[:, None], Z[:, :2]], axis=1)
+    I = np.array([3, 17, 4, 11, 0])
+    U0 = np.random.default_rng(1).standard_normal(B.shape)
+    U1, it, rel = orc.sgd_batched(H, B, [I], X0=U0, tol=1e-300, lr=2.0, momentum=0.9)
+    assert it == 1
+    r0 = B - H @ U0                                         # true residual at the start
+    expect = U0.copy()
+    for i in I:                                             # first step: the momentum is just the scaled residual
+        expect[i] += (2.0 / b) * r0[i]
+    np.testing.assert_allclose(U1, expect, rtol=1e-12, atol=1e-14)
+    # the estimate was exact at the start and is only refreshed on I (with the same values): unchanged norm
+    np.testing.assert_allclose(rel, np.linalg.norm(r0, axis=0) / np.linalg.norm(B, axis=0), rtol=1e-12)
+    # second step: rows outside the second batch keep their stale residual
+    J = np.array([1, 2, 5, 6, 7])
+    U2, _, rel2 = orc.sgd_batched(H, B, [I, J], X0=U0, tol=1e-300, lr=2.0, momentum=0.9)
+    r_est = r0.copy()
+    r_est[J] = (B - H @ U1)[J]
+    np.testing.assert_allclose(rel2, np.linalg.norm(r_est, axis=0) / np.linalg.norm(B, axis=0), rtol=1e-12)
+    m1 = U1 - U0
+    expect2 = U1 + 0.9 * m1
+    expect2[J] += (2.0 / b) * (B - H @ U1)[J]
+    np.testing.assert_allclose(U2, expect2, rtol=1e-12, atol=1e-14)
+
+
+def test_sgd_converges_to_the_library_solution_and_honours_the_rules():
+    n, b = 60, 12
+    X, ell, a, sigma, y, Z = _problem(n, 3, 43)
+    H = orc.coefficient_matrix(X, ell, a, sigma, orc.MATERN32)
+    B = np.concatenate([y[:, None], Z, np.zeros((n, 1))], axis=1)
+    sol = np.linalg.solve(H, B)
+    bt = _batches(n, b, 4000, 7)
+    U, iters, rel = orc.sgd_batched(H, B, bt, tol=1e-6, lr=0.4, momentum=0.9)
+    assert iters < 4000 and (rel < 1e-6).all() and np.all(U[:, -1] == 0.0)
+    np.testing.assert_allclose(U, sol, rtol=0, atol=1e-4 * np.abs(sol).max())
+    # the solution is a fixed point: nothing to do from there
+    U2, it2, _ = orc.sgd_batched(H, B, bt, X0=sol, tol=1e-8)
+    assert it2 == 0 and np.array_equal(U2, sol)
+    # per-column tolerances: loose columns stop being updated while the tight one goes on
+    tol = np.array([1e-5] + [0.3] * Z.shape[1] + [0.01])
+    U3, it3, rel3 = orc.sgd_batched(H, B, bt, tol=tol, lr=0.4, momentum=0.9)
+    assert (rel3 < tol).all() and rel3[1] > 1e-3 > rel3[0]
+    # warm start (Section 3): the solution at nearby hyperparameters needs fewer steps
+    H2 = orc.coefficient_matrix(X, ell * 1.02, a, sigma, orc.MATERN32)
+    _, cold, _ = orc.sgd_batched(H2, B, bt, tol=1e-3, lr=0.4, momentum=0.9)
+    _, warm, _ = orc.sgd_batched(H2, B, bt, X0=sol, tol=1e-3, lr=0.4, momentum=0.9)
+    assert warm < cold
+    # the cap
+    _, capped, relc = orc.sgd_batched(H, B, bt, tol=1e-12, lr=0.4, momentum=0.9, max_iters=5)
+    assert capped == 5 and (relc[:-1] > 1e-12).any()
+
+
 def test_warm_start_first_order_taylor_is_second_order_accurate():
     """Section 3: v(t+1) ~ v(t) - H_t^{-1} (H_{t+1} - H_t) v(t); halving the step
     in theta must quarter the error of that approximation."""
