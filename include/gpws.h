@@ -154,6 +154,36 @@ int gp_ap_solve(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, flo
                 int* h_iters, int* h_kmv_count, float* h_relres, int* h_picks);
 
 /*
+ * The same batched system solved by stochastic gradient descent on the quadratic objective of
+ * Section 2.1 (the paper lists the solver, citing Lin et al.; Appendix B: mini-batches of 1000 data
+ * points, momentum 0.9, no iterate averaging, a residual vector kept in memory and refreshed on the
+ * mini-batch rows only).  Step k, with I = the k-th mini-batch, for all t columns at once:
+ *   G = H[I,:] U - B[I,:];  R[I,:] = -G;  M = momentum * M;  M[I,:] -= (lr / batch) * G;  U += M.
+ * Column c is no longer updated once the ESTIMATED residual satisfies ||R_c|| / ||b_c|| < tol_c (the
+ * test is made after every step); a column with b_c = 0 gets the solution 0.  R starts as the true
+ * residual (B, or B - H x0 for a warm start, which costs one full product).
+ *   dB, dX0, dV, ldb, ldv, t, h_tol, h_relres, h_kmv_count: as for gp_cg_solve; h_relres are the
+ *          estimated relative residuals.
+ *   dBatches: device, max_iters x batch int32, row k = the indices of mini-batch k, each in [0, n) and
+ *          distinct within a row (not checked: repeated indices lose updates; an index outside
+ *          [0, n) is never dereferenced and makes the call return GP_ERR_ARG).  The library draws no
+ *          random numbers.
+ *   batch : 1 .. min(n, GP_SGD_MAX_BATCH).   lr > 0: the step on a sampled row is lr / batch
+ *          (Appendix B's rates are 20 .. 100 with batch 1000).   0 <= momentum < 1.
+ *   max_iters >= 0: cap on the number of steps.   h_iters: out, steps done.
+ *   dWork/work_bytes: device scratch, at least gp_sgd_workspace_bytes(ctx, t, batch), 256-byte aligned.
+ * Returns GP_OK, GP_NOT_CONVERGED (dV holds the last iterate), GP_ERR_BREAKDOWN when the residual
+ * estimate stops being finite (learning rate too large), or an argument/workspace/HIP error.
+ * Synchronises the stream.
+ */
+#define GP_SGD_MAX_BATCH 65536
+size_t gp_sgd_workspace_bytes(const gp_ctx* ctx, int t, int batch);
+int gp_sgd_solve(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv,
+                 int t, const float* h_tol, const int32_t* dBatches, int batch, int max_iters, double lr,
+                 double momentum, void* dWork, size_t work_bytes, int* h_iters, int* h_kmv_count,
+                 float* h_relres);
+
+/*
  * Stochastic estimate of the gradient of the log marginal likelihood (Section 2
  * gradient equation with the trace replaced by the s-probe estimator of
  * Section 2.1, normalised by 1/s):

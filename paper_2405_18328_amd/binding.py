@@ -31,7 +31,7 @@ LIB_PATH = os.environ.get("GPWS_LIB") or os.path.join(os.path.dirname(os.path.ab
 GP_AP_MAX_BLOCK = 2048
 
 EXPORTS = ["gp_create", "gp_destroy", "gp_set_theta", "gp_kmv", "gp_workspace_bytes", "gp_cg_solve",
-           "gp_ap_workspace_bytes", "gp_ap_solve", "gp_mll_grad", "gp_predict", "gp_profile", "gp_profile_read", "gp_product_path", "gp_last_error"]
+           "gp_ap_workspace_bytes", "gp_ap_solve", "gp_sgd_workspace_bytes", "gp_sgd_solve", "gp_mll_grad", "gp_predict", "gp_profile", "gp_profile_read", "gp_product_path", "gp_last_error"]
 
 
 def _load():
@@ -51,6 +51,10 @@ def _load():
     lib.gp_ap_workspace_bytes.restype = sz
     lib.gp_ap_solve.argtypes = [p, p, i64, p, p, i64, i32, C.POINTER(C.c_float), i32, i32, p, sz,
                                 C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(i32)]
+    lib.gp_sgd_workspace_bytes.argtypes = [p, i32, i32]
+    lib.gp_sgd_workspace_bytes.restype = sz
+    lib.gp_sgd_solve.argtypes = [p, p, i64, p, p, i64, i32, C.POINTER(C.c_float), p, i32, i32, dbl, dbl, p, sz,
+                                 C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_float)]
     lib.gp_mll_grad.argtypes = [p, p, i64, p, i64, i32, C.POINTER(dbl)]
     lib.gp_predict.argtypes = [p, p, i64, p, i64, i32, p, i64]
     lib.gp_profile.argtypes = [p, i32]
@@ -59,7 +63,7 @@ def _load():
     lib.gp_last_error.argtypes = [p]
     lib.gp_last_error.restype = C.c_char_p
     for name in EXPORTS:
-        if name not in ("gp_workspace_bytes", "gp_ap_workspace_bytes", "gp_last_error"):
+        if name not in ("gp_workspace_bytes", "gp_ap_workspace_bytes", "gp_sgd_workspace_bytes", "gp_last_error"):
             getattr(lib, name).restype = i32
     return lib
 
@@ -152,6 +156,23 @@ def gp_ap_solve(ctx, dB, ldb, dX0, dV, ldv, t, tol, block, max_iters, dWork, wor
                           picks.ctypes.data_as(C.POINTER(C.c_int)) if want_picks else None)
     _check(ctx, rc)
     return rc, iters.value, kmv.value, relres, (picks[:iters.value] if want_picks else None)
+
+
+def gp_sgd_workspace_bytes(ctx, t, batch):
+    return int(_lib.gp_sgd_workspace_bytes(ctx, int(t), int(batch)))
+
+
+def gp_sgd_solve(ctx, dB, ldb, dX0, dV, ldv, t, tol, dBatches, batch, max_iters, lr, momentum, dWork, work_bytes):
+    """dBatches: device int32 [max_iters, batch].  Returns (rc, iters, kmv_count, relres_est[t]); raises GpError on rc < 0."""
+    tol_arr = np.ascontiguousarray(np.broadcast_to(np.asarray(tol, dtype=np.float32), (t,)))
+    iters, kmv = C.c_int(0), C.c_int(0)
+    relres = np.zeros(t, dtype=np.float32)
+    rc = _lib.gp_sgd_solve(ctx, _ptr(dB), int(ldb), _ptr(dX0), _ptr(dV), int(ldv), int(t),
+                           tol_arr.ctypes.data_as(C.POINTER(C.c_float)), _ptr(dBatches), int(batch), int(max_iters),
+                           float(lr), float(momentum), _ptr(dWork), int(work_bytes), C.byref(iters), C.byref(kmv),
+                           relres.ctypes.data_as(C.POINTER(C.c_float)))
+    _check(ctx, rc)
+    return rc, iters.value, kmv.value, relres
 
 
 def gp_mll_grad(ctx, dV, ldv, dB, ldb, t, d):

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgpws.so")
-SOURCES = ["gpws_api.hip", "prep_kernels.hip", "tile_pass.hip", "tile_pass_f16.hip", "cg_kernels.hip", "grad_pass.hip", "grad_pass_f16.hip", "ap_kernels.hip"]
+SOURCES = ["gpws_api.hip", "prep_kernels.hip", "tile_pass.hip", "tile_pass_f16.hip", "cg_kernels.hip", "grad_pass.hip", "grad_pass_f16.hip", "ap_kernels.hip", "sgd_kernels.hip"]
 # packed FP32 VALU forms are kept off on purpose (some forms have miscomputed on the test machines)
 # MFMA accumulators are kept in ordinary VGPRs (vgpr-form): the tile kernels feed the result of one
 # MFMA chain through the VALU into the next chain, and the AGPR form costs a copy each way per value.

@@ -258,6 +258,35 @@ int gp_ap_solve(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, flo
                    h_relres, h_picks);
 }
 
+size_t gp_sgd_workspace_bytes(const gp_ctx* ctx, int t, int batch) {
+  if (!ctx || t < 1 || t > GP_MAX_T || batch < 1 || batch > GP_SGD_MAX_BATCH || batch > ctx->n) return 0;
+  return gp_sgd_workspace_bytes_impl(ctx, t, batch);
+}
+
+int gp_sgd_solve(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv, int t,
+                 const float* h_tol, const int32_t* dBatches, int batch, int max_iters, double lr, double momentum,
+                 void* dWork, size_t work_bytes, int* h_iters, int* h_kmv_count, float* h_relres) {
+  if (!ctx) return GP_ERR_ARG;
+  if (!ctx->theta_set) return gp_fail(ctx, GP_ERR_ARG, "gp_sgd_solve: gp_set_theta has not been called");
+  if (t < 1 || t > GP_MAX_T) return gp_fail(ctx, GP_ERR_ARG, "gp_sgd_solve: t = %d outside [1, %d]", t, GP_MAX_T);
+  if (batch < 1 || batch > GP_SGD_MAX_BATCH || batch > ctx->n)
+    return gp_fail(ctx, GP_ERR_ARG, "gp_sgd_solve: batch = %d outside [1, min(n, %d)]", batch, GP_SGD_MAX_BATCH);
+  int rc;
+  if ((rc = check_block(ctx, "gp_sgd_solve(dB)", dB, ldb, t)) < 0) return rc;
+  if ((rc = check_block(ctx, "gp_sgd_solve(dV)", dV, ldv, t)) < 0) return rc;
+  if (!h_tol) return gp_fail(ctx, GP_ERR_ARG, "gp_sgd_solve: NULL tolerances");
+  for (int c = 0; c < t; ++c)
+    if (!(h_tol[c] > 0.0f) || !std::isfinite(h_tol[c]))
+      return gp_fail(ctx, GP_ERR_ARG, "gp_sgd_solve: tolerance %d = %g is not positive and finite", c, (double)h_tol[c]);
+  if (max_iters < 0) return gp_fail(ctx, GP_ERR_ARG, "gp_sgd_solve: max_iters < 0");
+  if (max_iters > 0 && !dBatches) return gp_fail(ctx, GP_ERR_ARG, "gp_sgd_solve: NULL mini-batch indices");
+  if (!(lr > 0.0) || !std::isfinite(lr)) return gp_fail(ctx, GP_ERR_ARG, "gp_sgd_solve: learning rate %g is not positive and finite", lr);
+  if (!(momentum >= 0.0) || !(momentum < 1.0)) return gp_fail(ctx, GP_ERR_ARG, "gp_sgd_solve: momentum %g outside [0, 1)", momentum);
+  if (!dWork) return gp_fail(ctx, GP_ERR_WORKSPACE, "gp_sgd_solve: NULL workspace");
+  return gp_sgd_run(ctx, dB, ldb, dX0, dV, ldv, t, h_tol, dBatches, batch, max_iters, lr, momentum, dWork, work_bytes,
+                    h_iters, h_kmv_count, h_relres);
+}
+
 int gp_mll_grad(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int64_t ldb, int t, double* h_grad) {
   if (!ctx) return GP_ERR_ARG;
   if (!ctx->theta_set) return gp_fail(ctx, GP_ERR_ARG, "gp_mll_grad: gp_set_theta has not been called");

@@ -168,6 +168,12 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
               const float* h_tol, int block, int max_iters, void* dWork, size_t work_bytes, int* h_iters,
               int* h_kmv_count, float* h_relres, int* h_picks);
 
+// ---- sgd_kernels.hip
+size_t gp_sgd_workspace_bytes_impl(const gp_ctx* ctx, int t, int batch);
+int gp_sgd_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv, int t,
+               const float* h_tol, const int* dBatches, int batch, int max_iters, double lr, double momentum,
+               void* dWork, size_t work_bytes, int* h_iters, int* h_kmv_count, float* h_relres);
+
 // ---- cg_kernels.hip
 int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float* dV, int64_t ldv,
               int t, const float* h_tol, int max_iters, void* dWork, size_t work_bytes,

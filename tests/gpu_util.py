@@ -83,6 +83,23 @@ class Dev:
                                                          w.numel(), want_picks=picks)
         return rc, iters, kmv, relres, pk, Vd
 
+    def sgd_solve(self, B, tol, batches, lr, momentum=0.9, max_iters=None, X0=None, Vd=None):
+        """batches: int array [steps, batch].  Returns (rc, iters, kmv_count, relres_est, V device tensor)."""
+        n, t = B.shape
+        Bd = B if isinstance(B, torch.Tensor) else self.to(B)
+        if Vd is None:
+            Vd = torch.zeros((n, t), device=self.dev)
+        bt = torch.from_numpy(np.ascontiguousarray(batches, dtype=np.int32)).to(self.dev)
+        steps, batch = bt.shape
+        if max_iters is None:
+            max_iters = steps
+        assert max_iters <= steps
+        need = self.gp.gp_sgd_workspace_bytes(self.ctx, t, batch)
+        w = torch.empty(need, dtype=torch.uint8, device=self.dev)
+        rc, iters, kmv, relres = self.gp.gp_sgd_solve(self.ctx, Bd, t, X0, Vd, t, t, tol, bt, batch, max_iters, lr,
+                                                      momentum, w, w.numel())
+        return rc, iters, kmv, relres, Vd
+
     def grad(self, Vd, Bd):
         t = Bd.shape[1]
         return self.gp.gp_mll_grad(self.ctx, Vd, t, Bd, t, t, self.d)
