@@ -92,9 +92,12 @@ def main():
     ap.add_argument("--probe-tol", type=float, default=None,
                     help="tolerance of the probe systems when it differs from the workload's (Appendix B of the "
                          "paper solves y to 0.01 and the probes to 0.1); default: the workload's tolerance for all")
-    ap.add_argument("--solver", default="cg", choices=["cg", "ap"],
-                    help="linear system solver of the MLL steps: conjugate gradients (the headline path) or "
-                         "alternating projections (then iterations are block updates and a product is H[:, I] d)")
+    ap.add_argument("--solver", default="cg", choices=["cg", "ap", "sgd"],
+                    help="linear system solver of the MLL steps: conjugate gradients (the headline path), "
+                         "alternating projections (iterations are block updates, a product is H[:, I] d) or "
+                         "stochastic gradient descent (iterations are mini-batch steps, a product is H[I, :] U)")
+    ap.add_argument("--batch", type=int, default=1000, help="mini-batch size of --solver sgd (the paper's is 1000)")
+    ap.add_argument("--lr", type=float, default=50.0, help="learning rate of --solver sgd (step on a sampled row = lr / batch)")
     ap.add_argument("--block", type=int, default=2000, help="block size of --solver ap (the paper's is 2000)")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
                     help="also run three plain device copies of MIB MiB (reads MIB, writes MIB): the known-size "
@@ -117,6 +120,8 @@ def main():
     max_iters = args.max_iters if args.max_iters is not None else (6 if args.workload == "config5" else (30 if big else 1000))
     if args.solver == "ap" and args.max_iters is None:
         max_iters = 100000
+    if args.solver == "sgd" and args.max_iters is None:
+        max_iters = 4096
 
     kw = {"n": args.n} if args.n else {}
     t_gen = time.perf_counter()
@@ -134,20 +139,26 @@ def main():
         desc += f", probe systems to {args.probe_tol:g}"
     if args.solver == "ap":
         desc = desc.replace("CG rel tol", f"alternating projections (block {args.block}) rel tol")
+    if args.solver == "sgd":
+        desc = desc.replace("CG rel tol", f"SGD (batch {args.batch}, lr {args.lr:g}, momentum 0.9) estimated rel tol")
     opt = MllOptimizer(w.X, w.y, w.Z, w.kind, w.ell, w.a, w.sigma, tol, warm=True, max_iters=max_iters,
-                       solver=args.solver, block=args.block)
+                       solver=args.solver, block=args.block, batch=args.batch, sgd_lr=args.lr)
 
     def solve(B, x0, V):
         if args.solver == "cg":
             return gp.gp_cg_solve(opt.ctx, B, t, x0, V, t, t, tol, max_iters, opt.work, opt.work.numel())
+        if args.solver == "sgd":
+            return gp.gp_sgd_solve(opt.ctx, B, t, x0, V, t, t, tol, opt.batches, opt.batch, opt.max_iters, args.lr, 0.9,
+                                   opt.work, opt.work.numel())
         return gp.gp_ap_solve(opt.ctx, B, t, x0, V, t, t, tol, args.block, max_iters, opt.work, opt.work.numel())[:4]
 
     # algorithmic flops of the products of one solve: full products, plus (alternating projections) one
     # product over a block's columns per step
-    window_frac = min(args.block, n) / n if args.solver == "ap" else 1.0
+    window_frac = (min(args.block, n) / n if args.solver == "ap" else
+                   min(args.batch, n) / n if args.solver == "sgd" else 1.0)
 
     def products(rec_kmv, rec_iters):
-        return rec_kmv + (rec_iters * window_frac if args.solver == "ap" else 0.0)
+        return rec_kmv + (rec_iters * window_frac if args.solver != "cg" else 0.0)
     result = {}
     try:
         if args.calib_copy:
@@ -220,6 +231,10 @@ def main():
                           "max_relres": [round(r.max_relres, 6) for r in opt.history],
                           "not_converged_steps": int(sum(r.rc != 0 for r in timed))}
             extra = {"warm": warm_stats}
+            if args.solver == "sgd":
+                extra["solver"] = {"name": "stochastic gradient descent", "batch": args.batch, "lr": args.lr, "momentum": 0.9,
+                                   "note": "iters = mini-batch steps (at most 4096 per solve); the stopping test uses the "
+                                           "sparsely refreshed residual estimate"}
             if args.solver == "ap":
                 extra["solver"] = {"name": "alternating projections", "block": args.block,
                                    "note": "iters = block updates; cg_ms_per_step = solver time per step, which "

@@ -86,7 +86,7 @@ __global__ __launch_bounds__(256) void sgd_init_kernel(const float* __restrict__
         accr = fmaf(r, r, accr);
         mx = fmaxf(mx, fabsf(x));
       }
-      if (mx > 0.0f) atomicMax(&colmax[c], __float_as_uint(mx));
+      if (mx > 0.0f) atomicMax(&colmax[c], __float_as_uint(mx));   // once per solve: straight to memory
     }
     store_column_sums(m, valid, accb, cg, t, red, partB + (int64_t)blockIdx.x * t);
     store_column_sums(m, valid, accr, cg, t, red, partR + (int64_t)blockIdx.x * t);
@@ -161,8 +161,16 @@ __global__ __launch_bounds__(256) void sgd_batch_kernel(const int* __restrict__ 
         const int64_t i = clamp_index(I[s], n, bad);
         float hx;
         if (JS > 1) {
-          hx = 0.0f;
-          for (int q = 0; q < JS; ++q) hx += part[(int64_t)q * stride + e];
+          float h0 = 0.0f, h1 = 0.0f, h2 = 0.0f, h3 = 0.0f;      // four chains so that the loads overlap
+          int q = 0;
+          for (; q + 3 < JS; q += 4) {
+            h0 += part[(int64_t)q * stride + e];
+            h1 += part[(int64_t)(q + 1) * stride + e];
+            h2 += part[(int64_t)(q + 2) * stride + e];
+            h3 += part[(int64_t)(q + 3) * stride + e];
+          }
+          for (; q < JS; ++q) h0 += part[(int64_t)q * stride + e];
+          hx = (h0 + h1) + (h2 + h3);
         } else {
           hx = OUT[e];
         }
@@ -194,7 +202,10 @@ __global__ __launch_bounds__(256) void sgd_stream_kernel(float* __restrict__ U, 
                                                          float rho, const int* __restrict__ frozen,
                                                          unsigned* __restrict__ colmax,
                                                          const SgdFlags* __restrict__ flags) {
+  __shared__ unsigned smax[GP_MAX_T];
   if (flags->all_done) return;
+  for (int c = threadIdx.x; c < t; c += 256) smax[c] = 0u;
+  __syncthreads();
   int64_t r0, r1;
   wg_rows(n, &r0, &r1);
   const ColMap m = col_map(t);
@@ -211,9 +222,12 @@ __global__ __launch_bounds__(256) void sgd_stream_kernel(float* __restrict__ U, 
         U[e] = u;
         mx = fmaxf(mx, fabsf(u));
       }
-      if (mx > 0.0f) atomicMax(&colmax[c], __float_as_uint(mx));
+      if (mx > 0.0f) atomicMax(&smax[c], __float_as_uint(mx));
     }
   }
+  __syncthreads();
+  for (int c = threadIdx.x; c < t; c += 256)
+    if (smax[c]) atomicMax(&colmax[c], smax[c]);
 }
 
 // the batch rows' own part of the step: M[I] -= Gs, U[I] -= Gs (indices are distinct)
@@ -221,7 +235,10 @@ __global__ __launch_bounds__(256) void sgd_scatter_kernel(const int* __restrict_
                                                           const float* __restrict__ Gs, float* __restrict__ U,
                                                           float* __restrict__ M, unsigned* __restrict__ colmax,
                                                           const SgdFlags* __restrict__ flags, int* __restrict__ bad) {
+  __shared__ unsigned smax[GP_MAX_T];
   if (flags->all_done) return;
+  for (int c = threadIdx.x; c < t; c += 256) smax[c] = 0u;
+  __syncthreads();
   const int64_t total = (int64_t)b * t;
   for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
     const int64_t s = e / t;
@@ -232,13 +249,41 @@ __global__ __launch_bounds__(256) void sgd_scatter_kernel(const int* __restrict_
       M[i * t + c] -= g;
       const float u = U[i * t + c] - g;
       U[i * t + c] = u;
-      atomicMax(&colmax[c], __float_as_uint(fabsf(u)));
+      atomicMax(&smax[c], __float_as_uint(fabsf(u)));
     }
   }
+  __syncthreads();
+  for (int c = threadIdx.x; c < t; c += 256)
+    if (smax[c]) atomicMax(&colmax[c], smax[c]);
+}
+
+// scol[c] = sum over the G workgroup partials of column c: 1024 / t segments of the partials are summed
+// side by side and combined in a fixed order (t <= 1024; blockDim = 1024)
+__device__ void sgd_column_totals(const double* __restrict__ part, int G, int t, double* spart, double* scol) {
+  const int tid = threadIdx.x;
+  const int nseg = 1024 / t;
+  const int per = (G + nseg - 1) / nseg;
+  const int seg = tid / t, c = tid - seg * t;
+  if (seg < nseg) {
+    double v = 0.0;
+    const int w1 = (seg + 1) * per < G ? (seg + 1) * per : G;
+    for (int w = seg * per; w < w1; ++w) v += part[(int64_t)w * t + c];
+    spart[seg * t + c] = v;
+  }
+  __syncthreads();
+  if (tid < t) {
+    double v = 0.0;
+    for (int g = 0; g < nseg; ++g) v += spart[g * t + tid];
+    scol[tid] = v;
+  }
+  __syncthreads();
 }
 
 // per-column state: sums the workgroup partials in order, applies the stopping rule, posts the flags
 __global__ __launch_bounds__(1024) void sgd_finalise_kernel(SgdDev s, int G, int t, int init, const int* __restrict__ bad) {
+  __shared__ double spart[1024];
+  __shared__ double scol[GP_MAX_T];
+  __shared__ double scolb[GP_MAX_T];
   __shared__ int s_any, s_bad;
   const int tid = threadIdx.x;
   if (!init && s.flags->all_done) return;
@@ -246,16 +291,15 @@ __global__ __launch_bounds__(1024) void sgd_finalise_kernel(SgdDev s, int G, int
     s_any = 0;
     s_bad = *bad;
   }
-  __syncthreads();
-  for (int c = tid; c < t; c += 1024) {
-    double acc = 0.0, accb = 0.0;
-    for (int w = 0; w < G; ++w) {
-      acc += s.part[(int64_t)w * t + c];
-      if (init) accb += s.part2[(int64_t)w * t + c];
-    }
+  if (init) sgd_column_totals(s.part2, G, t, spart, scolb);
+  sgd_column_totals(s.part, G, t, spart, scol);
+  if (tid < t) {
+    const int c = tid;
+    const double acc = scol[c];
     int fr;
     double rr;
     if (init) {
+      const double accb = scolb[c];
       s.bn2[c] = accb;
       const int zero = accb == 0.0 ? 1 : 0;
       s.zero_rhs[c] = zero;
@@ -317,11 +361,11 @@ SgdLayout sgd_layout(const gp_ctx* ctx, int t, int batch) {
   L.b_pad = (batch + GP_ROW_ALIGN - 1) / GP_ROW_ALIGN * GP_ROW_ALIGN;
   // streaming grid: enough workgroups to fill the chip, at least about 8 rows each
   int64_t gw = (ctx->n + 7) / 8;
-  if (gw > 4 * ctx->num_cu) gw = 4 * ctx->num_cu;
+  if (gw > 2 * ctx->num_cu) gw = 2 * ctx->num_cu;
   if (gw < 1) gw = 1;
   L.GW = (int)gw;
   int64_t gb = ((int64_t)batch + 3) / 4;
-  if (gb > 2 * ctx->num_cu) gb = 2 * ctx->num_cu;
+  if (gb > ctx->num_cu) gb = ctx->num_cu;
   if (gb < 1) gb = 1;
   L.GB = (int)gb;
   const int G = L.GW > L.GB ? L.GW : L.GB;

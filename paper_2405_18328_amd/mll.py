@@ -69,8 +69,10 @@ class StepRecord:
 
 
 class MllOptimizer:
-    """Adam ascent on L(theta) with the linear solves done by gp_cg_solve (solver="cg") or
-    gp_ap_solve (solver="ap", blocks of `block` indices; iters then counts block updates).
+    """Adam ascent on L(theta) with the linear solves done by gp_cg_solve (solver="cg"),
+    gp_ap_solve (solver="ap", blocks of `block` indices; iters then counts block updates) or
+    gp_sgd_solve (solver="sgd", mini-batches of `batch` distinct rows drawn once, seeded, and reused
+    by every solve; iters counts steps, at most max_iters and at most 4096).
 
     warm=True keeps the probes Z fixed and passes the previous step's V as x0 (Section 3);
     warm=False starts every solve from zero and, if resample is given, redraws the probes
@@ -78,7 +80,8 @@ class MllOptimizer:
     """
 
     def __init__(self, X, y, Z, kind, ell0, a0, sigma0, tol, warm=True, lr=0.1, max_iters=1000,
-                 resample=None, device="cuda:0", solver="cg", block=2000):
+                 resample=None, device="cuda:0", solver="cg", block=2000, batch=1000,
+                 sgd_lr=50.0, sgd_momentum=0.9, seed=1234):
         self.dev = torch.device(device)
         self.X = torch.as_tensor(np.ascontiguousarray(X, dtype=np.float32)).to(self.dev)
         self.n, self.d = self.X.shape
@@ -94,12 +97,22 @@ class MllOptimizer:
         self.have_solution = False
         self.stream = torch.cuda.current_stream(self.dev)
         self.ctx = gp.gp_create(KIND_CODE[kind], self.n, self.d, self.X, self.stream.cuda_stream)
-        if solver not in ("cg", "ap"):
+        if solver not in ("cg", "ap", "sgd"):
             raise ValueError(f"unknown solver {solver!r}")
         self.solver = solver
         self.block = int(block)
+        self.batch = min(int(batch), self.n)
+        self.sgd_lr, self.sgd_momentum = float(sgd_lr), float(sgd_momentum)
+        if solver == "sgd":
+            # the library draws no random numbers: the mini-batch index sequences are made here
+            self.max_iters = min(self.max_iters, 4096)
+            gen = torch.Generator(device=self.dev)
+            gen.manual_seed(seed)
+            self.batches = torch.stack([torch.randperm(self.n, generator=gen, device=self.dev)[: self.batch]
+                                        for _ in range(self.max_iters)]).to(torch.int32).contiguous()
         need = (gp.gp_workspace_bytes(self.ctx, self.t) if solver == "cg"
-                else gp.gp_ap_workspace_bytes(self.ctx, self.t, self.block))
+                else gp.gp_ap_workspace_bytes(self.ctx, self.t, self.block) if solver == "ap"
+                else gp.gp_sgd_workspace_bytes(self.ctx, self.t, self.batch))
         if need == 0:
             raise ValueError("workspace size query failed (t or block out of range)")
         self.work = torch.empty(need, dtype=torch.uint8, device=self.dev)
@@ -130,9 +143,13 @@ class MllOptimizer:
         if self.solver == "cg":
             rc, iters, kmv, relres = gp.gp_cg_solve(self.ctx, self.B, self.t, x0, self.V, self.t, self.t, self.tol,
                                                     self.max_iters, self.work, self.work.numel())
-        else:
+        elif self.solver == "ap":
             rc, iters, kmv, relres, _ = gp.gp_ap_solve(self.ctx, self.B, self.t, x0, self.V, self.t, self.t, self.tol,
                                                        self.block, self.max_iters, self.work, self.work.numel())
+        else:
+            rc, iters, kmv, relres = gp.gp_sgd_solve(self.ctx, self.B, self.t, x0, self.V, self.t, self.t, self.tol,
+                                                     self.batches, self.batch, self.max_iters, self.sgd_lr,
+                                                     self.sgd_momentum, self.work, self.work.numel())
         t2 = time.perf_counter()
         g = gp.gp_mll_grad(self.ctx, self.V, self.t, self.B, self.t, self.t, self.d)
         t3 = time.perf_counter()
