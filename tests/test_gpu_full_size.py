@@ -170,3 +170,50 @@ def test_config2_full_size_alternating_projections_sampled_against_oracle():
         assert (got[outside] == 0.0).all()
     finally:
         opt.close()
+
+
+def test_config2_full_size_sgd_solver_sampled_against_oracle():
+    """n=16384, t=65, mini-batches of 1000 (Appendix B), learning rate 50, momentum 0.9, as
+    bench.py --solver sgd runs it: three warm-started optimiser steps, the true residual of the last
+    solution on sampled rows, and the first two steps from zero against the oracle (step 1 is
+    U[I1] = (lr/b) B[I1]; step 2 needs (H U1)[I2], exact rows from the oracle)."""
+    w = make("config2")
+    assert (w.n, w.d, w.s) == (16384, 26, 64)
+    lr, b = 50.0, 1000
+    opt = MllOptimizer(w.X, w.y, w.Z, w.kind, w.ell, w.a, w.sigma, w.tol, warm=True, max_iters=4096,
+                       solver="sgd", batch=b, sgd_lr=lr)
+    try:
+        recs = [opt.step() for _ in range(3)]
+        _note(f"sgd steps per optimiser step {[r.iters for r in recs]}")
+        assert all(r.rc == 0 for r in recs)
+        assert recs[-1].iters < recs[0].iters and recs[1].kmv_count == 1 and recs[0].kmv_count == 0
+        last = recs[-1]
+        ell, a, sigma = last.theta[: w.d], last.theta[w.d], last.theta[w.d + 1]
+        t = w.s + 1
+        V = opt.V.cpu().numpy().astype(np.float64)
+        B = opt.B.cpu().numpy().astype(np.float64)
+        rows = np.sort(np.random.default_rng(13).choice(w.n, size=1024, replace=False))
+        HV = orc.kmv_rows(w.X, ell, a, w.kind, V, rows, sigma=sigma)
+        res = np.linalg.norm(HV - B[rows], axis=0) * np.sqrt(w.n / rows.size)
+        rel = res / np.linalg.norm(B, axis=0)
+        _note(f"sampled true relative residual max {rel.max():.3e} (estimate passed {w.tol})")
+        assert rel.max() <= 2.0 * w.tol
+
+        batches = opt.batches.cpu().numpy()
+        I1, I2 = batches[0].astype(np.int64), batches[1].astype(np.int64)
+        assert np.unique(I1).size == b and I1.min() >= 0 and I1.max() < w.n
+        V2 = torch.zeros_like(opt.B)
+        rc, it, kmv, rr = gp.gp_sgd_solve(opt.ctx, opt.B, t, None, V2, t, t, 1e-12, opt.batches, b, 2, lr, 0.9,
+                                          opt.work, opt.work.numel())
+        assert rc == 1 and it == 2 and kmv == 0
+        U1 = np.zeros_like(B)
+        U1[I1] = (lr / b) * B[I1]
+        G2 = orc.kmv_rows(w.X, ell, a, w.kind, U1, I2, sigma=sigma) - B[I2]
+        U2 = U1 + 0.9 * U1
+        U2[I2] -= (lr / b) * G2
+        got = V2.cpu().numpy().astype(np.float64)
+        err = np.linalg.norm(got - U2, axis=0) / np.linalg.norm(U2, axis=0)
+        _note(f"two steps from zero: relative error max {err.max():.2e}")
+        assert err.max() <= 1e-4
+    finally:
+        opt.close()

@@ -593,7 +593,7 @@ def test_cg_breakdown_is_reported_not_hung():
 
 
 # ------------------------------------------------------------------ optimiser traces (Section 4, hyperparameter traces)
-@pytest.mark.parametrize("solver", ["cg", "ap"])
+@pytest.mark.parametrize("solver", ["cg", "ap", "sgd"])
 def test_optimiser_trace_tracks_the_exact_gradient_trace(solver):
     """The paper's end-to-end claim (Section 4, hyperparameter-trace figures): with warm starts and the
     solver tolerances of Appendix B the hyperparameters follow the trace obtained with exact (Cholesky)
@@ -617,7 +617,7 @@ def test_optimiser_trace_tracks_the_exact_gradient_trace(solver):
         raw0, lambda th: orc.mll_grad_hutchinson(w.X, th[:d], th[d], th[d + 1], w.kind, B), steps))
     tol = np.array([0.01] + [0.1] * s, dtype=np.float32)
     opt = MllOptimizer(w.X, w.y, w.Z, w.kind, np.ones(d), 1.0, 1.0, tol, warm=True, max_iters=100000,
-                       solver=solver, block=250)
+                       solver=solver, block=250, batch=250, sgd_lr=12.5)
     try:
         recs = [opt.step() for _ in range(steps)]
         gpu = np.array([r.theta for r in recs[1:]] + [opt.theta])     # theta after every step
