@@ -217,3 +217,75 @@ def test_config2_full_size_sgd_solver_sampled_against_oracle():
         assert err.max() <= 1e-4
     finally:
         opt.close()
+
+
+def test_config5_two_million_rows_first_steps_of_ap_and_sgd():
+    """n = 2,000,000 (1000 blocks of 2000 rows; mini-batches of 1000 rows): the first two steps of both
+    block solvers from zero, against the oracle on the few thousand rows they touch.
+    AP: the first block is argmax ||B[I,:]||, V[I1] = H[I1,I1]^-1 B[I1]; whichever block I2 != I1 comes
+    second, V[I2] = H[I2,I2]^-1 (B[I2] - H[I2,I1] V[I1]).
+    SGD: U1[I1] = (lr/b) B[I1]; U2 = U1 + rho U1 - (lr/b) (H[I2,:] U1 - B[I2]) on I2, and H[I2,:] U1
+    only involves the columns I1."""
+    w = make("config5")
+    assert w.n == 2_000_000
+    _note("inputs ready")
+    t = 5
+    Bh = np.ascontiguousarray(w.B[:, :t])
+    B = Bh.astype(np.float64)
+    dv = Dev(w.X, w.kind, w.ell, w.a, w.sigma)
+    try:
+        Bd = dv.to(Bh)
+        block = 2000
+        rc, it, kmv, rr, pk, Vd = dv.ap_solve(Bd, 1e-12, block, max_iters=2, picks=True)
+        assert rc == 1 and it == 2 and kmv == 0 and pk[0] != pk[1]
+        _note(f"AP picks {list(pk)}")
+        scores = np.add.reduceat(np.sum(B * B, axis=1), np.arange(0, w.n, block))
+        assert int(pk[0]) == int(np.argmax(scores))
+        (a0, a1), (b0, b1) = [(int(k) * block, min(w.n, (int(k) + 1) * block)) for k in pk]
+        X1, X2 = w.X[a0:a1], w.X[b0:b1]
+        d1 = orc.chol_solve(orc.coefficient_matrix(X1, w.ell, w.a, w.sigma, w.kind), B[a0:a1])
+        r2 = B[b0:b1] - orc.kernel_cross(X2, X1, w.ell, w.a, w.kind) @ d1
+        d2 = orc.chol_solve(orc.coefficient_matrix(X2, w.ell, w.a, w.sigma, w.kind), r2)
+        got = Vd.cpu().numpy().astype(np.float64)
+        e1 = np.linalg.norm(got[a0:a1] - d1, axis=0) / np.linalg.norm(d1, axis=0)
+        e2 = np.linalg.norm(got[b0:b1] - d2, axis=0) / np.linalg.norm(d2, axis=0)
+        # The second block's right-hand side B[I2] - H[I2,I1] d1 carries the product's rounding, which is
+        # relative to the terms summed, sum_j |k_ij| |d1_j| (d1 = H11^-1 B1 is large and oscillating on this
+        # ill-conditioned system, so the sum cancels heavily), and the block solve amplifies it.  Judge the
+        # step in residual space against that scale: the same 1e-5 normwise bar as for K V.
+        H22 = orc.coefficient_matrix(X2, w.ell, w.a, w.sigma, w.kind)
+        scale = np.linalg.norm(np.abs(orc.kernel_cross(X2, X1, w.ell, w.a, w.kind)) @ np.abs(d1), axis=0)
+        back = np.linalg.norm(H22 @ got[b0:b1] - r2, axis=0) / scale
+        _note(f"AP block solves: relative error {e1.max():.2e}, {e2.max():.2e}; second block's residual against "
+              f"the summed terms {back.max():.2e}")
+        assert e1.max() <= 2e-4 and back.max() <= KMV_TOL
+        got[a0:a1] = 0.0
+        got[b0:b1] = 0.0
+        assert not got.any()
+        del Vd, got
+        dv._apwork = None
+        torch.cuda.empty_cache()
+
+        lr, b = 2.0, 1000
+        rng = np.random.default_rng(21)
+        bt = np.stack([rng.permutation(w.n)[:b] for _ in range(2)]).astype(np.int32)
+        bt[0, 0], bt[1, 0] = w.n - 1, 0
+        assert np.unique(bt[0]).size == b and np.unique(bt[1]).size == b
+        rc, it, kmv, rr, Ud = dv.sgd_solve(Bd, 1e-12, bt, lr)
+        assert rc == 1 and it == 2 and kmv == 0
+        I1, I2 = bt[0].astype(np.int64), bt[1].astype(np.int64)
+        U1 = np.zeros((w.n, t))
+        U1[I1] = (lr / b) * B[I1]
+        H21 = orc.kernel_cross(w.X[I2], w.X[I1], w.ell, w.a, w.kind)
+        G2 = H21 @ U1[I1] + (w.sigma ** 2) * U1[I2] - B[I2]
+        U2 = 1.9 * U1
+        U2[I2] -= (lr / b) * G2
+        got = Ud.cpu().numpy().astype(np.float64)
+        touched = np.union1d(I1, I2)
+        err = np.linalg.norm(got[touched] - U2[touched], axis=0) / np.linalg.norm(U2[touched], axis=0)
+        _note(f"SGD two steps: relative error {err.max():.2e}")
+        assert err.max() <= 1e-4
+        got[touched] = 0.0
+        assert not got.any()
+    finally:
+        dv.close()
