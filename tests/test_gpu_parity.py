@@ -636,3 +636,41 @@ def test_optimiser_trace_tracks_the_exact_gradient_trace(solver):
         assert np.mean([r.iters for r in recs[5:]]) < recs[0].iters
     finally:
         opt.close()
+
+
+def test_probe_laws_gaussian_and_rademacher_give_unbiased_gradients():
+    """Section 2.1 allows Gaussian and Rademacher probes (any law with E[z z^T] = I); the laws differ in the
+    fourth moment (3 against 1), which is what enters the spread of the trace estimate: z^T A z has
+    variance 2 ||A||_F^2 for Gaussian probes and 2 (||A||_F^2 - sum_i A_ii^2) for Rademacher probes, so
+    Rademacher is never worse and is much better where H^-1 dH/dtheta_k has a heavy diagonal (the signal
+    and noise scales).  Measured on the GPU path: 40 draws of s = 8 probes per law, tight solves, gradient
+    against the oracle's exact (Cholesky) gradient: both unbiased, spread ratio as the formula says."""
+    from paper_2405_18328_amd.inputs import draw_probes
+    w = make("config1", n=800)
+    d, s, draws = w.d, 8, 40
+    y = np.asarray(w.y, dtype=np.float64)
+    exact = orc.mll_grad_exact(w.X, y, w.ell, w.a, w.sigma, w.kind)
+    dv = _dev(w)
+    try:
+        stats = {}
+        for law in ("gaussian", "rademacher"):
+            rng = np.random.default_rng(77)
+            errs = []
+            for _ in range(draws):
+                Z = draw_probes(rng, w.n, s, law)
+                B = np.concatenate([np.asarray(w.y, dtype=np.float32)[:, None], Z.astype(np.float32)], axis=1)
+                rc, _, _, _, Vd = dv.solve(B, 1e-5)
+                assert rc == 0
+                errs.append(dv.grad(Vd, dv.to(B)) - exact)
+            errs = np.array(errs)
+            stats[law] = (errs.mean(axis=0), errs.std(axis=0, ddof=1))
+            bias, sd = stats[law]
+            # unbiased: the mean error over the draws is within 4 standard errors, component by component
+            assert (np.abs(bias) <= 4.0 * sd / np.sqrt(draws) + 1e-3 * np.abs(exact)).all(), (law, bias, sd)
+        ratio = stats["rademacher"][1] / stats["gaussian"][1]
+        print(f"[probes] spread ratio rademacher / gaussian per component: {np.round(ratio, 2)}", flush=True)
+        # 40 draws fix a standard deviation to about 11 %: never worse beyond that noise, and clearly
+        # better on the two scale components (observed 0.09 and 0.44)
+        assert (ratio < 1.35).all() and (ratio[d:] < 0.7).all()
+    finally:
+        dv.close()
