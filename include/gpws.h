@@ -4,9 +4,11 @@
  *
  * The path (paper Section 2.1): a first-order optimiser needs estimates of the
  * gradient of the log marginal likelihood; the estimate needs
- * H^{-1}[y, z_1..z_s] for H = k(x,x) + sigma^2 I; conjugate gradients obtains it
- * from products H*V that are evaluated matrix-free (K is never stored).  The
- * warm start (Section 3) passes the previous outer step's solution as x0.
+ * H^{-1}[y, z_1..z_s] for H = k(x,x) + sigma^2 I; an iterative solver (conjugate
+ * gradients, alternating projections or stochastic gradient descent, the three
+ * the paper runs) obtains it from products with H or with blocks of its rows or
+ * columns, all evaluated matrix-free (K is never stored).  The warm start
+ * (Section 3) passes the previous outer step's solution as x0.
  *
  * Conventions
  *   - Every pointer named d* is DEVICE memory owned by the caller; every
@@ -16,7 +18,7 @@
  *     p[i*ld + c], ld >= t.  Column 0 of a right-hand-side block is y, columns
  *     1..s are the probes z_j; t = s + 1.
  *   - All work is enqueued on the HIP stream given to gp_create.  Calls that
- *     return host results (gp_cg_solve, gp_mll_grad) synchronise that stream
+ *     return host results (the solvers, gp_mll_grad) synchronise that stream
  *     before returning; gp_set_theta waits for earlier work on the stream and
  *     may synchronise once more (see there); gp_kmv is asynchronous.
  *   - theta = (ell_1..ell_d, a, sigma): lengthscales, signal scale (amplitude,
