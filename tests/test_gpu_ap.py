@@ -263,3 +263,39 @@ def test_ap_argument_errors():
         assert rc == 0 and (rr < 0.05).all()
     finally:
         dv.close()
+
+
+def test_ap_many_columns_and_padded_leading_dimensions():
+    """t = 300 (more than one pass of 256 columns in the block solve and of the streaming kernels) with
+    leading dimensions larger than t for B, x0 and V; the padding columns of V must not be written."""
+    import torch
+    w = make("config3", n=420, s=4)
+    a, sigma = 1.0, 0.5
+    t, block = 300, 128
+    rng = np.random.default_rng(3)
+    B = rng.standard_normal((w.n, t))
+    X0 = 0.2 * rng.standard_normal((w.n, t))
+    H = orc.coefficient_matrix(w.X, w.ell, a, sigma, w.kind)
+    dv = Dev(w.X, w.kind, w.ell, a, sigma)
+    gp = dv.gp
+    try:
+        ldb, ldv = t + 5, t + 9
+        Bd = torch.full((w.n, ldb), 7.0, device=dv.dev)
+        Bd[:, :t] = dv.to(B)
+        Vd = torch.full((w.n, ldv), -777.0, device=dv.dev)
+        Vd[:, :t] = dv.to(X0)
+        need = gp.gp_ap_workspace_bytes(dv.ctx, t, block)
+        wk = torch.empty(need, dtype=torch.uint8, device=dv.dev)
+        Bf, X0f = B.astype(np.float32).astype(np.float64), X0.astype(np.float32).astype(np.float64)
+        for k in (1, 4):
+            Vd[:, :t] = dv.to(X0)
+            Vo, _, rro, pko = orc.ap_batched(H, Bf, X0=X0f, tol=1e-12, block=block, max_iters=k)
+            rc, it, kmv, rr, pk = gp.gp_ap_solve(dv.ctx, Bd, ldb, Vd, Vd, ldv, t, 1e-12, block, k, wk, wk.numel(),
+                                                 want_picks=True)
+            assert rc == 1 and it == k and kmv == 1 and list(pk) == pko
+            got = Vd.cpu().numpy()
+            assert (got[:, t:] == -777.0).all()
+            assert (_colrel(got[:, :t], Vo) <= STEP_TOL).all()
+            np.testing.assert_allclose(rr, rro, rtol=2e-3)
+    finally:
+        dv.close()

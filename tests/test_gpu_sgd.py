@@ -211,3 +211,38 @@ def test_sgd_argument_errors_and_divergence_report():
         assert rc in (0, 1) and np.isfinite(rr).all()
     finally:
         dv.close()
+
+
+def test_sgd_many_columns_and_padded_leading_dimensions():
+    """t = 300 (more than one pass of 256 columns in the streaming kernels) with leading dimensions larger
+    than t for B, x0 and V; the padding columns of V must not be written."""
+    w = make("config3", n=420, s=4)
+    a, sigma = 1.0, 0.5
+    t, b = 300, 96
+    rng = np.random.default_rng(3)
+    B = rng.standard_normal((w.n, t)).astype(np.float32)
+    X0 = (0.2 * rng.standard_normal((w.n, t))).astype(np.float32)
+    H = orc.coefficient_matrix(w.X, w.ell, a, sigma, w.kind)
+    bt = _batches(w.n, b, 12, 2)
+    lr = 0.08 * b / (a * a + sigma * sigma)
+    dv = Dev(w.X, w.kind, w.ell, a, sigma)
+    gp = dv.gp
+    try:
+        ldb, ldv = t + 5, t + 9
+        Bd = torch.full((w.n, ldb), 7.0, device=dv.dev)
+        Bd[:, :t] = dv.to(B)
+        Vd = torch.full((w.n, ldv), -777.0, device=dv.dev)
+        Vd[:, :t] = dv.to(X0)
+        btd = torch.from_numpy(bt).to(dv.dev)
+        need = gp.gp_sgd_workspace_bytes(dv.ctx, t, b)
+        wk = torch.empty(need, dtype=torch.uint8, device=dv.dev)
+        Uo, _, rro = orc.sgd_batched(H, B.astype(np.float64), list(bt), X0=X0.astype(np.float64), tol=1e-12, lr=lr,
+                                     momentum=0.9)
+        rc, it, kmv, rr = gp.gp_sgd_solve(dv.ctx, Bd, ldb, Vd, Vd, ldv, t, 1e-12, btd, b, 12, lr, 0.9, wk, wk.numel())
+        assert rc == 1 and it == 12 and kmv == 1
+        got = Vd.cpu().numpy()
+        assert (got[:, t:] == -777.0).all()
+        assert (_colrel(got[:, :t], Uo) <= 1e-4).all()
+        np.testing.assert_allclose(rr, rro, rtol=1e-3)
+    finally:
+        dv.close()
