@@ -97,7 +97,10 @@ def main():
                          "alternating projections (iterations are block updates, a product is H[:, I] d) or "
                          "stochastic gradient descent (iterations are mini-batch steps, a product is H[I, :] U)")
     ap.add_argument("--batch", type=int, default=1000, help="mini-batch size of --solver sgd (the paper's is 1000)")
-    ap.add_argument("--lr", type=float, default=50.0, help="learning rate of --solver sgd (step on a sampled row = lr / batch)")
+    ap.add_argument("--lr", type=float, default=None,
+                    help="learning rate of --solver sgd (step on a sampled row = lr / batch); default per workload: "
+                         "50 for configs 1-2, 5 for config 3, 0.5 for configs 4-5 (the largest of a coarse grid that "
+                         "stays stable, as the paper chose its rates per dataset)")
     ap.add_argument("--block", type=int, default=2000, help="block size of --solver ap (the paper's is 2000)")
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
                     help="also run three plain device copies of MIB MiB (reads MIB, writes MIB): the known-size "
@@ -114,6 +117,8 @@ def main():
     from paper_2405_18328_amd.mll import MllOptimizer
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.lr is None:
+        args.lr = {"config1": 50.0, "config2": 50.0, "config3": 5.0, "config4": 0.5, "config5": 0.5}[args.workload]
     big = args.workload in ("config3", "config4", "config5")
     steps = args.steps if args.steps is not None else (2 if big else 20)
     warmup = args.warmup if args.warmup is not None else (1 if big else 5)
