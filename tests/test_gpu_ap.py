@@ -299,3 +299,40 @@ def test_ap_many_columns_and_padded_leading_dimensions():
             np.testing.assert_allclose(rr, rro, rtol=2e-3)
     finally:
         dv.close()
+
+
+def test_ap_random_small_shapes():
+    """Twelve seeded combinations of n, d, t, block size and kernel (odd sizes, blocks that cut chunks of 32,
+    a last block of a single row, t = 1): three steps against the oracle."""
+    rng = np.random.default_rng(2024)
+    for case in range(12):
+        n = int(rng.integers(33, 700))
+        d = int(rng.integers(1, 20))
+        t = int(rng.integers(1, 40))
+        block = int(rng.integers(1, 300)) if case else n - 1          # case 0: last block is one row
+        kind = "se" if case % 2 else "matern32"
+        X = rng.standard_normal((n, d)).astype(np.float32)
+        ell = rng.uniform(0.8, 2.5, size=d) * np.sqrt(d)
+        a, sigma = float(rng.uniform(0.5, 1.5)), float(rng.uniform(0.3, 1.0))
+        B = rng.standard_normal((n, t)).astype(np.float32)
+        print(f"[ap-shape] case {case}: n={n} d={d} t={t} block={block} {kind}", flush=True)
+        H = orc.coefficient_matrix(X, ell, a, sigma, kind)
+        Bf = B.astype(np.float64)
+        dv = Dev(X, kind, ell, a, sigma)
+        try:
+            k = 3
+            Vo, ito, rro, pko = orc.ap_batched(H, Bf, tol=1e-12, block=block, max_iters=k)
+            Vs, safe = np.zeros_like(Bf), True
+            for _ in range(ito):
+                safe = safe and _margin_ok(H, Bf, Vs, block, np.ones(t, bool))
+                Vs, _, _, _ = orc.ap_batched(H, Bf, X0=Vs, tol=1e-12, block=block, max_iters=1)
+            # a single block solves the system in one step: fp64 then meets even this tolerance and stops,
+            # fp32 cannot, so the library is held to the oracle's number of steps
+            rc, it, _, rr, pk, Vd = dv.ap_solve(B, 1e-12, block, max_iters=ito, picks=True)
+            assert it == ito
+            if safe:
+                assert list(pk) == pko
+                assert (_colrel(Vd.cpu().numpy(), Vo) <= STEP_TOL).all(), case
+                np.testing.assert_allclose(rr, rro, rtol=2e-3, atol=2e-5)   # a single-block solve leaves an fp32 rounding-level residual
+        finally:
+            dv.close()

@@ -246,3 +246,32 @@ def test_sgd_many_columns_and_padded_leading_dimensions():
         np.testing.assert_allclose(rr, rro, rtol=1e-3)
     finally:
         dv.close()
+
+
+def test_sgd_random_small_shapes():
+    """Twelve seeded combinations of n, d, t, batch size and kernel (odd sizes, t = 1, batch = n): ten
+    steps against the oracle with the same mini-batches."""
+    rng = np.random.default_rng(2025)
+    for case in range(12):
+        n = int(rng.integers(33, 700))
+        d = int(rng.integers(1, 20))
+        t = int(rng.integers(1, 40))
+        b = int(rng.integers(1, n + 1)) if case else n
+        kind = "se" if case % 2 else "matern32"
+        X = rng.standard_normal((n, d)).astype(np.float32)
+        ell = rng.uniform(0.8, 2.5, size=d) * np.sqrt(d)
+        a, sigma = float(rng.uniform(0.5, 1.5)), float(rng.uniform(0.3, 1.0))
+        B = rng.standard_normal((n, t)).astype(np.float32)
+        print(f"[sgd-shape] case {case}: n={n} d={d} t={t} batch={b} {kind}", flush=True)
+        H = orc.coefficient_matrix(X, ell, a, sigma, kind)
+        lr = 0.5 * b / np.linalg.eigvalsh(H)[-1] / 10.0        # stable for any batch: the largest eigenvalue bounds every block's
+        bt = _batches(n, b, 10, case)
+        dv = Dev(X, kind, ell, a, sigma)
+        try:
+            Uo, ito, rro = orc.sgd_batched(H, B.astype(np.float64), list(bt), tol=1e-12, lr=lr, momentum=0.9)
+            rc, it, _, rr, Vd = dv.sgd_solve(B, 1e-12, bt, lr)
+            assert rc == 1 and it == ito == 10
+            assert (_colrel(Vd.cpu().numpy(), Uo) <= 1e-4).all(), case
+            np.testing.assert_allclose(rr, rro, rtol=1e-3)
+        finally:
+            dv.close()
