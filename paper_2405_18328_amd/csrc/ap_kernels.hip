@@ -171,6 +171,7 @@ __global__ __launch_bounds__(64) void ap_chol_diag_kernel(fac_t* __restrict__ A,
                                                           int* __restrict__ breakdown) {
   __shared__ fac_t T[TS][TS + 1];
   __shared__ fac_t Xi[TS][TS + 1];
+  __shared__ fac_t rdiag[TS];          // 1 / L[c][c]
   const int64_t tile_off = (int64_t)blockIdx.x * BP * BP + (int64_t)k * TS * BP + k * TS;
   fac_t* Ab = A + tile_off;
   fac_t* Xb = X + tile_off;
@@ -186,12 +187,20 @@ __global__ __launch_bounds__(64) void ap_chol_diag_kernel(fac_t* __restrict__ A,
   __syncthreads();
   bool any_bad = false;
   for (int c = 0; c < TS; ++c) {
-    const fac_t piv = T[c][c];
-    const bool bad = !(piv > 0.0);          // also catches NaN
+    const fac_t piv0 = T[c][c];
+    const bool bad = !(piv0 > 0.0) || !(piv0 < 1.0e300);   // also catches NaN
     any_bad = any_bad || bad;
-    const fac_t dg = bad ? 1.0 : sqrt(piv);
-    const fac_t lc = lane > c ? T[lane][c] / dg : (lane == c ? dg : 0.0);   // column c of L, this lane's row
+    const fac_t piv = bad ? 1.0 : piv0;
+    // 1 / sqrt(piv) from the single-precision estimate and three Newton steps (each squares the relative
+    // error: 2^-22, 2^-43, below 2^-53): a dozen dependent operations instead of a correctly rounded
+    // square root followed by a division per lane; this chain is the critical path of every column step
+    fac_t rinv = (fac_t)__builtin_amdgcn_rsqf((float)piv);
+#pragma unroll
+    for (int it = 0; it < 3; ++it) rinv = rinv * fma(-0.5 * piv, rinv * rinv, 1.5);
+    const fac_t dg = piv * rinv;
+    const fac_t lc = lane > c ? T[lane][c] * rinv : (lane == c ? dg : 0.0);   // column c of L, this lane's row
     T[lane][c] = lc;
+    if (lane == c) rdiag[c] = rinv;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -214,6 +223,7 @@ __global__ __launch_bounds__(64) void ap_chol_diag_kernel(fac_t* __restrict__ A,
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
   if (any_bad && lane == 0) *breakdown = 1;
+  __syncthreads();
   // column `lane` of L^-1: x_i = (delta_i,lane - sum_{m < i} L[i][m] x_m) / L[i][i]; x_m = 0 for m < lane
   for (int i = 0; i < TS; ++i) {
     fac_t s0 = lane == i ? 1.0 : 0.0, s1 = 0.0;
@@ -224,7 +234,7 @@ __global__ __launch_bounds__(64) void ap_chol_diag_kernel(fac_t* __restrict__ A,
       s1 = fma(-T[i][m + 1], Xi[m + 1][lane], s1);
     }
     if (m < i) s0 = fma(-T[i][m], Xi[m][lane], s0);
-    Xi[i][lane] = (s0 + s1) / T[i][i];
+    Xi[i][lane] = (s0 + s1) * rdiag[i];
   }
   __syncthreads();
   for (int i = 0; i < TS; ++i) {
