@@ -674,3 +674,32 @@ def test_probe_laws_gaussian_and_rademacher_give_unbiased_gradients():
         assert (ratio < 1.35).all() and (ratio[d:] < 0.7).all()
     finally:
         dv.close()
+
+
+def test_cg_large_n_product_not_split_over_columns():
+    """n = 70000: enough row blocks that the product inside the solver is not split over column ranges
+    (the solver then reads H P straight from the product's output instead of summing partials).  Cold
+    and warm solve, true residual on sampled rows from the oracle."""
+    w = make("config3", n=70000, s=2)
+    a, sigma = 1.0, 1.0
+    dv = Dev(w.X, w.kind, w.ell, a, sigma)
+    try:
+        tol = 1e-3
+        rc, it, kmv, rr, Vd = dv.solve(w.B, tol, max_iters=500)
+        assert rc == 0 and kmv == it and (rr < tol).all()
+        rows = np.sort(np.random.default_rng(3).choice(w.n, size=256, replace=False))
+        B = np.asarray(w.B, dtype=np.float64)
+
+        def sampled_rel(V):
+            HV = orc.kmv_rows(w.X, w.ell, a, w.kind, V.astype(np.float64), rows, sigma=sigma)
+            return np.linalg.norm(HV - B[rows], axis=0) * np.sqrt(w.n / rows.size) / np.linalg.norm(B, axis=0)
+
+        rel = sampled_rel(Vd.cpu().numpy())
+        print(f"[large-n cg] {it} iterations, sampled true relative residual {rel.max():.2e}", flush=True)
+        assert rel.max() <= 2.0 * tol
+        # warm start from the solution at slightly different hyperparameters: one extra product, fewer iterations
+        dv.set_theta(np.asarray(w.ell) * 1.02, a, sigma)
+        rc2, it2, kmv2, rr2, Vd2 = dv.solve(w.B, tol, max_iters=500, X0=Vd.clone())
+        assert rc2 == 0 and kmv2 == it2 + 1 and it2 < it
+    finally:
+        dv.close()
