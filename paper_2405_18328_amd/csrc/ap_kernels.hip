@@ -60,50 +60,46 @@ struct ApDev {
 // B[l / 16][l % 16]; result register v of lane l: D[4 v + l / 16][l % 16]).
 typedef double d4 __attribute__((ext_vector_type(4)));
 
+constexpr int KD = 32;   // contraction depth held in LDS at a time: two 32 x 64 operand slabs = 33 KB per
+                         // workgroup, so that four workgroups share a compute unit and their loads, LDS
+                         // traffic and matrix-core work overlap
+
 struct Tile {
-  fac_t v[TS][TS + 1];
+  fac_t v[KD][TS + 1];
 };
 
 struct Acc {
   d4 b[4];   // column block cb: rows 16 w + 4 v + l / 16, column 16 cb + l % 16
 };
 
-// source element (row, col) = src[row * ld + col].  by_col = false: the source row is the contraction
-// index, T[row][col] = src(row, col); by_col = true: the source column is, T[col][row] = src(row, col).
-// All global loads of a tile (16 per thread) are issued before the first LDS store, so that their
-// latencies overlap.
-struct TileRegs {
-  fac_t v[16];
+// One 64 x 64 operand tile in memory: element (row, col) = base[row * ld + col].  by_col = false: the rows
+// are the contraction index (slab h = rows 32 h .. 32 h + 31, T[row][col]); by_col = true: the columns
+// are (slab h = columns 32 h .., stored transposed, T[col][row]).
+struct Operand {
+  const fac_t* base;
+  int64_t ld;
+  bool by_col;
 };
-__device__ __forceinline__ void fetch_tile(TileRegs& g, const fac_t* __restrict__ src, int64_t ld) {
+
+struct SlabRegs {
+  fac_t v[8];
+};
+// all 8 loads of a thread are issued before anything waits on them
+__device__ __forceinline__ void fetch_slab(SlabRegs& g, const Operand& o, int h) {
 #pragma unroll
-  for (int q = 0; q < 16; ++q) {
+  for (int q = 0; q < 8; ++q) {
     const int e = threadIdx.x + 256 * q;
-    g.v[q] = src[(int64_t)(e / TS) * ld + (e % TS)];
+    g.v[q] = o.by_col ? o.base[(int64_t)(e / KD) * o.ld + KD * h + (e % KD)]
+                      : o.base[(int64_t)(KD * h + e / TS) * o.ld + (e % TS)];
   }
 }
-__device__ __forceinline__ void stash_tile(Tile& T, const TileRegs& g, bool by_col) {
+__device__ __forceinline__ void stash_slab(Tile& T, const SlabRegs& g, bool by_col) {
 #pragma unroll
-  for (int q = 0; q < 16; ++q) {
+  for (int q = 0; q < 8; ++q) {
     const int e = threadIdx.x + 256 * q;
-    const int rr = e / TS, cc = e % TS;
-    if (by_col) T.v[cc][rr] = g.v[q];
-    else T.v[rr][cc] = g.v[q];
+    if (by_col) T.v[e % KD][e / KD] = g.v[q];
+    else T.v[e / TS][e % TS] = g.v[q];
   }
-}
-__device__ __forceinline__ void load_tile(Tile& T, const fac_t* __restrict__ src, int64_t ld, bool by_col) {
-  TileRegs g;
-  fetch_tile(g, src, ld);
-  stash_tile(T, g, by_col);
-}
-// both operand tiles of a product: 32 loads in flight, then the stores
-__device__ __forceinline__ void load_tiles(Tile& TA, const fac_t* __restrict__ srcA, int64_t ldA, bool by_colA,
-                                           Tile& TB, const fac_t* __restrict__ srcB, int64_t ldB, bool by_colB) {
-  TileRegs ga, gb;
-  fetch_tile(ga, srcA, ldA);
-  fetch_tile(gb, srcB, ldB);
-  stash_tile(TA, ga, by_colA);
-  stash_tile(TB, gb, by_colB);
 }
 
 __device__ __forceinline__ void clear_acc(Acc& acc) {
@@ -111,15 +107,42 @@ __device__ __forceinline__ void clear_acc(Acc& acc) {
   for (int cb = 0; cb < 4; ++cb) acc.b[cb] = d4{0.0, 0.0, 0.0, 0.0};
 }
 
-__device__ __forceinline__ void mac_tile(const Tile& TA, const Tile& TB, Acc& acc) {
+__device__ __forceinline__ void mac_slab(const Tile& TA, const Tile& TB, Acc& acc) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int lo = lane & 15, hi = lane >> 4;
 #pragma unroll 4
-  for (int m0 = 0; m0 < TS; m0 += 4) {
+  for (int m0 = 0; m0 < KD; m0 += 4) {
     const fac_t a = TA.v[m0 + hi][16 * w + lo];
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb)
       acc.b[cb] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, TB.v[m0 + hi][16 * cb + lo], acc.b[cb], 0, 0, 0);
+  }
+}
+
+// acc += sum over the tiles m = m_lo .. m_hi of A_m B_m, where opA(m) / opB(m) name the two 64 x 64
+// operand tiles of step m.  Slabs of 32 are staged through LDS; the next slab's loads are in flight
+// while the matrix cores work on the current one.
+template <typename FA, typename FB>
+__device__ __forceinline__ void tile_chain(Tile& TA, Tile& TB, Acc& acc, int m_lo, int m_hi, FA opA, FB opB) {
+  if (m_lo > m_hi) return;
+  const int steps = 2 * (m_hi - m_lo + 1);
+  SlabRegs ga, gb;
+  Operand oa = opA(m_lo), ob = opB(m_lo);
+  fetch_slab(ga, oa, 0);
+  fetch_slab(gb, ob, 0);
+  for (int q = 0; q < steps; ++q) {
+    stash_slab(TA, ga, oa.by_col);
+    stash_slab(TB, gb, ob.by_col);
+    __syncthreads();
+    if (q + 1 < steps) {
+      const int m = m_lo + (q + 1) / 2;
+      oa = opA(m);
+      ob = opB(m);
+      fetch_slab(ga, oa, (q + 1) & 1);
+      fetch_slab(gb, ob, (q + 1) & 1);
+    }
+    mac_slab(TA, TB, acc);
+    __syncthreads();
   }
 }
 
@@ -252,12 +275,12 @@ __global__ __launch_bounds__(256) void ap_chol_panel_kernel(fac_t* __restrict__ 
   const int it = k + 1 + blockIdx.x;
   fac_t* Aik = A + (int64_t)blockIdx.y * BP * BP + (int64_t)it * TS * BP + k * TS;
   const fac_t* DIb = DI + (int64_t)blockIdx.y * BP * TS + (int64_t)k * TS * TS;
-  load_tiles(TA, Aik, BP, true,     // A_ik(r, m)
-             TB, DIb, TS, true);    // L_kk^-1(c, m)
-  __syncthreads();
   Acc acc;
   clear_acc(acc);
-  mac_tile(TA, TB, acc);
+  const int64_t ldA = BP;
+  tile_chain(TA, TB, acc, 0, 0,
+             [=](int) { return Operand{Aik, ldA, true}; },      // A_ik(r, m)
+             [=](int) { return Operand{DIb, TS, true}; });      // L_kk^-1(c, m)
 #pragma unroll
   for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
@@ -270,12 +293,14 @@ __global__ __launch_bounds__(256) void ap_chol_update_kernel(fac_t* __restrict__
   if (blockIdx.x > blockIdx.y) return;
   const int I = k + 1 + blockIdx.y, J = k + 1 + blockIdx.x;
   fac_t* Ab = A + (int64_t)blockIdx.z * BP * BP;
-  load_tiles(TA, Ab + (int64_t)I * TS * BP + k * TS, BP, true,    // L_Ik(r, m)
-             TB, Ab + (int64_t)J * TS * BP + k * TS, BP, true);   // L_Jk(c, m)
-  __syncthreads();
   Acc acc;
   clear_acc(acc);
-  mac_tile(TA, TB, acc);
+  const fac_t* LI = Ab + (int64_t)I * TS * BP + k * TS;
+  const fac_t* LJ = Ab + (int64_t)J * TS * BP + k * TS;
+  const int64_t ldA = BP;
+  tile_chain(TA, TB, acc, 0, 0,
+             [=](int) { return Operand{LI, ldA, true}; },       // L_Ik(r, m)
+             [=](int) { return Operand{LJ, ldA, true}; });      // L_Jk(c, m)
   fac_t* Aij = Ab + (int64_t)I * TS * BP + J * TS;
 #pragma unroll
   for (int cb = 0; cb < 4; ++cb)
@@ -317,22 +342,13 @@ __global__ __launch_bounds__(256) void ap_trinv_merge_kernel(const fac_t* __rest
   }
   Acc acc;
   clear_acc(acc);
-  // the next pair of tiles is fetched into registers while the matrix cores work on the current one
-  TileRegs ga, gb;
-  if (mlo <= mhi) {
-    fetch_tile(ga, P + (int64_t)ti * TS * BP + mlo * TS, BP);   // P(r, q): the source column is the contraction index
-    fetch_tile(gb, Q + (int64_t)mlo * TS * BP + tj * TS, BP);   // Q(q, c)
-  }
-  for (int m = mlo; m <= mhi; ++m) {
-    stash_tile(TA, ga, true);
-    stash_tile(TB, gb, false);
-    __syncthreads();
-    if (m < mhi) {
-      fetch_tile(ga, P + (int64_t)ti * TS * BP + (m + 1) * TS, BP);
-      fetch_tile(gb, Q + (int64_t)(m + 1) * TS * BP + tj * TS, BP);
-    }
-    mac_tile(TA, TB, acc);
-    __syncthreads();
+  {
+    const fac_t* Pt = P + (int64_t)ti * TS * BP;
+    const fac_t* Qt = Q + (int64_t)tj * TS;
+    const int64_t ld = BP;
+    tile_chain(TA, TB, acc, mlo, mhi,
+               [=](int m) { return Operand{Pt + (int64_t)m * TS, ld, true}; },          // P(r, q): the source column is the contraction index
+               [=](int m) { return Operand{Qt + (int64_t)m * TS * ld, ld, false}; });   // Q(q, c)
   }
   fac_t* out = (step == 0 ? T : X) + zo + (int64_t)(o2 + ti) * TS * BP + (o1 + tj) * TS;
   const fac_t sign = step == 0 ? 1.0 : -1.0;
@@ -350,19 +366,13 @@ __global__ __launch_bounds__(256) void ap_lauum_kernel(const fac_t* __restrict__
   const fac_t* Wb = W + (int64_t)blockIdx.z * BP * BP;
   Acc acc;
   clear_acc(acc);
-  TileRegs ga, gb;
-  fetch_tile(ga, Wb + (int64_t)ti * TS * BP + ti * TS, BP);   // X_m,ti(q, r)
-  fetch_tile(gb, Wb + (int64_t)ti * TS * BP + tj * TS, BP);   // X_m,tj(q, c)
-  for (int m = ti; m < nt; ++m) {
-    stash_tile(TA, ga, false);
-    stash_tile(TB, gb, false);
-    __syncthreads();
-    if (m + 1 < nt) {      // fetched while the matrix cores work on tile m
-      fetch_tile(ga, Wb + (int64_t)(m + 1) * TS * BP + ti * TS, BP);
-      fetch_tile(gb, Wb + (int64_t)(m + 1) * TS * BP + tj * TS, BP);
-    }
-    mac_tile(TA, TB, acc);
-    __syncthreads();
+  {
+    const fac_t* Wi = Wb + (int64_t)ti * TS;
+    const fac_t* Wj = Wb + (int64_t)tj * TS;
+    const int64_t ld = BP;
+    tile_chain(TA, TB, acc, ti, nt - 1,
+               [=](int m) { return Operand{Wi + (int64_t)m * TS * ld, ld, false}; },    // X_m,ti(q, r)
+               [=](int m) { return Operand{Wj + (int64_t)m * TS * ld, ld, false}; });   // X_m,tj(q, c)
   }
   float* Hb = Hinv + (int64_t)blockIdx.z * BP * BP;
 #pragma unroll
