@@ -183,88 +183,175 @@ __global__ __launch_bounds__(256) void ap_build_kernel(const float* __restrict__
   A[(int64_t)blockIdx.z * BP * BP + (int64_t)i * BP + j] = v;
 }
 
+// value of v in lane `src` (wave-uniform), for a double
+__device__ __forceinline__ double lane_bcast(double v, int src) {
+  const unsigned long long u = __builtin_bit_cast(unsigned long long, v);
+  const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)u, src);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(u >> 32), src);
+  return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+}
+
+// 16 x 16 block product on the matrix cores with both operands row-major in LDS (row stride TS + 1):
+// acc += P[0..15][0..15] Q[0..15][0..15], P and Q pointing at the blocks' first elements.
+__device__ __forceinline__ d4 block16_mac(const fac_t* P, const fac_t* Q, d4 acc) {
+  const int lane = threadIdx.x & 63, lo = lane & 15, hi = lane >> 4;
+#pragma unroll
+  for (int s4 = 0; s4 < 16; s4 += 4)
+    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(P[lo * (TS + 1) + s4 + hi], Q[(s4 + hi) * (TS + 1) + lo], acc, 0, 0, 0);
+  return acc;
+}
+// the same with the second operand transposed: acc += P Q^T
+__device__ __forceinline__ d4 block16_mac_nt(const fac_t* P, const fac_t* Q, d4 acc) {
+  const int lane = threadIdx.x & 63, lo = lane & 15, hi = lane >> 4;
+#pragma unroll
+  for (int s4 = 0; s4 < 16; s4 += 4)
+    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(P[lo * (TS + 1) + s4 + hi], Q[lo * (TS + 1) + s4 + hi], acc, 0, 0, 0);
+  return acc;
+}
+
 // diagonal tile k of every block in the batch: L_kk in place (upper part zeroed); its inverse goes to
-// DI and to the diagonal tile of X (the matrix that becomes L^-1).  One wave per tile, so that no
-// barrier is needed between the 64 column steps: lane i owns row i of the tile in LDS, the rank-1
-// update of the right-looking factorisation reads the other rows' column entries at wave-uniform
-// addresses, and LDS operations of one wave complete in order.  The inverse is then formed column by
-// column (lane j owns column j) by forward substitution.
-__global__ __launch_bounds__(64) void ap_chol_diag_kernel(fac_t* __restrict__ A, int BP, int k,
-                                                          fac_t* __restrict__ DI, fac_t* __restrict__ X,
-                                                          int* __restrict__ breakdown) {
-  __shared__ fac_t T[TS][TS + 1];
-  __shared__ fac_t Xi[TS][TS + 1];
-  __shared__ fac_t rdiag[TS];          // 1 / L[c][c]
+// DI and to the diagonal tile of X (the matrix that becomes L^-1).  One workgroup of four waves per
+// tile, the tile in LDS, worked in panels of 16 columns:
+//   - a panel is factorised by wave 0 with lane = row and the row's 16 panel entries in registers: the
+//     64 dependent column steps of the tile (pivot, reciprocal square root, scale, rank-1 update of the
+//     panel's remaining columns) touch no memory, the other rows' entries come by lane broadcast;
+//   - the rest of the tile is then updated with the panel (rank 16) on the matrix cores by all waves.
+// The inverse is built the same way: the four 16 x 16 diagonal blocks by forward substitution in
+// registers (lane = column, one block per wave), the blocks below them by merging pairs,
+// X21 = -X22 (L21 X11), on the matrix cores.
+__global__ __launch_bounds__(256) void ap_chol_diag_kernel(fac_t* __restrict__ A, int BP, int k,
+                                                           fac_t* __restrict__ DI, fac_t* __restrict__ X,
+                                                           int* __restrict__ breakdown) {
+  constexpr int LD = TS + 1;
+  constexpr int PW = 16;                 // panel width
+  __shared__ fac_t T[TS * LD];           // the tile, then L (lower part)
+  __shared__ fac_t Xi[TS * LD];          // L^-1
+  __shared__ fac_t Tm[32 * LD];          // L21 X11 of the pair being merged
+  __shared__ fac_t rdiag[TS];            // 1 / L[c][c]
   const int64_t tile_off = (int64_t)blockIdx.x * BP * BP + (int64_t)k * TS * BP + k * TS;
   fac_t* Ab = A + tile_off;
   fac_t* Xb = X + tile_off;
   fac_t* DIb = DI + (int64_t)blockIdx.x * BP * TS + (int64_t)k * TS * TS;
-  const int lane = threadIdx.x;
-  for (int i0 = 0; i0 < TS; i0 += 16) {     // 16 loads in flight at a time
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lo = lane & 15, hi = lane >> 4;
+  {
     fac_t g[16];
 #pragma unroll
-    for (int q = 0; q < 16; ++q) g[q] = Ab[(int64_t)(i0 + q) * BP + lane];
+    for (int q = 0; q < 16; ++q) {
+      const int e = tid + 256 * q;
+      g[q] = Ab[(int64_t)(e / TS) * BP + (e % TS)];
+    }
 #pragma unroll
-    for (int q = 0; q < 16; ++q) T[i0 + q][lane] = g[q];
+    for (int q = 0; q < 16; ++q) {
+      const int e = tid + 256 * q;
+      T[(e / TS) * LD + (e % TS)] = g[q];
+      Xi[(e / TS) * LD + (e % TS)] = 0.0;
+    }
   }
   __syncthreads();
   bool any_bad = false;
-  for (int c = 0; c < TS; ++c) {
-    const fac_t piv0 = T[c][c];
-    const bool bad = !(piv0 > 0.0) || !(piv0 < 1.0e300);   // also catches NaN
-    any_bad = any_bad || bad;
-    const fac_t piv = bad ? 1.0 : piv0;
-    // 1 / sqrt(piv) from the single-precision estimate and three Newton steps (each squares the relative
-    // error: 2^-22, 2^-43, below 2^-53): a dozen dependent operations instead of a correctly rounded
-    // square root followed by a division per lane; this chain is the critical path of every column step
-    fac_t rinv = (fac_t)__builtin_amdgcn_rsqf((float)piv);
+  for (int p0 = 0; p0 < TS; p0 += PW) {
+    if (wave == 0) {
+      fac_t x[PW];
 #pragma unroll
-    for (int it = 0; it < 3; ++it) rinv = rinv * fma(-0.5 * piv, rinv * rinv, 1.5);
-    const fac_t dg = piv * rinv;
-    const fac_t lc = lane > c ? T[lane][c] * rinv : (lane == c ? dg : 0.0);   // column c of L, this lane's row
-    T[lane][c] = lc;
-    if (lane == c) rdiag[c] = rinv;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    // eight columns at a time, all reads before the writes: the column-c entries are not written in
-    // this loop and a lane writes only its own row, so the loads of a group can be in flight together
-    for (int j0 = c + 1; j0 < TS; j0 += 8) {
-      fac_t col[8], row[8];
+      for (int q = 0; q < PW; ++q) x[q] = T[lane * LD + p0 + q];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        const int jj = j0 + q < TS ? j0 + q : TS - 1;
-        col[q] = T[jj][c];
-        row[q] = T[lane][jj];
+      for (int c = 0; c < PW; ++c) {
+        const fac_t piv0 = lane_bcast(x[c], p0 + c);
+        const bool bad = !(piv0 > 0.0) || !(piv0 < 1.0e300);   // also catches NaN
+        any_bad = any_bad || bad;
+        const fac_t piv = bad ? 1.0 : piv0;
+        // 1 / sqrt(piv) from the single-precision estimate and three Newton steps (each squares the
+        // relative error: 2^-22, 2^-43, below 2^-53); this chain is the critical path of a column step
+        fac_t rinv = (fac_t)__builtin_amdgcn_rsqf((float)piv);
+#pragma unroll
+        for (int it = 0; it < 3; ++it) rinv = rinv * fma(-0.5 * piv, rinv * rinv, 1.5);
+        const fac_t lc = lane > p0 + c ? x[c] * rinv : (lane == p0 + c ? piv * rinv : 0.0);   // column p0 + c of L
+        x[c] = lc;
+        if (lane == p0 + c) rdiag[p0 + c] = rinv;
+#pragma unroll
+        for (int j = c + 1; j < PW; ++j) x[j] = fma(-lc, lane_bcast(lc, p0 + j), x[j]);   // meaningful for rows >= p0 + j
       }
+      if (lane >= p0) {
 #pragma unroll
-      for (int q = 0; q < 8; ++q)
-        if (j0 + q < TS) T[lane][j0 + q] = fma(-lc, col[q], row[q]);   // meaningful for rows >= j0 + q
+        for (int q = 0; q < PW; ++q) T[lane * LD + p0 + q] = x[q];
+      }
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __syncthreads();
+    // trailing blocks (bi >= bj > panel): T_bi,bj -= L_bi,p L_bj,p^T
+    const int pb = p0 / PW, nbk = TS / PW;
+    int idx = 0;
+    for (int bi = pb + 1; bi < nbk; ++bi)
+      for (int bj = pb + 1; bj <= bi; ++bj, ++idx) {
+        if ((idx & 3) != wave) continue;
+        d4 acc = block16_mac_nt(&T[(PW * bi) * LD + p0], &T[(PW * bj) * LD + p0], d4{0.0, 0.0, 0.0, 0.0});
+#pragma unroll
+        for (int v = 0; v < 4; ++v) T[(PW * bi + 4 * v + hi) * LD + PW * bj + lo] -= acc[v];
+      }
+    __syncthreads();
   }
-  if (any_bad && lane == 0) *breakdown = 1;
-  __syncthreads();
-  // column `lane` of L^-1: x_i = (delta_i,lane - sum_{m < i} L[i][m] x_m) / L[i][i]; x_m = 0 for m < lane
-  for (int i = 0; i < TS; ++i) {
-    fac_t s0 = lane == i ? 1.0 : 0.0, s1 = 0.0;
-    int m = 0;
-#pragma unroll 4
-    for (; m + 1 < i; m += 2) {
-      s0 = fma(-T[i][m], Xi[m][lane], s0);
-      s1 = fma(-T[i][m + 1], Xi[m + 1][lane], s1);
+  if (any_bad && tid == 0) *breakdown = 1;
+  // inverse of the four diagonal 16 x 16 blocks: wave w takes block w, lane j < 16 its column j,
+  // x_i = (delta_ij - sum_{m < i} L[i][m] x_m) / L[i][i]
+  if (lo == lane) {   // lanes 0..15
+    const int o = PW * wave;
+    fac_t x[PW];
+#pragma unroll
+    for (int i = 0; i < PW; ++i) {
+      fac_t s0 = lane == i ? 1.0 : 0.0;
+#pragma unroll
+      for (int m = 0; m < i; ++m) s0 = fma(-T[(o + i) * LD + o + m], x[m], s0);
+      x[i] = s0 * rdiag[o + i];
     }
-    if (m < i) s0 = fma(-T[i][m], Xi[m][lane], s0);
-    Xi[i][lane] = (s0 + s1) * rdiag[i];
+#pragma unroll
+    for (int i = 0; i < PW; ++i) Xi[(o + i) * LD + o + lane] = x[i];
   }
   __syncthreads();
-  for (int i = 0; i < TS; ++i) {
-    Ab[(int64_t)i * BP + lane] = lane <= i ? T[i][lane] : 0.0;
-    const fac_t v = Xi[i][lane];
-    DIb[i * TS + lane] = v;
-    Xb[(int64_t)i * BP + lane] = v;
+  // merge pairs of blocks: level 1 = (0,1) and (2,3), 16 x 16 each; level 2 = the 32 x 32 block below
+  // the first two block columns.  Tm = L21 X11, then X21 = -X22 Tm.
+  {
+    // level 1: waves 0 and 1 take one pair each
+    if (wave < 2) {
+      const int o1 = 2 * PW * wave, o2 = o1 + PW;
+      const d4 t = block16_mac(&T[o2 * LD + o1], &Xi[o1 * LD + o1], d4{0.0, 0.0, 0.0, 0.0});
+#pragma unroll
+      for (int v = 0; v < 4; ++v) Tm[(PW * wave + 4 * v + hi) * LD + lo] = t[v];
+    }
+    __syncthreads();
+    if (wave < 2) {
+      const int o1 = 2 * PW * wave, o2 = o1 + PW;
+      const d4 r = block16_mac(&Xi[o2 * LD + o2], &Tm[(PW * wave) * LD], d4{0.0, 0.0, 0.0, 0.0});
+#pragma unroll
+      for (int v = 0; v < 4; ++v) Xi[(o2 + 4 * v + hi) * LD + o1 + lo] = -r[v];
+    }
+    __syncthreads();
+    // level 2: four 16 x 16 output blocks (bi, bj), one per wave; halves are 2 blocks wide
+    const int bi = wave >> 1, bj = wave & 1;
+    {
+      d4 t = d4{0.0, 0.0, 0.0, 0.0};
+      for (int m = bj; m < 2; ++m)     // X11 is lower triangular: block (m, bj) is zero for m < bj
+        t = block16_mac(&T[(32 + PW * bi) * LD + PW * m], &Xi[(PW * m) * LD + PW * bj], t);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) Tm[(PW * bi + 4 * v + hi) * LD + PW * bj + lo] = t[v];
+    }
+    __syncthreads();
+    {
+      d4 r = d4{0.0, 0.0, 0.0, 0.0};
+      for (int m = 0; m <= bi; ++m)    // X22 is lower triangular
+        r = block16_mac(&Xi[(32 + PW * bi) * LD + 32 + PW * m], &Tm[(PW * m) * LD + PW * bj], r);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) Xi[(32 + PW * bi + 4 * v + hi) * LD + PW * bj + lo] = -r[v];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    const int e = tid + 256 * q;
+    const int i = e / TS, j = e % TS;
+    Ab[(int64_t)i * BP + j] = j <= i ? T[i * LD + j] : 0.0;
+    const fac_t v = Xi[i * LD + j];
+    DIb[i * TS + j] = v;
+    Xb[(int64_t)i * BP + j] = v;
   }
 }
 
@@ -808,7 +895,7 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     hipLaunchKernelGGL(ap_build_kernel, dim3(BP / 16, BP / 16, cnt), dim3(16, 16), 0, st, ctx->dX, ctx->d, n,
                        (const double*)ctx->dTheta, ctx->kernel, block, BP, blk0, A);
     for (int k = 0; k < nt; ++k) {
-      hipLaunchKernelGGL(ap_chol_diag_kernel, dim3(cnt), dim3(64), 0, st, A, BP, k, DI, W, fac_breakdown);
+      hipLaunchKernelGGL(ap_chol_diag_kernel, dim3(cnt), dim3(256), 0, st, A, BP, k, DI, W, fac_breakdown);
       const int below = nt - k - 1;
       if (below > 0) {
         hipLaunchKernelGGL(ap_chol_panel_kernel, dim3(below, cnt), dim3(256), 0, st, A, BP, k, (const fac_t*)DI);
