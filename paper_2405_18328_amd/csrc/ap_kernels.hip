@@ -151,36 +151,53 @@ __device__ __forceinline__ int acc_row(int v) { return 16 * (threadIdx.x >> 6) +
 __device__ __forceinline__ int acc_col(int cb) { return 16 * cb + (threadIdx.x & 15); }
 
 // ---- set-up: H[I,I], Cholesky, inverse ------------------------------------------------------------
-// A[z] (BP x BP, row-major, fp64) = H[I,I] for block blk0 + z, identity on the padding rows/columns
+// A[z] (BP x BP, row-major, fp64) = H[I,I] for block blk0 + z, identity on the padding rows/columns.
+// One workgroup per 64 x 64 tile on or below the diagonal (the mirror image is written too); the 2 x 64
+// input rows are staged in LDS, differences (exact), scaling and the kernel function in fp64.
 __global__ __launch_bounds__(256) void ap_build_kernel(const float* __restrict__ X, int d, int64_t n,
                                                        const double* __restrict__ theta, int kind, int block, int BP,
                                                        int blk0, fac_t* __restrict__ A) {
+  extern __shared__ float xs[];            // [2][64][d + 1] input rows of the tile's row and column ranges
+  if (blockIdx.x > blockIdx.y) return;
+  const int ti = blockIdx.y, tj = blockIdx.x;
   const int64_t j0 = (int64_t)(blk0 + blockIdx.z) * block;
   const int64_t left = n - j0;
   const int bs = (int)(left < block ? left : block);
-  const int i = blockIdx.y * 16 + threadIdx.y, j = blockIdx.x * 16 + threadIdx.x;
-  if (i >= BP || j >= BP) return;
-  fac_t v;
-  if (i < bs && j < bs) {
-    const float* xi = X + (j0 + i) * d;
-    const float* xj = X + (j0 + j) * d;
-    double r2 = 0.0;
-    for (int k = 0; k < d; ++k) {
-      const double df = ((double)xi[k] - (double)xj[k]) * theta[k];   // theta[k] = 1 / ell_k
-      r2 = fma(df, df, r2);
-    }
-    const double a = theta[d], sg = theta[d + 1];
-    if (kind == GP_SE_ARD) {
-      v = a * a * exp(-0.5 * r2);
-    } else {
-      const double u = sqrt(3.0 * r2);
-      v = a * a * (1.0 + u) * exp(-u);
-    }
-    if (i == j) v += sg * sg;
-  } else {
-    v = (i == j) ? 1.0 : 0.0;
+  const int ldx = d + 1;
+  for (int e = threadIdx.x; e < 2 * TS * d; e += 256) {
+    const int side = e / (TS * d), q = e % (TS * d);
+    const int r = q / d, kk = q % d;
+    const int row = (side == 0 ? ti : tj) * TS + r;
+    xs[(side * TS + r) * ldx + kk] = row < bs ? X[(j0 + row) * d + kk] : 0.0f;
   }
-  A[(int64_t)blockIdx.z * BP * BP + (int64_t)i * BP + j] = v;
+  __syncthreads();
+  const double a = theta[d], sg = theta[d + 1];
+  fac_t* Ab = A + (int64_t)blockIdx.z * BP * BP;
+  for (int e = threadIdx.x; e < TS * TS; e += 256) {
+    const int r = e / TS, c = e % TS;
+    const int i = ti * TS + r, j = tj * TS + c;
+    fac_t v;
+    if (i < bs && j < bs) {
+      const float* xi = xs + r * ldx;
+      const float* xj = xs + (TS + c) * ldx;
+      double r2 = 0.0;
+      for (int kk = 0; kk < d; ++kk) {
+        const double df = ((double)xi[kk] - (double)xj[kk]) * theta[kk];   // exact difference; theta[kk] = 1 / ell_kk
+        r2 = fma(df, df, r2);
+      }
+      if (kind == GP_SE_ARD) {
+        v = a * a * exp(-0.5 * r2);
+      } else {
+        const double u = sqrt(3.0 * r2);
+        v = a * a * (1.0 + u) * exp(-u);
+      }
+      if (i == j) v += sg * sg;
+    } else {
+      v = (i == j) ? 1.0 : 0.0;
+    }
+    Ab[(int64_t)i * BP + j] = v;
+    Ab[(int64_t)j * BP + i] = v;
+  }
 }
 
 // value of v in lane `src` (wave-uniform), for a double
@@ -892,8 +909,8 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
   const int BP = L.BP, nt = BP / TS;
   for (int blk0 = 0; blk0 < L.nb; blk0 += L.batch) {
     const int cnt = L.nb - blk0 < L.batch ? L.nb - blk0 : L.batch;
-    hipLaunchKernelGGL(ap_build_kernel, dim3(BP / 16, BP / 16, cnt), dim3(16, 16), 0, st, ctx->dX, ctx->d, n,
-                       (const double*)ctx->dTheta, ctx->kernel, block, BP, blk0, A);
+    hipLaunchKernelGGL(ap_build_kernel, dim3(nt, nt, cnt), dim3(256), 2 * TS * (ctx->d + 1) * sizeof(float), st, ctx->dX,
+                       ctx->d, n, (const double*)ctx->dTheta, ctx->kernel, block, BP, blk0, A);
     for (int k = 0; k < nt; ++k) {
       hipLaunchKernelGGL(ap_chol_diag_kernel, dim3(cnt), dim3(256), 0, st, A, BP, k, DI, W, fac_breakdown);
       const int below = nt - k - 1;
