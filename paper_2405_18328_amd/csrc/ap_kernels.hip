@@ -599,8 +599,16 @@ __global__ __launch_bounds__(256) void ap_solve_reduce_kernel(const float* __res
   const int64_t total = (int64_t)bs * t;
   for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
     const int c = (int)(e % t);
-    float v = 0.0f;
-    for (int k = 0; k < ksplit; ++k) v += part[(int64_t)k * total + e];
+    float v0 = 0.0f, v1 = 0.0f, v2 = 0.0f, v3 = 0.0f;     // four chains so that the loads overlap
+    int k = 0;
+    for (; k + 3 < ksplit; k += 4) {
+      v0 += part[(int64_t)k * total + e];
+      v1 += part[(int64_t)(k + 1) * total + e];
+      v2 += part[(int64_t)(k + 2) * total + e];
+      v3 += part[(int64_t)(k + 3) * total + e];
+    }
+    for (; k < ksplit; ++k) v0 += part[(int64_t)k * total + e];
+    float v = (v0 + v1) + (v2 + v3);
     if (frozen[c]) v = 0.0f;
     D[j0 * t + e] = v;
     atomicMax(&smax[c], __float_as_uint(fabsf(v)));
@@ -730,16 +738,22 @@ __global__ __launch_bounds__(1024) void ap_finalise_kernel(ApDev s, int nb, int 
     s.colmax[c] = 0u;
   }
   __syncthreads();
-  // block with the largest residual over the live columns, lowest index on a tie
+  // block with the largest residual over the live columns, lowest index on a tie: wave w scores the
+  // blocks w, w + 16, ..: lanes take the columns 64 apart, then a butterfly sum (fixed order)
   double best = -1.0;
   int bi = 0x7fffffff;
-  for (int k = tid; k < nb; k += 1024) {
-    double sc = 0.0;
-    for (int c = 0; c < t; ++c)
-      if (!sfrozen[c]) sc += s.bnorm[(int64_t)k * t + c];
-    if (sc > best) {
-      best = sc;
-      bi = k;
+  {
+    const int lane = tid & 63, w = tid >> 6;
+    for (int k = w; k < nb; k += 16) {
+      double sc = 0.0;
+      for (int c = lane; c < t; c += 64)
+        if (!sfrozen[c]) sc += s.bnorm[(int64_t)k * t + c];
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) sc += __shfl_xor(sc, off, 64);
+      if (sc > best) {
+        best = sc;
+        bi = k;
+      }
     }
   }
   sscore[tid] = best;
