@@ -297,7 +297,9 @@ def main():
                        "kmv_products_timed": float(n_kmv), "input_generation_s": round(t_gen, 1)},
             "pct_fp32_peak": 100.0 * value / FP32_PEAK_TFLOPS,
             "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                         "frac": achieved / peak, "traffic": TRAFFIC.get((args.workload, n)),
+                         "frac": achieved / peak,
+                         # counter-based bytes exist for the square product only (the CG path's launches)
+                         "traffic": TRAFFIC.get((args.workload, n)) if args.solver == "cg" and not args.predict else None,
                          "kernel": "kmv_tile_kernel" if path == 0 else "kmv_tile_f16_kernel",
                          "product_path": PATH_NAMES[path], "peak_dtype": "fp32" if path == 0 else "fp16",
                          "launches": int(launches), "avg_launch_ms": avg_kern_s * 1e3,
