@@ -307,7 +307,7 @@ def main():
                          "executed_mfma_tflops": executed, "executed_mfma_frac_of_peak": executed / peak,
                          "achieved_vs_fp32_peak": achieved / FP32_PEAK_TFLOPS,
                          "valu_issue_frac": (VALU_INSTS[(args.workload, n)] / avg_kern_s / VALU_ISSUE_PEAK
-                                             if (args.workload, n) in VALU_INSTS and launches and not args.predict
+                                             if (args.workload, n) in VALU_INSTS and launches and not args.predict and args.solver == "cg"
                                              else None)},
         }
         result.update(extra)
