@@ -530,6 +530,74 @@ def test_planted_mistakes_are_caught():
         assert not np.allclose(g, fd, rtol=1e-3, atol=1e-6), name
 
 
+def test_planted_mistakes_in_the_block_solvers_are_caught():
+    """The invariants the alternating-projections and SGD pins rest on are violated by mutated steps
+    (mistakes planted here, on the CPU), and satisfied by a faithful re-statement of the step that agrees
+    with the oracle: the pins have teeth for these two solvers too."""
+    n, b = 33, 8
+    X, ell, a, sigma, y, Z = _problem(n, 3, 51)
+    H = orc.coefficient_matrix(X, ell, a, sigma, orc.MATERN32)
+    B = np.concatenate([y[:, None], Z[:, :2]], axis=1)
+    V0 = 0.1 * np.random.default_rng(2).standard_normal(B.shape)
+    blocks = orc.ap_blocks(n, b)
+
+    def ap_step(pick=np.argmax, sign=-1.0, solve_with=lambda Hii: Hii):
+        R = B - H @ V0
+        j0, j1 = blocks[int(pick([np.sum(R[s:e] ** 2) for s, e in blocks]))]
+        D = np.linalg.solve(solve_with(H[j0:j1, j0:j1]), R[j0:j1])
+        V = V0.copy()
+        V[j0:j1] += D
+        return V, R + sign * (H[:, j0:j1] @ D), (j0, j1)
+
+    def ap_invariants(V, Rtracked, blk):
+        j0, j1 = blk
+        Rtrue = B - H @ V
+        R0 = B - H @ V0
+        gain = 0.5 * np.einsum("ic,ic->c", R0[j0:j1], np.linalg.solve(H[j0:j1, j0:j1], R0[j0:j1]))
+        drop = _objective(H, B, V0) - _objective(H, B, V)
+        best = blk == blocks[int(np.argmax([np.sum(R0[s:e] ** 2) for s, e in blocks]))]
+        return (best and np.abs(Rtrue[j0:j1]).max() < 1e-10 and np.allclose(Rtracked, Rtrue, atol=1e-10)
+                and np.allclose(drop, gain, rtol=1e-8))
+
+    good = ap_step()
+    Vo, _, _, _ = orc.ap_batched(H, B, X0=V0, tol=1e-14, block=b, max_iters=1)
+    np.testing.assert_allclose(good[0], Vo, rtol=1e-12, atol=1e-14)
+    assert ap_invariants(*good)
+    ap_mutants = {
+        "smallest block chosen": ap_step(pick=np.argmin),
+        "residual updated with the wrong sign": ap_step(sign=+1.0),
+        "block solved without the noise term": ap_step(solve_with=lambda Hii: Hii - sigma ** 2 * np.eye(len(Hii))),
+    }
+    for name, res in ap_mutants.items():
+        assert not ap_invariants(*res), name
+
+    I = np.array([3, 17, 4, 11, 0, 30, 21, 9])
+    lr, rho = 1.2, 0.9
+
+    def sgd_two_steps(step_div=None, g_sign=-1.0, mom=rho):
+        U, M = V0.copy(), np.zeros_like(B)
+        for J in (I, (I + 1) % n):
+            G = H[J] @ U - B[J]
+            M *= mom
+            M[J] += g_sign * (lr / (step_div or J.size)) * G
+            U = U + M
+        return U
+
+    Uo, _, _ = orc.sgd_batched(H, B, [I, (I + 1) % n], X0=V0, tol=1e-300, lr=lr, momentum=rho)
+    np.testing.assert_allclose(sgd_two_steps(), Uo, rtol=1e-12, atol=1e-14)
+    # the hand pin: after one step from U0 only the batch rows moved, by (lr/|I|) times their true residual
+    r0 = B - H @ V0
+    U1o, _, _ = orc.sgd_batched(H, B, [I], X0=V0, tol=1e-300, lr=lr, momentum=rho)
+    assert np.allclose(U1o[I] - V0[I], (lr / I.size) * r0[I], rtol=1e-12)
+    sgd_mutants = {
+        "step lr / n instead of lr / |I|": sgd_two_steps(step_div=n),
+        "ascent instead of descent": sgd_two_steps(g_sign=+1.0),
+        "momentum dropped": sgd_two_steps(mom=0.0),
+    }
+    for name, U in sgd_mutants.items():
+        assert not np.allclose(U, Uo, rtol=1e-6, atol=1e-9), name
+
+
 def test_cross_kmv_is_the_posterior_mean_of_a_library_gp():
     """Eq. 1: mu(X*) = k(X*, X) H^{-1} y.  scikit-learn's GaussianProcessRegressor with a fixed
     kernel a^2 RBF(ell) / a^2 Matern(ell, nu=1.5) and alpha = sigma^2 computes the same mean."""
