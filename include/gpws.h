@@ -91,8 +91,11 @@ int gp_set_theta(gp_ctx* ctx, const double* h_lengthscale, double signal_scale, 
  * OUT = K V (add_noise = 0) or (K + sigma^2 I) V (add_noise = 1): the
  * matrix-free product at the heart of every solver iteration (Section 2.1,
  * "Linear System Solver").  dV: n x t, leading dimension ldv; dOut: n x t,
- * leading dimension ldo; dOut must not overlap dV.  1 <= t <= GP_MAX_T.
- * Asynchronous on the context's stream.
+ * leading dimension ldo; the byte ranges of dOut and dV must not overlap
+ * (GP_ERR_ARG otherwise).  1 <= t <= GP_MAX_T.
+ * Asynchronous on the context's stream, except that the first call, and any call
+ * that needs more scratch than an earlier one (larger t), waits for the stream
+ * and reallocates the context's scratch block with hipMalloc.
  */
 int gp_kmv(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo, int add_noise);
 

@@ -889,18 +889,18 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
   void* kmv_scratch = w + L.off_kmv;
 
   const size_t need_pinned = sizeof(ApFlags) + sizeof(float) * t * 2;
-  if (ctx->pinned_bytes < 32768 + sizeof(ApFlags) || need_pinned > 32768)
+  if (ctx->pinned_bytes < GP_PIN_POST + sizeof(ApFlags) || need_pinned > GP_PIN_THETA)
     return gp_fail(ctx, GP_ERR_ARG, "gp_ap_solve: t too large for the pinned staging block");
-  ApFlags* hflags = (ApFlags*)ctx->hPinned;
-  float* htol = (float*)((char*)ctx->hPinned + sizeof(ApFlags));
+  ApFlags* hflags = (ApFlags*)((char*)ctx->hPinned + GP_PIN_SOLVER);
+  float* htol = (float*)((char*)ctx->hPinned + GP_PIN_SOLVER + sizeof(ApFlags));
   float* hrel = htol + t;
   GP_HIP(ctx, hipStreamSynchronize(st));   // the pinned block may still be in use by an earlier call
   for (int c = 0; c < t; ++c) htol[c] = h_tol[c];
   GP_HIP(ctx, hipMemsetAsync(w + L.off_state, 0, L.off_kmv - L.off_state, st));
   GP_HIP(ctx, hipMemcpyAsync(s.tol, htol, sizeof(float) * t, hipMemcpyHostToDevice, st));
 
-  ApFlags* hpost = (ApFlags*)((char*)ctx->hPinned + 32768);
-  s.post = (ApFlags*)((char*)ctx->dPinned + 32768);
+  ApFlags* hpost = (ApFlags*)((char*)ctx->hPinned + GP_PIN_POST);
+  s.post = (ApFlags*)((char*)ctx->dPinned + GP_PIN_POST);
   hpost->seq = 0;
   auto wait_seq = [&](int want) -> int {
     volatile ApFlags* h = hpost;

@@ -466,8 +466,10 @@ int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
 
   // staging through pinned memory: tolerances in, flags and residuals out
   const size_t need_pinned = sizeof(CgFlags) + sizeof(float) * t * 2;
-  if (ctx->pinned_bytes < need_pinned) return gp_fail(ctx, GP_ERR_ARG, "gp_cg_solve: t too large for the pinned staging block");
-  CgFlags* hflags = (CgFlags*)ctx->hPinned;
+  if (need_pinned > GP_PIN_THETA) return gp_fail(ctx, GP_ERR_ARG, "gp_cg_solve: t too large for the pinned staging block");
+  // this region is written by the host only here; every solver synchronises the stream before it
+  // returns, so the copy a previous call queued from it has run (gp_set_theta stages elsewhere)
+  CgFlags* hflags = (CgFlags*)((char*)ctx->hPinned + GP_PIN_SOLVER);
   float* htol = (float*)(hflags + 1);
   float* hrel = htol + t;
   for (int c = 0; c < t; ++c) htol[c] = h_tol[c];
@@ -478,8 +480,8 @@ int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
   // The finalise kernels post the flags into pinned host memory themselves (no copy command in the
   // stream between iterations); the host polls the sequence number, and checks the stream now and
   // then so that a failed launch or a missing post ends the wait instead of hanging it.
-  CgFlags* hpost = (CgFlags*)((char*)ctx->hPinned + 32768);
-  s.post = (CgFlags*)((char*)ctx->dPinned + 32768);
+  CgFlags* hpost = (CgFlags*)((char*)ctx->hPinned + GP_PIN_POST);
+  s.post = (CgFlags*)((char*)ctx->dPinned + GP_PIN_POST);
   hpost->seq = 0;
   auto wait_seq = [&](int want) -> int {
     volatile CgFlags* h = hpost;
@@ -498,6 +500,13 @@ int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     return GP_OK;
   };
 
+  // an error return leaves nothing of this solve running: kernels queued so far would otherwise post
+  // their flags into the next solve's sequence
+  auto drained = [&](int rc) -> int {
+    (void)hipStreamSynchronize(st);
+    return rc;
+  };
+
   int kmv_count = 0;
   // the load kernel leaves max |X0| per column for the warm start's product, whose column-split
   // partials the residual kernel sums itself
@@ -507,7 +516,7 @@ int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
   GP_HIP(ctx, hipGetLastError());
   if (dX0) {
     int rc = gp_kmv_launch(ctx, X, t, t, HP, t, 1, kmv_scratch, L.kmv_bytes, s.colmax, nullptr, &df0);
-    if (rc < 0) return rc;
+    if (rc < 0) return drained(rc);
     ++kmv_count;
   }
   GP_HIP(ctx, hipMemsetAsync(s.colmax, 0, sizeof(unsigned) * t, st));
@@ -517,14 +526,14 @@ int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
   GP_HIP(ctx, hipGetLastError());
   {
     const int rc = wait_seq(1);
-    if (rc < 0) return rc;
+    if (rc < 0) return drained(rc);
   }
 
   int it = 0;
   while (!hpost->all_done && it < max_iters) {
     KmvDeferred df = {nullptr, 0, 1};
     int rc = gp_kmv_launch(ctx, P, t, t, HP, t, 1, kmv_scratch, L.kmv_bytes, s.colmax, nullptr, &df);
-    if (rc < 0) return rc;
+    if (rc < 0) return drained(rc);
     ++kmv_count;
     hipLaunchKernelGGL(cg_dot_kernel, grid, block, 0, st, (const float*)P, HP, df.part, df.stride, df.JS,
                        ctx->n * (int64_t)t, total, t, s.flags, s.part);
@@ -535,7 +544,7 @@ int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     hipLaunchKernelGGL(cg_update_p_kernel, grid, block, 0, st, P, (const float*)R, total, t, (const float*)s.beta, s.flags, s.colmax);
     GP_HIP(ctx, hipGetLastError());
     rc = wait_seq(it + 2);
-    if (rc < 0) return rc;
+    if (rc < 0) return drained(rc);
     ++it;
   }
 

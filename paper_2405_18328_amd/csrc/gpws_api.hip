@@ -55,6 +55,9 @@ int gp_create(gp_ctx** out, int kernel, int64_t n, int d, const float* dX, void*
     else if (!strcmp(f, "f16x2")) ctx->path_forced = GP_PATH_F16X2;
     else if (!strcmp(f, "f16x3")) ctx->path_forced = GP_PATH_F16X3;
   }
+  // tuning aids of the tile pass, read once here and never in a launch path
+  if (const char* e = getenv("GPWS_MI")) ctx->mi_forced = atoi(e) == 2 ? 2 : 1;
+  if (const char* e = getenv("GPWS_W")) ctx->w_forced = atoi(e) == 8 ? 8 : 4;
   ctx->n_pad = (n + GP_ROW_ALIGN - 1) / GP_ROW_ALIGN * GP_ROW_ALIGN;
   ctx->stream = (hipStream_t)hip_stream;
   ctx->dX = dX;
@@ -127,9 +130,9 @@ int gp_set_theta(gp_ctx* ctx, const double* h_lengthscale, double signal_scale, 
     return gp_fail(ctx, GP_ERR_ARG, "gp_set_theta: signal scale %g is not positive and finite", signal_scale);
   if (!(noise_scale >= 0.0) || !std::isfinite(noise_scale))
     return gp_fail(ctx, GP_ERR_ARG, "gp_set_theta: noise scale %g is negative or not finite", noise_scale);
-  // the pinned block is reused as staging; earlier work on the stream that reads it must be done
+  // the staging region is this call's alone; the copy a previous call queued from it must have run
   GP_HIP(ctx, hipStreamSynchronize(ctx->stream));
-  double* stage = (double*)ctx->hPinned;
+  double* stage = (double*)((char*)ctx->hPinned + GP_PIN_THETA);
   for (int k = 0; k < ctx->d; ++k) {
     ctx->ell[k] = h_lengthscale[k];
     stage[k] = 1.0 / h_lengthscale[k];
@@ -151,7 +154,7 @@ int gp_set_theta(gp_ctx* ctx, const double* h_lengthscale, double signal_scale, 
   if (bound <= (double)GP_NORM_X2_MAX && ctx->path_forced < 0) {
     ctx->max_norm = (float)bound;
   } else {
-    float* hmax = (float*)((char*)ctx->hPinned + 4096);
+    float* hmax = (float*)((char*)ctx->hPinned + GP_PIN_NORM);
     GP_HIP(ctx, hipMemcpyAsync(hmax, ctx->dMaxNorm, sizeof(float), hipMemcpyDeviceToHost, ctx->stream));
     GP_HIP(ctx, hipStreamSynchronize(ctx->stream));
     ctx->max_norm = *hmax;
@@ -182,7 +185,12 @@ int gp_kmv(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_
   int rc;
   if ((rc = check_block(ctx, "gp_kmv(dV)", dV, ldv, t)) < 0) return rc;
   if ((rc = check_block(ctx, "gp_kmv(dOut)", dOut, ldo, t)) < 0) return rc;
-  if ((const float*)dOut == dV) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: dOut must not alias dV");
+  {
+    // byte ranges the two blocks span (last row ends after t elements, not after a full leading dimension)
+    const uintptr_t v0 = (uintptr_t)dV, v1 = v0 + ((size_t)(ctx->n - 1) * (size_t)ldv + (size_t)t) * sizeof(float);
+    const uintptr_t o0 = (uintptr_t)dOut, o1 = o0 + ((size_t)(ctx->n - 1) * (size_t)ldo + (size_t)t) * sizeof(float);
+    if (v0 < o1 && o0 < v1) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: dOut overlaps dV");
+  }
   const size_t need = gp_kmv_scratch_bytes(ctx, t);
   if ((rc = gp_ensure_scratch(ctx, need)) < 0) return rc;
   return gp_kmv_launch(ctx, dV, ldv, t, dOut, ldo, add_noise ? 1 : 0, ctx->dScratch, ctx->scratch_bytes, nullptr);

@@ -28,6 +28,14 @@ constexpr float GP_NORM_X2_MAX = 64.0f;
 constexpr float GP_NORM_X3_MAX = 16000.0f;
 constexpr int GP_FLUSH_CHUNKS = 1024; // tile kernels add their fp32 accumulators into OUT every this many column chunks (power of 2)
 constexpr int GP_PROF_MAX = 8192;     // event pairs available to gp_profile
+// Regions of the context's pinned host block (64 KB).  A region the host writes before an asynchronous
+// host-to-device copy must not be written again until that copy has run, so gp_set_theta has one no
+// other call touches (it waits for the stream before writing it); the solvers stage their tolerances
+// and read results back in the first region and synchronise before they return.
+constexpr size_t GP_PIN_SOLVER = 0;       // flags, tolerances in, residuals / gradient sums out
+constexpr size_t GP_PIN_THETA = 16384;    // gp_set_theta: 1/ell, a, sigma staged for the device copy
+constexpr size_t GP_PIN_NORM = 24576;     // largest scaled squared norm read back
+constexpr size_t GP_PIN_POST = 32768;     // flags the solvers' finalise kernels post for the host loop
 
 // Operands of the distance contraction, packed so that one wave-wide dword
 // load is one MFMA operand: P[(chunk*KS + ks)*64 + lane] holds, for row
@@ -57,6 +65,8 @@ struct gp_ctx {
   int XP;                 // pieces used per operand of the distance chain (2 or 3)
   int path;               // GP_PATH_* chosen by gp_set_theta
   int path_forced;        // -1, or a GP_PATH_* forced through the GPWS_PATH environment variable
+  int mi_forced;          // 0, or the sub-tiles per wave forced through GPWS_MI (tuning aid, read at gp_create)
+  int w_forced;           // 0, or the wavefronts per workgroup forced through GPWS_W (tuning aid, read at gp_create)
   bool f16_ok;            // false when d + 3 components do not fit the widest fp16 operand bucket (SE, d = 126)
   float max_norm;         // host copy of max_i |xs_i|^2
   double* dMean;          // d column means of X

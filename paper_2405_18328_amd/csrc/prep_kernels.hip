@@ -216,7 +216,7 @@ int gp_pack_rows(gp_ctx* ctx, const float* dXstar, int64_t m, void* buf, KmvRows
                      (u32x4*)(w + L.off_a[2]), (u32x4*)(w + L.off_b[0]), (u32x4*)(w + L.off_b[1]), (u32x4*)(w + L.off_b[2]));
   GP_HIP(ctx, hipGetLastError());
   // the product path must cover the scaled norms of both point sets
-  unsigned* hmax = (unsigned*)ctx->hPinned;
+  unsigned* hmax = (unsigned*)((char*)ctx->hPinned + GP_PIN_NORM);
   GP_HIP(ctx, hipMemcpyAsync(hmax, dmax, sizeof(unsigned), hipMemcpyDeviceToHost, ctx->stream));
   GP_HIP(ctx, hipStreamSynchronize(ctx->stream));
   float mx;

@@ -436,18 +436,18 @@ int gp_sgd_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, floa
   void* kmv_scratch = w + L.off_kmv;
 
   const size_t need_pinned = sizeof(SgdFlags) + sizeof(float) * t * 2;
-  if (ctx->pinned_bytes < 32768 + sizeof(SgdFlags) || need_pinned > 32768)
+  if (ctx->pinned_bytes < GP_PIN_POST + sizeof(SgdFlags) || need_pinned > GP_PIN_THETA)
     return gp_fail(ctx, GP_ERR_ARG, "gp_sgd_solve: t too large for the pinned staging block");
-  SgdFlags* hflags = (SgdFlags*)ctx->hPinned;
-  float* htol = (float*)((char*)ctx->hPinned + sizeof(SgdFlags));
+  SgdFlags* hflags = (SgdFlags*)((char*)ctx->hPinned + GP_PIN_SOLVER);
+  float* htol = (float*)((char*)ctx->hPinned + GP_PIN_SOLVER + sizeof(SgdFlags));
   float* hrel = htol + t;
   GP_HIP(ctx, hipStreamSynchronize(st));   // the pinned block may still be in use by an earlier call
   for (int c = 0; c < t; ++c) htol[c] = h_tol[c];
   GP_HIP(ctx, hipMemsetAsync(w + L.off_state, 0, L.off_part - L.off_state, st));
   GP_HIP(ctx, hipMemcpyAsync(s.tol, htol, sizeof(float) * t, hipMemcpyHostToDevice, st));
 
-  SgdFlags* hpost = (SgdFlags*)((char*)ctx->hPinned + 32768);
-  s.post = (SgdFlags*)((char*)ctx->dPinned + 32768);
+  SgdFlags* hpost = (SgdFlags*)((char*)ctx->hPinned + GP_PIN_POST);
+  s.post = (SgdFlags*)((char*)ctx->dPinned + GP_PIN_POST);
   hpost->all_done = 0;      // the mirror still holds the previous call's last post
   hpost->bad = 0;
   hpost->iters = 0;

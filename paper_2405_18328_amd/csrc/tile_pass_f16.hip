@@ -557,9 +557,9 @@ KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx, int64_t rows, int64_t col_chunks) {
   // two sub-tiles per wave halve the LDS operand traffic; past one k-step of distance operands the
   // second sub-tile no longer fits the register file without spills
   pl.MI = (ctx->KH == 1 && rows >= 8192) ? 2 : 1;
-  if (const char* e = getenv("GPWS_MI")) pl.MI = (atoi(e) == 2 && ctx->KH <= 2) ? 2 : 1;   // tuning aid
+  if (ctx->mi_forced) pl.MI = (ctx->mi_forced == 2 && ctx->KH <= 2) ? 2 : 1;   // tuning aid
   pl.W = 4;   // 8-wave workgroups halve the L2-to-LDS traffic but measured no faster on MI355X
-  if (const char* e = getenv("GPWS_W")) pl.W = atoi(e) == 8 ? 8 : 4;                            // tuning aid
+  if (ctx->w_forced) pl.W = ctx->w_forced;                                      // tuning aid
   const int rows_per_wg = 32 * pl.W * pl.MI;
   pl.row_blocks = (int)((rows + rows_per_wg - 1) / rows_per_wg);
   const int target = 2 * ctx->num_cu;
