@@ -216,6 +216,57 @@ def mll_grad_hutchinson(X, ell, a, sigma, kind, B, V=None):
     return np.array(g)
 
 
+def mll_grad_hutchinson_rows(X, ell, a, sigma, kind, B, V, rows=None, row_block=256, workers=1):
+    """The estimator of mll_grad_hutchinson at a given V, summed over rows i of the derivative matrices:
+
+        g_k = sum_i [ 1/2 v_y,i (dH_k v_y)_i - 1/(2s) sum_j v_j,i (dH_k z_j)_i ]
+
+    Rows i of every dH_k are formed a block at a time against all n columns and dropped again, so
+    nothing n x n is ever held and n of several 10^4 fits in memory.  rows = None sums over all n rows
+    (that is the estimator); an index array sums those rows' terms only, which is the whole estimator
+    whenever V is zero outside them.  workers > 1 only spreads the row blocks over threads.
+    """
+    X, B, V, ell = _f64(X), _f64(B), _f64(V), _f64(ell)
+    a, sigma = float(a), float(sigma)
+    n, d = X.shape
+    s = B.shape[1] - 1
+    rows = np.arange(n) if rows is None else np.asarray(rows, dtype=np.int64)
+    vy, Vz, Z = V[:, 0], V[:, 1:], B[:, 1:]
+
+    def term(I, M):
+        """The rows I of one derivative matrix (M = dH_k[I, :]) entered into both parts of g_k."""
+        quad = 0.5 * vy[I] @ (M @ vy)
+        tr = np.sum(Vz[I] * (M @ Z)) / s if s > 0 else 0.0
+        return quad - 0.5 * tr
+
+    def block(I):
+        g = np.zeros(d + 2)
+        r2 = scaled_sqdist(X[I], X, ell)
+        if kind == SE:
+            psi = a * a * np.exp(-0.5 * r2)
+        elif kind == MATERN32:
+            psi = 3.0 * a * a * np.exp(-_SQRT3 * np.sqrt(r2))
+        else:
+            raise ValueError(kind)
+        for k in range(d):
+            D = (X[I, k][:, None] - X[:, k][None, :]) ** 2
+            g[k] = term(I, psi * D / ell[k] ** 3)                      # rows of dK/d ell_k, as in dK_dell
+        g[d] = term(I, 2.0 * kernel_from_sqdist(r2, a, kind) / a)      # rows of dK/da
+        E = np.zeros((I.size, n))
+        E[np.arange(I.size), I] = 2.0 * sigma                          # rows of dH/dsigma = 2 sigma I
+        g[d + 1] = term(I, E)
+        return g
+
+    blocks = [rows[i0:i0 + row_block] for i0 in range(0, rows.size, row_block)]
+    if workers > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            parts = list(ex.map(block, blocks))
+    else:
+        parts = [block(I) for I in blocks]
+    return np.sum(parts, axis=0) if parts else np.zeros(d + 2)
+
+
 # --------------------------------------------------------------------------
 # Batched conjugate gradients, no preconditioner (Section 2.1 "Linear System
 # Solver", Appendix B stopping rule)

@@ -203,6 +203,37 @@ def test_hutchinson_at_given_V_noise_component_identity():
 
 
 # ---------------------------------------------------------------- probes (Lemma 2)
+@pytest.mark.parametrize("kind", KINDS)
+def test_hutchinson_by_rows_equals_the_dense_estimator(kind):
+    """The row-blocked form used at n of several 10^4 is the dense estimator: all rows in ragged blocks
+    (also on threads), a partition of the rows adds up to it, and rows outside the support of V add nothing."""
+    rng = np.random.default_rng(31)
+    n, d, s = 61, 3, 5
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    X[7] = X[3]                                   # a coincident pair (r = 0 off the diagonal)
+    ell, a, sigma = np.array([0.7, 1.3, 2.1]), 1.4, 0.6
+    B = rng.standard_normal((n, s + 1))
+    V = rng.standard_normal((n, s + 1))
+    dense = orc.mll_grad_hutchinson(X, ell, a, sigma, kind, B, V=V)
+    for rb, workers in ((7, 1), (64, 1), (5, 3)):
+        got = orc.mll_grad_hutchinson_rows(X, ell, a, sigma, kind, B, V, row_block=rb, workers=workers)
+        assert np.allclose(got, dense, rtol=1e-12, atol=1e-12 * np.abs(dense).max())
+    perm = rng.permutation(n)
+    parts = [orc.mll_grad_hutchinson_rows(X, ell, a, sigma, kind, B, V, rows=perm[:20]),
+             orc.mll_grad_hutchinson_rows(X, ell, a, sigma, kind, B, V, rows=perm[20:])]
+    assert np.allclose(parts[0] + parts[1], dense, rtol=1e-12, atol=1e-12 * np.abs(dense).max())
+    assert np.abs(parts[0]).min() > 0
+    R = np.sort(perm[:17])
+    Vs = np.zeros_like(V)
+    Vs[R] = V[R]
+    assert np.allclose(orc.mll_grad_hutchinson_rows(X, ell, a, sigma, kind, B, Vs, rows=R),
+                       orc.mll_grad_hutchinson(X, ell, a, sigma, kind, B, V=Vs), rtol=1e-12,
+                       atol=1e-12 * np.abs(dense).max())
+    # no probes: the quadratic term alone
+    assert np.allclose(orc.mll_grad_hutchinson_rows(X, ell, a, sigma, kind, B[:, :1], V[:, :1], row_block=9),
+                       orc.mll_grad_hutchinson(X, ell, a, sigma, kind, B[:, :1], V=V[:, :1]), rtol=1e-12)
+
+
 @pytest.mark.parametrize("law,fourth", [("gaussian", 3.0), ("rademacher", 1.0)])
 def test_probe_generator_lemma2(law, fourth):
     """E ||((1/s) sum z z^T - I) c||^2 = (E z^4 + n - 2) / s for unit c (Appendix A, Lemma 2)."""
