@@ -154,9 +154,13 @@ __global__ __launch_bounds__(256) void grad_tile_f16_kernel(GradArgsH p) {
   // Writes the accumulators to OUT (first: stores; later: adds to what is there) without alpha and
   // 2^qshift, and clears them.  Doing so after every segment keeps the chains of fp32 partial sums
   // short; the same threads read and write the same elements, in a fixed order.
+  // The weights of odd row sub-tiles are packed with their sign flipped (grad_pack_ac_f16_kernel) and the
+  // flip is undone here: what is left of the one-sided rounding described at the weight chain below
+  // then enters the sums over rows with alternating sign instead of adding up.
   const int alpha_exp = p.scales[0];
-  const float oscale = ldexpf(1.0f, -alpha_exp - p.qshift);
-  const float vscale = ldexpf(1.0f, -alpha_exp);
+  const float row_sign = (sub0 & 1) ? -1.0f : 1.0f;
+  const float oscale = row_sign * ldexpf(1.0f, -alpha_exp - p.qshift);
+  const float vscale = row_sign * ldexpf(1.0f, -alpha_exp);
   float* out = p.OUT + (int64_t)js * p.split_stride;
   auto flush = [&](bool first) {
     // an opaque zero keeps the address arithmetic of the flush inside it: hoisted out of the segment
@@ -218,13 +222,25 @@ __global__ __launch_bounds__(256) void grad_tile_f16_kernel(GradArgsH p) {
       S = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0], xb[1][kh], S, 0, 0, 0);
       S = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0], xb[0][kh], S, 0, 0, 0);
     }
+    // Largest terms first, on purpose.  This matrix instruction rounds to nearest when its accumulator
+    // input is the largest addend, but an accumulator input smaller than the products is cut off below
+    // half a unit in the last place of the result toward minus infinity (measured on MI355X).  Small
+    // cross terms summed first and the hi*hi products added on top of them would give every w_ij a bias
+    // of about -2^-25 |w_ij| of one sign, which the sum over all pairs does not average out while the
+    // terms themselves cancel (V nearly orthogonal to K's large eigenvectors, as after a solve).
+    {
+      f16x8 chs[KT];
 #pragma unroll
-    for (int kt = 0; kt < KT; ++kt) {
-      const f16x8 ch_ = as_f16x8(s[C_OFF + (0 * KT + kt) * 64 + lane]);
-      const f16x8 cl_ = as_f16x8(s[C_OFF + (1 * KT + kt) * 64 + lane]);
-      Wc = __builtin_amdgcn_mfma_f32_32x32x16_f16(cl_, abh[kt], Wc, 0, 0, 0);
-      Wc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ch_, abl[kt], Wc, 0, 0, 0);
-      Wc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ch_, abh[kt], Wc, 0, 0, 0);
+      for (int kt = 0; kt < KT; ++kt) {
+        chs[kt] = as_f16x8(s[C_OFF + (0 * KT + kt) * 64 + lane]);
+        Wc = __builtin_amdgcn_mfma_f32_32x32x16_f16(chs[kt], abh[kt], Wc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt) {
+        const f16x8 cl_ = as_f16x8(s[C_OFF + (1 * KT + kt) * 64 + lane]);
+        Wc = __builtin_amdgcn_mfma_f32_32x32x16_f16(chs[kt], abl[kt], Wc, 0, 0, 0);
+        Wc = __builtin_amdgcn_mfma_f32_32x32x16_f16(cl_, abh[kt], Wc, 0, 0, 0);
+      }
     }
     if (ch == sub0) {   // the pair (i, i): r^2 = 0 exactly
       asm volatile("" ::: "memory");   // keeps this a real (wave-uniform) branch instead of selects on every chunk
@@ -351,6 +367,7 @@ __global__ __launch_bounds__(256) void grad_pack_ac_f16_kernel(const float* __re
         const float cv = col == 0 ? v : B[row * ldb + col];
         c = ldexpf(cv, C_TOP - ec);
         a = ldexpf((col == 0 ? half_w : probe_w) * v, alpha_exp + ec - C_TOP);
+        if (chunk & 1) a = -a;   // undone by the tile kernel's epilogue (row_sign)
       }
       split2(c, c_hi[z], c_lo[z]);
       split2(a, a_hi[z], a_lo[z]);

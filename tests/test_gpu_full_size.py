@@ -19,8 +19,28 @@ pytestmark = pytest.mark.gpu
 KMV_TOL = 1e-5
 
 
+_WORKLOADS = {}
+
+
 def _note(msg):
     print(f"[full-size] {msg}", flush=True)
+
+
+def _make(name, **kw):
+    """Workloads of this module are generated once (the n = 2M one takes half a minute)."""
+    key = (name, tuple(sorted(kw.items())))
+    if key not in _WORKLOADS:
+        _WORKLOADS[key] = make(name, **kw)
+    return _WORKLOADS[key]
+
+
+def _oracle_rows_threaded(w, ell, a, sigma, M, rows, workers=8):
+    """orc.kmv_rows on `rows`, the row sample cut into pieces that run on threads."""
+    from concurrent.futures import ThreadPoolExecutor
+    pieces = np.array_split(np.asarray(rows), max(1, min(workers, len(rows) // 8)))
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        outs = list(ex.map(lambda r: orc.kmv_rows(w.X, ell, a, w.kind, M, r, sigma=sigma), pieces))
+    return np.concatenate(outs, axis=0)
 
 
 def test_config2_full_size_mll_steps_sampled_against_oracle():
@@ -84,7 +104,7 @@ def test_config2_full_size_mll_steps_sampled_against_oracle():
 def test_config5_two_million_rows_sampled_against_oracle():
     """n=2,000,000, d=11, SE, t=65 (5% duplicated rows): one K V product as bench.py --kmv-only
     launches it; exact rows from the oracle, equal rows for duplicated inputs, symmetry of K."""
-    w = make("config5")
+    w = _make("config5")
     assert w.n == 2_000_000 and w.d == 11
     _note("inputs ready")
     dv = Dev(w.X, w.kind, w.ell, w.a, w.sigma)
@@ -226,7 +246,7 @@ def test_config5_two_million_rows_first_steps_of_ap_and_sgd():
     second, V[I2] = H[I2,I2]^-1 (B[I2] - H[I2,I1] V[I1]).
     SGD: U1[I1] = (lr/b) B[I1]; U2 = U1 + rho U1 - (lr/b) (H[I2,:] U1 - B[I2]) on I2, and H[I2,:] U1
     only involves the columns I1."""
-    w = make("config5")
+    w = _make("config5")
     assert w.n == 2_000_000
     _note("inputs ready")
     t = 5
@@ -287,5 +307,188 @@ def test_config5_two_million_rows_first_steps_of_ap_and_sgd():
         assert err.max() <= 1e-4
         got[touched] = 0.0
         assert not got.any()
+    finally:
+        dv.close()
+
+
+# ---------------------------------------------------------------------------------------------------
+# Column ranges longer than one accumulation segment.  Every tile kernel adds its fp32 accumulators into
+# its output after 1024 column chunks (32768 columns) and goes on; a workgroup walks more than one such
+# segment only when its column range is not split, i.e. from 65536 rows up.  The cases below run that
+# loop in every tile kernel (K V and gradient, split-fp16 and fp32) under an oracle check.
+# ---------------------------------------------------------------------------------------------------
+LONG_N = 70001      # 2188 column chunks: three segments, a ragged last chunk, no column split
+
+
+@pytest.mark.parametrize("name,kw,path", [
+    ("config4", dict(n=LONG_N, s=8), None),         # Matern-3/2, d = 90: six 16-wide k-steps of distance operands
+    ("config4", dict(n=LONG_N, s=8), "fp32"),       # the same through the fp32 matrix-core kernel (KS = 46)
+    ("config2", dict(n=LONG_N, s=64), None),        # Matern-3/2, d = 26, t = 65 (two N-tiles + the y column)
+    ("config2", dict(n=LONG_N, s=8), "f16x3"),      # three fp16 pieces per distance operand
+    ("config5", dict(n=LONG_N, s=8), "fp32"),       # SE, d = 11 through the fp32 kernel, two sub-tiles per wave
+])
+def test_kmv_column_ranges_of_several_segments(monkeypatch, name, kw, path):
+    if path:
+        monkeypatch.setenv("GPWS_PATH", path)
+    w = _make(name, **kw)
+    dv = Dev(w.X, w.kind, w.ell, w.a, w.sigma)
+    try:
+        want = {None: gp.gp_product_path(dv.ctx), "fp32": 0, "f16x2": 1, "f16x3": 2}[path]
+        assert gp.gp_product_path(dv.ctx) == want
+        got = dv.kmv(w.B, 1)
+        rows = np.random.default_rng(8).choice(w.n, size=160, replace=False)
+        rows[:6] = [0, w.n - 1, 32767, 32768, 65535, 65536]
+        ref = _oracle_rows_threaded(w, w.ell, w.a, w.sigma, w.B, rows)
+        err = relerr(got[rows], ref)
+        _note(f"{name} {kw} path {path}: K V error on {rows.size} rows {err:.2e}")
+        assert err <= KMV_TOL
+        assert np.abs(got[rows] - ref).max() <= 50 * KMV_TOL * np.abs(ref).max()
+    finally:
+        dv.close()
+
+
+_GRAD_REF = {}
+
+
+@pytest.mark.parametrize("name,path", [("config3", None), ("config3", "fp32"), ("config3", "f16x3"),
+                                       ("config2", None), ("config2", "fp32"), ("config2", "f16x3")])
+def test_gradient_column_ranges_of_several_segments(monkeypatch, name, path):
+    """gp_mll_grad at n = 70001 (SE d = 3 and Matern-3/2 d = 26, t = 9) on each arithmetic path.  The
+    oracle's estimator summed over rows (pinned to the dense one at small n) needs every row of every
+    derivative matrix, n^2 d entries, so V is given support on 1536 rows spread over the whole range:
+    the sum then has those rows' terms only and the oracle forms just them, against all n columns."""
+    if path:
+        monkeypatch.setenv("GPWS_PATH", path)
+    w = _make(name, n=LONG_N, s=8)
+    a, sigma = 1.1, 0.3
+    ell = w.ell * np.linspace(0.9, 1.4, w.d)
+    rng = np.random.default_rng(17)
+    R = np.sort(rng.choice(w.n, size=1536, replace=False))
+    R[:3], R[-3:] = [0, 1, 2], [w.n - 3, w.n - 2, w.n - 1]
+    R = np.unique(np.concatenate([R, [32767, 32768, 65535, 65536]]))
+    V = np.zeros(w.B.shape, dtype=np.float32)
+    V[R] = (rng.standard_normal((R.size, w.s + 1)) * 0.3).astype(np.float32)
+    if name not in _GRAD_REF:
+        _note(f"oracle estimator over {R.size} rows x {w.n} columns, d = {w.d}")
+        _GRAD_REF[name] = orc.mll_grad_hutchinson_rows(w.X, ell, a, sigma, w.kind, w.B, V, rows=R, row_block=32, workers=8)
+    ref = _GRAD_REF[name]
+    dv = Dev(w.X, w.kind, ell, a, sigma)
+    try:
+        g = dv.grad(dv.to(V), dv.to(w.B))
+        err = relerr(g, ref)
+        _note(f"{name} path {path} ({gp.gp_product_path(dv.ctx)}): gradient error {err:.2e}")
+        assert np.isfinite(g).all() and err <= 1e-3
+        assert relerr(g[: w.d], ref[: w.d]) <= 1e-3
+        # the same call again gives the same bits (fixed-order sums, no float atomics)
+        assert np.array_equal(g, dv.grad(dv.to(V), dv.to(w.B)))
+    finally:
+        dv.close()
+
+
+@pytest.mark.parametrize("name", ["config3", "config4"])
+def test_config3_and_config4_full_size_product_sampled_against_oracle(name):
+    """One K V product at the full n of the two remaining large configurations (n = 400000, d = 3, SE;
+    n = 500000, d = 90, Matern-3/2 at ell = sqrt(d)), t = 65, as bench.py --kmv-only launches it."""
+    w = _make(name)
+    assert (w.n, w.d) == {"config3": (400000, 3), "config4": (500000, 90)}[name]
+    _note(f"{name} inputs ready")
+    dv = Dev(w.X, w.kind, w.ell, w.a, w.sigma)
+    try:
+        t = w.s + 1
+        Bd = dv.to(w.B)
+        out = torch.empty_like(Bd)
+        gp.gp_kmv(dv.ctx, Bd, t, t, out, t, 1)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        assert np.isfinite(got).all()
+        rows = np.random.default_rng(9).choice(w.n, size=64, replace=False)
+        rows[:4] = [0, w.n - 1, 262143, 262144]
+        ref = _oracle_rows_threaded(w, w.ell, w.a, w.sigma, w.B, rows)
+        err = relerr(got[rows], ref)
+        _note(f"{name}: K V error on {rows.size} rows {err:.2e}")
+        assert err <= KMV_TOL
+        assert np.abs(got[rows] - ref).max() <= 50 * KMV_TOL * np.abs(ref).max()
+    finally:
+        dv.close()
+        _WORKLOADS.clear()
+
+
+def test_config5_two_million_rows_capped_cg_and_gradient():
+    """n = 2,000,000, t = 65: the solver's vector kernels and the gradient pass at the largest size.
+    (a) three CG iterations from zero.  Unpreconditioned CG does not converge here (condition number
+        ~1e8), so the call must come back GP_NOT_CONVERGED; its iterate and recursive residuals are
+        compared with the oracle's textbook CG run for three iterations on the same product (the library's
+        own gp_kmv, which the test above checks against exact rows), and the TRUE residual B - H V of the
+        iterate, from exact oracle rows, with the reported recursive one.
+    (b) gp_mll_grad at that iterate: the noise-scale component against its closed form, the amplitude
+        component through the product K [v_y, Z], and every component against the oracle's estimator
+        summed over rows for a V (t = 9) supported on 132 rows."""
+    w = _make("config5")
+    n, t, s = w.n, w.s + 1, w.s
+    dv = Dev(w.X, w.kind, w.ell, w.a, w.sigma)
+    try:
+        Bd = dv.to(w.B)
+        rc, it, kmv, rr, Vd = dv.solve(Bd, w.tol, max_iters=3)
+        _note(f"capped solve: rc {rc}, {it} iterations, recursive residuals {rr.min():.3g} .. {rr.max():.3g}")
+        assert rc == gp.GP_NOT_CONVERGED and it == 3 and kmv == 3
+        V = Vd.cpu().numpy().astype(np.float64)
+        B = w.B.astype(np.float64)
+
+        def matvec(P):
+            Pd = torch.from_numpy(np.ascontiguousarray(P, dtype=np.float32)).to(dv.dev)
+            out = torch.empty_like(Pd)
+            gp.gp_kmv(dv.ctx, Pd, t, t, out, t, 1)
+            torch.cuda.synchronize()
+            return out.cpu().numpy().astype(np.float64)
+
+        Vref, itref, rrref = orc.cg_batched(matvec, B, tol=w.tol, max_iters=3)
+        _note("oracle CG on the same product done")
+        assert itref == 3
+        err = np.linalg.norm(V - Vref, axis=0) / np.linalg.norm(Vref, axis=0)
+        _note(f"iterate against the oracle's CG: {err.max():.2e}; residuals {np.abs(rr / rrref - 1).max():.2e}")
+        assert err.max() <= 1e-4
+        assert np.abs(rr / rrref - 1.0).max() <= 1e-3
+        del Vref
+        # true residual on sampled rows (exact rows of H V from the oracle), all columns together and one by one
+        rows = np.random.default_rng(15).choice(n, size=192, replace=False)
+        HV = _oracle_rows_threaded(w, w.ell, w.a, w.sigma, V, rows)
+        r2 = np.sum((HV - B[rows]) ** 2, axis=0) * (n / rows.size)
+        rel = np.sqrt(r2) / np.linalg.norm(B, axis=0)
+        agg = np.sqrt(r2.sum() / np.sum((rr.astype(np.float64) * np.linalg.norm(B, axis=0)) ** 2))
+        _note(f"true / recursive residual: all columns {agg:.3f}, per column {np.min(rel / rr):.2f} .. {np.max(rel / rr):.2f}")
+        assert 0.85 <= agg <= 1.15
+        assert (rel / rr > 0.5).all() and (rel / rr < 2.0).all()
+
+        # (b) gradient at the iterate
+        g = dv.grad(Vd, Bd)
+        assert np.isfinite(g).all()
+        g_sigma = w.sigma * (V[:, 0] @ V[:, 0] - np.sum(V[:, 1:] * B[:, 1:]) / s)
+        assert g[-1] == pytest.approx(g_sigma, rel=1e-5)
+        C = Bd.clone()
+        C[:, 0] = Vd[:, 0]
+        KC = torch.empty_like(C)
+        gp.gp_kmv(dv.ctx, C, t, t, KC, t, 0)
+        torch.cuda.synchronize()
+        KC = KC.cpu().numpy().astype(np.float64)
+        terms = np.concatenate([[0.5 * V[:, 0] @ KC[:, 0]], -0.5 * np.sum(V[:, 1:] * KC[:, 1:], axis=0) / s])
+        g_a = (2.0 / w.a) * terms.sum()
+        _note(f"dL/dsigma {g[-1]:.6g} (closed form {g_sigma:.6g}); dL/da {g[-2]:.6g} (through K C {g_a:.6g})")
+        assert abs(g[-2] - g_a) <= 1e-3 * (2.0 / w.a) * np.abs(terms).sum()
+        del KC, C, V
+
+        # every component against the oracle, t = 9, V supported on 132 rows (the oracle forms those rows
+        # of the d + 2 derivative matrices against all 2M columns)
+        t9 = 9
+        B9 = np.ascontiguousarray(w.B[:, :t9])
+        rng = np.random.default_rng(19)
+        R = np.unique(np.concatenate([rng.choice(n, size=128, replace=False), [0, n - 1, 1_048_575, 1_048_576]]))
+        Vs = np.zeros(B9.shape, dtype=np.float32)
+        Vs[R] = (rng.standard_normal((R.size, t9)) * 0.3).astype(np.float32)
+        gs = dv.grad(dv.to(Vs), dv.to(B9))
+        _note(f"oracle estimator over {R.size} rows x {n} columns")
+        ref = orc.mll_grad_hutchinson_rows(w.X, w.ell, w.a, w.sigma, w.kind, B9, Vs, rows=R, row_block=4, workers=8)
+        err = relerr(gs, ref)
+        _note(f"gradient with V supported on {R.size} rows: error {err:.2e}")
+        assert err <= 1e-3 and relerr(gs[: w.d], ref[: w.d]) <= 1e-3
     finally:
         dv.close()
