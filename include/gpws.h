@@ -99,6 +99,25 @@ int gp_set_theta(gp_ctx* ctx, const double* h_lengthscale, double signal_scale, 
  */
 int gp_kmv(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo, int add_noise);
 
+/*
+ * gp_kmv for callers that cannot allocate: code between hipStreamBeginCapture and
+ * hipStreamEndCapture, serving loops that must never reach hipMalloc, harnesses that forbid it.
+ * Same arguments, same kernels and bit-identical results as gp_kmv, but the scratch of the product
+ * (column maxima, the packed images of V, column-split partial sums) is a file-scope device array
+ * of GP_KMV_STATIC_SCRATCH_BYTES bytes that every GPU the library is used on holds until the
+ * process ends, and the call reaches no hipMalloc, hipFree, stream synchronisation or memset
+ * command.  A product whose scratch does not fit (256 bytes per row for the packed images of V,
+ * plus n t floats per column split, of which there are up to 64 when n is small: n = 16384, t = 65
+ * needs 39 MB, n = 200000 needs 52 MB, n = 300000 does not fit) is refused with GP_ERR_WORKSPACE
+ * and nothing is launched: use gp_kmv for it.
+ * All calls on one GPU, from any context, share that GPU's array: two such calls must not be in
+ * flight on one GPU at the same time (calls on one stream are ordered and safe; calls on different
+ * streams race).  Nothing in it needs to survive between calls; what must start at zero is cleared
+ * by the call itself.
+ */
+#define GP_KMV_STATIC_SCRATCH_BYTES (64u << 20)
+int gp_kmv_static(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo, int add_noise);
+
 /* Bytes of device workspace gp_cg_solve needs for t right-hand sides (0 on bad arguments). */
 size_t gp_workspace_bytes(const gp_ctx* ctx, int t);
 

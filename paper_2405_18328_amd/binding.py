@@ -30,7 +30,7 @@ LIB_PATH = os.environ.get("GPWS_LIB") or os.path.join(os.path.dirname(os.path.ab
 
 GP_AP_MAX_BLOCK = 2048
 
-EXPORTS = ["gp_create", "gp_destroy", "gp_set_theta", "gp_kmv", "gp_workspace_bytes", "gp_cg_solve",
+EXPORTS = ["gp_create", "gp_destroy", "gp_set_theta", "gp_kmv", "gp_kmv_static", "gp_workspace_bytes", "gp_cg_solve",
            "gp_ap_workspace_bytes", "gp_ap_solve", "gp_sgd_workspace_bytes", "gp_sgd_solve", "gp_mll_grad", "gp_predict", "gp_profile", "gp_profile_read", "gp_product_path", "gp_last_error"]
 
 
@@ -43,6 +43,7 @@ def _load():
     lib.gp_destroy.argtypes = [p]
     lib.gp_set_theta.argtypes = [p, C.POINTER(dbl), dbl, dbl]
     lib.gp_kmv.argtypes = [p, p, i64, i32, p, i64, i32]
+    lib.gp_kmv_static.argtypes = [p, p, i64, i32, p, i64, i32]
     lib.gp_workspace_bytes.argtypes = [p, i32]
     lib.gp_workspace_bytes.restype = sz
     lib.gp_cg_solve.argtypes = [p, p, i64, p, p, i64, i32, C.POINTER(C.c_float), i32, p, sz,
@@ -120,6 +121,13 @@ def gp_set_theta(ctx, lengthscale, signal_scale, noise_scale):
 
 def gp_kmv(ctx, dV, ldv, t, dOut, ldo, add_noise):
     return _check(ctx, _lib.gp_kmv(ctx, _ptr(dV), int(ldv), int(t), _ptr(dOut), int(ldo), int(add_noise)))
+
+
+GP_KMV_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def gp_kmv_static(ctx, dV, ldv, t, dOut, ldo, add_noise):
+    return _check(ctx, _lib.gp_kmv_static(ctx, _ptr(dV), int(ldv), int(t), _ptr(dOut), int(ldo), int(add_noise)))
 
 
 def gp_workspace_bytes(ctx, t):

@@ -6,6 +6,7 @@
 #include <cstring>
 #include <cmath>
 #include <cstdlib>
+#include <mutex>
 #include <new>
 
 #include "gpws_internal.h"
@@ -31,6 +32,34 @@ int gp_ensure_scratch(gp_ctx* ctx, size_t bytes) {
   ctx->scratch_bytes = bytes;
   return GP_OK;
 }
+
+// ---- scratch of gp_kmv_static -------------------------------------------------------------------
+// A file-scope device array instead of an allocation: every GPU the library runs on holds its own
+// copy from the moment the code object is loaded until the process ends.  In host code the array's
+// name is only a stand-in for the symbol, not a device address; the address on a given device comes
+// from hipGetSymbolAddress with that device current, and only that pointer is ever handed to kernels.
+static __device__ __align__(256) unsigned char scratch[GP_KMV_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int GP_MAX_DEVICES = 64;
+std::mutex g_static_lock;
+void* g_static_ptr[GP_MAX_DEVICES];   // per device: where `scratch` lives there (NULL until resolved)
+
+// Address of the static scratch on device `dev`, which must be the current device; resolved once.
+hipError_t static_scratch_on(int dev, void** out) {
+  *out = nullptr;
+  if (dev < 0 || dev >= GP_MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> hold(g_static_lock);
+  if (!g_static_ptr[dev]) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_static_ptr[dev] = ptr;
+  }
+  *out = g_static_ptr[dev];
+  return hipSuccess;
+}
+}  // namespace
 
 extern "C" {
 
@@ -70,6 +99,7 @@ int gp_create(gp_ctx** out, int kernel, int64_t n, int d, const float* dX, void*
   ctx->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
     return gp_fail(ctx, GP_ERR_HIP, "libgpws is built for gfx950 only, device is %s", prop.gcnArchName);
+  GP_HIP(ctx, static_scratch_on(dev, &ctx->static_scratch));
 
   const size_t packed = ((size_t)(ctx->n_pad / GP_CHUNK) * ctx->KS * 64 + GP_PACK_SLACK) * sizeof(float);
   GP_HIP(ctx, hipMalloc((void**)&ctx->dXA, packed));
@@ -178,22 +208,38 @@ static int check_block(gp_ctx* ctx, const char* who, const void* p, int64_t ld, 
   return GP_OK;
 }
 
-int gp_kmv(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo, int add_noise) {
+// argument checks shared by gp_kmv and gp_kmv_static
+static int kmv_check(gp_ctx* ctx, const char* who, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo) {
   if (!ctx) return GP_ERR_ARG;
-  if (!ctx->theta_set) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: gp_set_theta has not been called");
-  if (t < 1 || t > GP_MAX_T) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: t = %d outside [1, %d]", t, GP_MAX_T);
+  if (!ctx->theta_set) return gp_fail(ctx, GP_ERR_ARG, "%s: gp_set_theta has not been called", who);
+  if (t < 1 || t > GP_MAX_T) return gp_fail(ctx, GP_ERR_ARG, "%s: t = %d outside [1, %d]", who, t, GP_MAX_T);
   int rc;
-  if ((rc = check_block(ctx, "gp_kmv(dV)", dV, ldv, t)) < 0) return rc;
-  if ((rc = check_block(ctx, "gp_kmv(dOut)", dOut, ldo, t)) < 0) return rc;
-  {
-    // byte ranges the two blocks span (last row ends after t elements, not after a full leading dimension)
-    const uintptr_t v0 = (uintptr_t)dV, v1 = v0 + ((size_t)(ctx->n - 1) * (size_t)ldv + (size_t)t) * sizeof(float);
-    const uintptr_t o0 = (uintptr_t)dOut, o1 = o0 + ((size_t)(ctx->n - 1) * (size_t)ldo + (size_t)t) * sizeof(float);
-    if (v0 < o1 && o0 < v1) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: dOut overlaps dV");
-  }
+  if ((rc = check_block(ctx, who, dV, ldv, t)) < 0) return rc;
+  if ((rc = check_block(ctx, who, dOut, ldo, t)) < 0) return rc;
+  // byte ranges the two blocks span (last row ends after t elements, not after a full leading dimension)
+  const uintptr_t v0 = (uintptr_t)dV, v1 = v0 + ((size_t)(ctx->n - 1) * (size_t)ldv + (size_t)t) * sizeof(float);
+  const uintptr_t o0 = (uintptr_t)dOut, o1 = o0 + ((size_t)(ctx->n - 1) * (size_t)ldo + (size_t)t) * sizeof(float);
+  if (v0 < o1 && o0 < v1) return gp_fail(ctx, GP_ERR_ARG, "%s: dOut overlaps dV", who);
+  return GP_OK;
+}
+
+int gp_kmv(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo, int add_noise) {
+  int rc = kmv_check(ctx, "gp_kmv", dV, ldv, t, dOut, ldo);
+  if (rc < 0) return rc;
   const size_t need = gp_kmv_scratch_bytes(ctx, t);
   if ((rc = gp_ensure_scratch(ctx, need)) < 0) return rc;
   return gp_kmv_launch(ctx, dV, ldv, t, dOut, ldo, add_noise ? 1 : 0, ctx->dScratch, ctx->scratch_bytes, nullptr);
+}
+
+int gp_kmv_static(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo, int add_noise) {
+  int rc = kmv_check(ctx, "gp_kmv_static", dV, ldv, t, dOut, ldo);
+  if (rc < 0) return rc;
+  if (!ctx->static_scratch) return gp_fail(ctx, GP_ERR_HIP, "gp_kmv_static: the static scratch was not resolved on this device");
+  const size_t need = gp_kmv_scratch_bytes(ctx, t);
+  if (need > (size_t)GP_KMV_STATIC_SCRATCH_BYTES)
+    return gp_fail(ctx, GP_ERR_WORKSPACE, "gp_kmv_static: n = %lld, t = %d need %zu bytes of scratch, the static block holds %zu; use gp_kmv",
+                   (long long)ctx->n, t, need, (size_t)GP_KMV_STATIC_SCRATCH_BYTES);
+  return gp_kmv_launch(ctx, dV, ldv, t, dOut, ldo, add_noise ? 1 : 0, ctx->static_scratch, (size_t)GP_KMV_STATIC_SCRATCH_BYTES, nullptr);
 }
 
 int gp_predict(gp_ctx* ctx, const float* dXstar, int64_t m, const float* dV, int64_t ldv, int t, float* dOut,

@@ -78,6 +78,7 @@ struct gp_ctx {
   // lazily grown scratch for split-column partial sums of gp_kmv / gp_mll_grad
   void* dScratch;
   size_t scratch_bytes;
+  void* static_scratch;   // this device's address of the file-scope scratch gp_kmv_static uses (never freed)
   // small device + pinned host blocks for scalars
   double* dRed;           // reduction partials
   size_t red_bytes;

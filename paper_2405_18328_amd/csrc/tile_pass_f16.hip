@@ -435,6 +435,16 @@ __global__ __launch_bounds__(256) void colmax_kernel(const float* __restrict__ V
     if (smax[c]) atomicMax(&colmax[c], smax[c]);
 }
 
+// zeroes t words of one or two arrays (a kernel, not a memset command: memset nodes recorded into a
+// captured graph have misbehaved on replay, and gp_kmv_static must be capturable)
+__global__ __launch_bounds__(256) void clear_words_kernel(unsigned* __restrict__ a, unsigned* __restrict__ b, int t) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c < t) {
+    a[c] = 0u;
+    if (b) b[c] = 0u;
+  }
+}
+
 // V' images of one column pass: unit u = ((chunk*2 + mh)*NT + nt)*2 + part, lane l: element e is
 // V'[32 chunk + 16 mh + 8 (e/4) + 4 (l/32) + e%4][col0 + 32 nt + l%32]; rows >= n and columns past the pass are zero.
 __global__ __launch_bounds__(256) void pack_v_kernel(const float* __restrict__ V, int64_t ldv, int64_t n, int nchunks,
@@ -578,8 +588,8 @@ KmvPlan gp_plan_kmv_f16(const gp_ctx* ctx, int64_t rows, int64_t col_chunks) {
 int gp_launch_colmax(gp_ctx* ctx, const float* dV, int64_t ldv, int t, unsigned* cm, const float* dV2, int64_t ldv2,
                      unsigned* cm2, bool cleared) {
   if (!cleared) {
-    GP_HIP(ctx, hipMemsetAsync(cm, 0, (size_t)t * sizeof(unsigned), ctx->stream));
-    if (dV2) GP_HIP(ctx, hipMemsetAsync(cm2, 0, (size_t)t * sizeof(unsigned), ctx->stream));
+    hipLaunchKernelGGL(clear_words_kernel, dim3((t + 255) / 256), dim3(256), 0, ctx->stream, cm, dV2 ? cm2 : nullptr, t);
+    GP_HIP(ctx, hipGetLastError());
   }
   // few workgroups: every one ends with t atomic maxima on the same t words
   int blocks = (int)((ctx->n * (int64_t)t + 8191) / 8192);
