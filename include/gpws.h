@@ -236,17 +236,29 @@ int gp_predict(gp_ctx* ctx, const float* dXstar, int64_t m, const float* dV, int
                int64_t ldo);
 
 /*
- * Instrumentation for roofline reports (not part of the method): while enabled,
- * every launch of the K V tile-pass kernel made through this context (by gp_kmv
- * or inside gp_cg_solve) is bracketed by a pair of HIP events on the context's
- * stream.  gp_profile(ctx, 1) resets the counters and starts recording,
- * gp_profile(ctx, 0) stops.  gp_profile_read synchronises the stream and returns
- * the number of bracketed launches and the sum of their durations in
- * milliseconds (at most 8192 launches are recorded per enable; later ones are
- * not counted).  Either output pointer may be NULL.
+ * Instrumentation for roofline reports (not part of the method): while enabled, every launch of
+ * the chosen kinds of kernel made through this context is bracketed by a pair of HIP events on the
+ * context's stream.  gp_profile(ctx, mask) resets the counters and starts recording the kinds whose
+ * bit (1 << GP_PROF_*) is set in mask -- mask 1 records the K V tile-pass kernel only, whether
+ * launched by gp_kmv, gp_predict or inside a solver; gp_profile(ctx, 0) stops.
+ * gp_profile_read_kind synchronises the stream and returns the number of bracketed launches of
+ * one kind and the sum of their durations in milliseconds; gp_profile_read is the same for
+ * GP_PROF_TILE.  At most 8192 launches are recorded per enable, later ones are not counted.
+ * Either output pointer may be NULL.  Bracketing costs a few microseconds per launch, which
+ * shows in the wall time of latency-bound solves: record the small kernels only where the
+ * measurement is about them.
  */
+enum {
+  GP_PROF_TILE = 0,      /* K V tile pass (either arithmetic path) */
+  GP_PROF_CG_DOT = 1,    /* gp_cg_solve: p^T (H p) */
+  GP_PROF_CG_XR = 2,     /* gp_cg_solve: x += alpha p, r -= alpha H p, r^T r */
+  GP_PROF_CG_P = 3,      /* gp_cg_solve: p = r + beta p */
+  GP_PROF_GRAD_TILE = 4, /* gp_mll_grad: the gradient tile pass */
+  GP_PROF_KINDS = 5
+};
 int gp_profile(gp_ctx* ctx, int enable);
 int gp_profile_read(gp_ctx* ctx, int* h_launches, double* h_total_ms);
+int gp_profile_read_kind(gp_ctx* ctx, int kind, int* h_launches, double* h_total_ms);
 
 /*
  * Which arithmetic the K V tile pass uses for the current theta (Section 2.1 leaves the

@@ -31,7 +31,7 @@ LIB_PATH = os.environ.get("GPWS_LIB") or os.path.join(os.path.dirname(os.path.ab
 GP_AP_MAX_BLOCK = 2048
 
 EXPORTS = ["gp_create", "gp_destroy", "gp_set_theta", "gp_kmv", "gp_kmv_static", "gp_workspace_bytes", "gp_cg_solve",
-           "gp_ap_workspace_bytes", "gp_ap_solve", "gp_sgd_workspace_bytes", "gp_sgd_solve", "gp_mll_grad", "gp_predict", "gp_profile", "gp_profile_read", "gp_product_path", "gp_last_error"]
+           "gp_ap_workspace_bytes", "gp_ap_solve", "gp_sgd_workspace_bytes", "gp_sgd_solve", "gp_mll_grad", "gp_predict", "gp_profile", "gp_profile_read", "gp_profile_read_kind", "gp_product_path", "gp_last_error"]
 
 
 def _load():
@@ -60,6 +60,7 @@ def _load():
     lib.gp_predict.argtypes = [p, p, i64, p, i64, i32, p, i64]
     lib.gp_profile.argtypes = [p, i32]
     lib.gp_profile_read.argtypes = [p, C.POINTER(i32), C.POINTER(dbl)]
+    lib.gp_profile_read_kind.argtypes = [p, i32, C.POINTER(i32), C.POINTER(dbl)]
     lib.gp_product_path.argtypes = [p]
     lib.gp_last_error.argtypes = [p]
     lib.gp_last_error.restype = C.c_char_p
@@ -204,6 +205,17 @@ def gp_product_path(ctx):
     if rc < 0:
         raise GpError(rc, "gp_product_path: no theta set")
     return rc
+
+
+GP_PROF_TILE, GP_PROF_CG_DOT, GP_PROF_CG_XR, GP_PROF_CG_P, GP_PROF_GRAD_TILE = range(5)
+GP_PROF_KINDS = 5
+
+
+def gp_profile_read_kind(ctx, kind):
+    """Returns (launches, total_ms) of the bracketed launches of one kind (GP_PROF_*)."""
+    n, ms = C.c_int(0), C.c_double(0.0)
+    _check(ctx, _lib.gp_profile_read_kind(ctx, int(kind), C.byref(n), C.byref(ms)))
+    return n.value, ms.value
 
 
 def gp_profile_read(ctx):

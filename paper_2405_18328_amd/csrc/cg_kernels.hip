@@ -535,13 +535,19 @@ int gp_cg_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     int rc = gp_kmv_launch(ctx, P, t, t, HP, t, 1, kmv_scratch, L.kmv_bytes, s.colmax, nullptr, &df);
     if (rc < 0) return drained(rc);
     ++kmv_count;
+    bool pr = gp_prof_begin(ctx, GP_PROF_CG_DOT);
     hipLaunchKernelGGL(cg_dot_kernel, grid, block, 0, st, (const float*)P, HP, df.part, df.stride, df.JS,
                        ctx->n * (int64_t)t, total, t, s.flags, s.part);
+    gp_prof_end(ctx, pr);
     hipLaunchKernelGGL(cg_fin_alpha_kernel, dim3(1), dim3(FT), 0, st, s, L.G, t);
+    pr = gp_prof_begin(ctx, GP_PROF_CG_XR);
     hipLaunchKernelGGL(cg_update_xr_kernel, grid, block, 0, st, X, R, (const float*)P, (const float*)HP, total, t,
                        (const float*)s.alpha, s.flags, s.part);
+    gp_prof_end(ctx, pr);
     hipLaunchKernelGGL(cg_fin_beta_kernel, dim3(1), dim3(FT), 0, st, s, L.G, t);
+    pr = gp_prof_begin(ctx, GP_PROF_CG_P);
     hipLaunchKernelGGL(cg_update_p_kernel, grid, block, 0, st, P, (const float*)R, total, t, (const float*)s.beta, s.flags, s.colmax);
+    gp_prof_end(ctx, pr);
     GP_HIP(ctx, hipGetLastError());
     rc = wait_seq(it + 2);
     if (rc < 0) return drained(rc);

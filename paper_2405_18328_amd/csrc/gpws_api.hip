@@ -145,6 +145,7 @@ int gp_destroy(gp_ctx* ctx) {
     for (int i = 0; i < 2 * GP_PROF_MAX; ++i) (void)hipEventDestroy(ctx->prof_ev[i]);
     delete[] ctx->prof_ev;
   }
+  delete[] ctx->prof_kind;
   delete ctx;
   return GP_OK;
 }
@@ -354,13 +355,15 @@ int gp_mll_grad(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int6
 
 int gp_profile(gp_ctx* ctx, int enable) {
   if (!ctx) return GP_ERR_ARG;
+  if (enable < 0 || enable >= (1 << GP_PROF_KINDS)) return gp_fail(ctx, GP_ERR_ARG, "gp_profile: unknown kinds in mask %d", enable);
   if (enable && !ctx->prof_ev) {
     ctx->prof_ev = new (std::nothrow) hipEvent_t[2 * GP_PROF_MAX];
-    if (!ctx->prof_ev) return gp_fail(ctx, GP_ERR_ARG, "gp_profile: out of host memory");
+    ctx->prof_kind = new (std::nothrow) unsigned char[GP_PROF_MAX];
+    if (!ctx->prof_ev || !ctx->prof_kind) return gp_fail(ctx, GP_ERR_ARG, "gp_profile: out of host memory");
     for (int i = 0; i < 2 * GP_PROF_MAX; ++i) GP_HIP(ctx, hipEventCreate(&ctx->prof_ev[i]));
   }
   if (enable) ctx->prof_count = 0;
-  ctx->prof_on = enable != 0;
+  ctx->prof_mask = (unsigned)enable;
   return GP_OK;
 }
 
@@ -369,18 +372,26 @@ int gp_product_path(const gp_ctx* ctx) {
   return ctx->path;
 }
 
-int gp_profile_read(gp_ctx* ctx, int* h_launches, double* h_total_ms) {
+int gp_profile_read_kind(gp_ctx* ctx, int kind, int* h_launches, double* h_total_ms) {
   if (!ctx) return GP_ERR_ARG;
+  if (kind < 0 || kind >= GP_PROF_KINDS) return gp_fail(ctx, GP_ERR_ARG, "gp_profile_read_kind: kind %d", kind);
   GP_HIP(ctx, hipStreamSynchronize(ctx->stream));
   double tot = 0.0;
+  int count = 0;
   for (int i = 0; i < ctx->prof_count; ++i) {
+    if (ctx->prof_kind[i] != kind) continue;
     float ms = 0.0f;
     GP_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]));
     tot += (double)ms;
+    ++count;
   }
-  if (h_launches) *h_launches = ctx->prof_count;
+  if (h_launches) *h_launches = count;
   if (h_total_ms) *h_total_ms = tot;
   return GP_OK;
+}
+
+int gp_profile_read(gp_ctx* ctx, int* h_launches, double* h_total_ms) {
+  return gp_profile_read_kind(ctx, GP_PROF_TILE, h_launches, h_total_ms);
 }
 
 const char* gp_last_error(const gp_ctx* ctx) { return ctx ? ctx->err : "NULL context"; }

@@ -86,10 +86,12 @@ struct gp_ctx {
   void* dPinned;          // the same block as the device addresses it (kernels post small results there)
   size_t pinned_bytes;
   int num_cu;
-  // event pairs bracketing tile-pass launches while profiling is on
-  bool prof_on;
+  // event pairs bracketing kernel launches while profiling is on (gp_profile): prof_mask has bit k set
+  // when launches of kind k (GP_PROF_* of gpws.h) are bracketed
+  unsigned prof_mask;
   int prof_count;
   hipEvent_t* prof_ev;    // 2 * GP_PROF_MAX events, created on first enable
+  unsigned char* prof_kind;   // kind of every recorded pair
   char err[256];
 };
 
@@ -127,6 +129,19 @@ int gp_fail(gp_ctx* ctx, int code, const char* fmt, ...);
     if (e__ != hipSuccess)                                                             \
       return gp_fail(ctx, GP_ERR_HIP, "%s failed: %s", #call, hipGetErrorString(e__)); \
   } while (0)
+
+// Bracket one kernel launch of the given kind with an event pair when that kind is being profiled:
+//   const bool pr = gp_prof_begin(ctx, kind);  launch;  gp_prof_end(ctx, pr);
+inline bool gp_prof_begin(gp_ctx* ctx, int kind) {
+  if (!((ctx->prof_mask >> kind) & 1u) || ctx->prof_count >= GP_PROF_MAX) return false;
+  if (hipEventRecord(ctx->prof_ev[2 * ctx->prof_count], ctx->stream) != hipSuccess) return false;
+  ctx->prof_kind[ctx->prof_count] = (unsigned char)kind;
+  return true;
+}
+inline void gp_prof_end(gp_ctx* ctx, bool begun) {
+  if (!begun) return;
+  if (hipEventRecord(ctx->prof_ev[2 * ctx->prof_count + 1], ctx->stream) == hipSuccess) ++ctx->prof_count;
+}
 
 int gp_ks_bucket(int d);   // -1 if d is out of range
 int gp_ensure_scratch(gp_ctx* ctx, size_t bytes);

@@ -459,7 +459,9 @@ int gp_grad_run(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, int6
       grad_fn fn = ctx->kernel == GP_SE_ARD ? pick_grad<GP_SE_ARD>(ctx->KS, KT, NT)
                                             : pick_grad<GP_MATERN32_ARD>(ctx->KS, KT, NT);
       if (!fn) return gp_fail(ctx, GP_ERR_ARG, "gp_mll_grad: no kernel for KS=%d", ctx->KS);
+      const bool pr = gp_prof_begin(ctx, GP_PROF_GRAD_TILE);
       hipLaunchKernelGGL(fn, grid, block, 0, st, a);
+      gp_prof_end(ctx, pr);
       GP_HIP(ctx, hipGetLastError());
       c += a.ncols;
     }

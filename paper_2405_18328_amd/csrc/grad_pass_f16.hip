@@ -578,7 +578,9 @@ int gp_grad_run_f16(gp_ctx* ctx, const float* dV, int64_t ldv, const float* dB, 
       }
       gradh_fn fn = pick_gradh(ctx->kernel, ctx->KH, ctx->XP, KT, NT);
       if (!fn) return gp_fail(ctx, GP_ERR_ARG, "gp_mll_grad: no fp16 kernel for KH=%d", ctx->KH);
+      const bool pr = gp_prof_begin(ctx, GP_PROF_GRAD_TILE);
       hipLaunchKernelGGL(fn, grid, block, 0, st, a);
+      gp_prof_end(ctx, pr);
       GP_HIP(ctx, hipGetLastError());
       c += a.ncols;
     }

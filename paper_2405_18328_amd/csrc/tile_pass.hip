@@ -379,14 +379,10 @@ int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut,
     tile_fn fn = ctx->kernel == GP_SE_ARD ? pick_ks<GP_SE_ARD>(ctx->KS, NT, pl.MI)
                                           : pick_ks<GP_MATERN32_ARD>(ctx->KS, NT, pl.MI);
     if (!fn) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: no kernel for KS=%d", ctx->KS);
-    const bool prof = ctx->prof_on && ctx->prof_count < GP_PROF_MAX;
-    if (prof) GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count], ctx->stream));
+    const bool prof = gp_prof_begin(ctx, GP_PROF_TILE);
     hipLaunchKernelGGL(fn, grid, block, 0, ctx->stream, a);
     GP_HIP(ctx, hipGetLastError());
-    if (prof) {
-      GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count + 1], ctx->stream));
-      ++ctx->prof_count;
-    }
+    gp_prof_end(ctx, prof);
     c += a.ncols;
   }
   if (defer) {

@@ -674,14 +674,10 @@ int gp_kmv_launch_f16(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* d
     vcol = -1;
     tileh_fn fn = pick_h(ctx->kernel, ctx->KH, XP, NT, pl.MI, pl.W);
     if (!fn) return gp_fail(ctx, GP_ERR_ARG, "gp_kmv: no fp16 kernel for KH=%d", ctx->KH);
-    const bool prof = ctx->prof_on && ctx->prof_count < GP_PROF_MAX;
-    if (prof) GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count], st));
+    const bool prof = gp_prof_begin(ctx, GP_PROF_TILE);
     hipLaunchKernelGGL(fn, grid, block, 0, st, a);
     GP_HIP(ctx, hipGetLastError());
-    if (prof) {
-      GP_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_count + 1], st));
-      ++ctx->prof_count;
-    }
+    gp_prof_end(ctx, prof);
     c += a.ncols;
   }
   if (defer) {

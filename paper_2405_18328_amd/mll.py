@@ -66,6 +66,7 @@ class StepRecord:
     step_ms: float
     max_relres: float
     grad: np.ndarray = field(repr=False, default=None)
+    relres: np.ndarray = field(repr=False, default=None)    # final relative residual of every column
 
 
 class MllOptimizer:
@@ -157,6 +158,6 @@ class MllOptimizer:
         self.adam.ascend(g)
         t4 = time.perf_counter()
         rec = StepRecord(theta, iters, kmv, rc, (t2 - t1) * 1e3, (t3 - t2) * 1e3, (t4 - t0) * 1e3,
-                         float(relres.max()), g)
+                         float(relres.max()), g, np.array(relres, dtype=np.float64))
         self.history.append(rec)
         return rec
