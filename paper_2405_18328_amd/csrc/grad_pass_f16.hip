@@ -222,25 +222,19 @@ __global__ __launch_bounds__(256) void grad_tile_f16_kernel(GradArgsH p) {
       S = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0], xb[1][kh], S, 0, 0, 0);
       S = __builtin_amdgcn_mfma_f32_32x32x16_f16(xa[0], xb[0][kh], S, 0, 0, 0);
     }
-    // Largest terms first, on purpose.  This matrix instruction rounds to nearest when its accumulator
-    // input is the largest addend, but an accumulator input smaller than the products is cut off below
-    // half a unit in the last place of the result toward minus infinity (measured on MI355X).  Small
-    // cross terms summed first and the hi*hi products added on top of them would give every w_ij a bias
-    // of about -2^-25 |w_ij| of one sign, which the sum over all pairs does not average out while the
-    // terms themselves cancel (V nearly orthogonal to K's large eigenvectors, as after a solve).
-    {
-      f16x8 chs[KT];
+    // Per k-step the hi*hi products first, on purpose.  This matrix instruction rounds to nearest when
+    // its accumulator input is the largest addend, but an accumulator input smaller than the products is
+    // cut off below half a unit in the last place of the result toward minus infinity (measured on
+    // MI355X).  Small cross terms summed first and the hi*hi products added on top of them would give
+    // every w_ij a bias of about -2^-25 |w_ij| of one sign, which the sum over all pairs does not average
+    // out while the terms themselves cancel (V nearly orthogonal to K's large eigenvectors, as after a solve).
 #pragma unroll
-      for (int kt = 0; kt < KT; ++kt) {
-        chs[kt] = as_f16x8(s[C_OFF + (0 * KT + kt) * 64 + lane]);
-        Wc = __builtin_amdgcn_mfma_f32_32x32x16_f16(chs[kt], abh[kt], Wc, 0, 0, 0);
-      }
-#pragma unroll
-      for (int kt = 0; kt < KT; ++kt) {
-        const f16x8 cl_ = as_f16x8(s[C_OFF + (1 * KT + kt) * 64 + lane]);
-        Wc = __builtin_amdgcn_mfma_f32_32x32x16_f16(chs[kt], abl[kt], Wc, 0, 0, 0);
-        Wc = __builtin_amdgcn_mfma_f32_32x32x16_f16(cl_, abh[kt], Wc, 0, 0, 0);
-      }
+    for (int kt = 0; kt < KT; ++kt) {
+      const f16x8 ch_ = as_f16x8(s[C_OFF + (0 * KT + kt) * 64 + lane]);
+      const f16x8 cl_ = as_f16x8(s[C_OFF + (1 * KT + kt) * 64 + lane]);
+      Wc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ch_, abh[kt], Wc, 0, 0, 0);
+      Wc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ch_, abl[kt], Wc, 0, 0, 0);
+      Wc = __builtin_amdgcn_mfma_f32_32x32x16_f16(cl_, abh[kt], Wc, 0, 0, 0);
     }
     if (ch == sub0) {   // the pair (i, i): r^2 = 0 exactly
       asm volatile("" ::: "memory");   // keeps this a real (wave-uniform) branch instead of selects on every chunk
