@@ -139,9 +139,8 @@ __global__ __launch_bounds__(256) void grad_tile_f16_kernel(GradArgsH p) {
   // inline assembly keeps the ordering explicit (s_waitcnt vmcnt(N) + barrier) instead of the
   // compiler's conservative drain of all LDS-DMA loads at every barrier; m0 is restored
   auto dma16 = [](const u32x4* src, unsigned lds_addr) {
-    unsigned saved_m0;
-    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
-                 : "=&s"(saved_m0) : "v"(src), "s"(lds_addr) : "memory");
+    // m0 carries the LDS address of the load; it is declared clobbered, so the compiler keeps nothing in it
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "memory", "m0");
   };
   auto issue_chunk = [&](int ch_target) {
     const int ch = min(ch_target, c_end - 1);           // past the end: harmless reload of the last chunk

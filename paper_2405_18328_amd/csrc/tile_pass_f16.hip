@@ -158,9 +158,8 @@ __global__ __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   for (int x = 0; x < LPW; ++x) g_lds[x] = __builtin_amdgcn_readfirstlane(lds_base + 16u * (unsigned)g_off[x]);
   const unsigned vy_lds = __builtin_amdgcn_readfirstlane(lds_base + 16u * (unsigned)(VY_OFF + 8 * wave));
   auto dma16 = [](const u32x4* src, unsigned lds_addr) {
-    unsigned saved_m0;   // m0 is restored, so the compiler's own uses of it are undisturbed
-    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
-                 : "=&s"(saved_m0) : "v"(src), "s"(lds_addr) : "memory");
+    // m0 carries the LDS address of the load; it is declared clobbered, so the compiler keeps nothing in it
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr) : "memory", "m0");
   };
   auto issue_chunk = [&](int ch_target) {
     const int ch = min(ch_target, c_end - 1);           // past the end: harmless reload of the last chunk
