@@ -26,7 +26,6 @@ namespace {
 
 constexpr int TS = 64;              // tile edge of the factorisation kernels
 constexpr int AP_BATCH = 64;        // blocks factorised side by side (3 x 32 MiB of fp64 scratch each at block 2000)
-constexpr int SOLVE_KSPLIT = 16;    // ranges of the contraction index in the block solve
 
 typedef double fac_t;
 
@@ -51,6 +50,8 @@ struct ApDev {
   double* norms;    // [nb][S][t] squared residual norms per block slice
   double* normsB;   // [nb][S][t] the same for B (init only)
   double* bnorm;    // [nb][t] squared residual norms per block (finalise kernel's scratch)
+  double* bnormB;   // [nb][t] the same for B (init only)
+  unsigned* ticket; // workgroups of the finalise kernel that are through with their block sums
 };
 
 // ---- 64 x 64 tile products on the fp64 matrix cores ---------------------------------------------
@@ -462,7 +463,12 @@ __global__ __launch_bounds__(256) void ap_trinv_merge_kernel(const fac_t* __rest
     for (int v = 0; v < 4; ++v) out[(int64_t)acc_row(v) * BP + acc_col(cb)] = sign * acc.b[cb][v];
 }
 
-// H[I,I]^-1 = X^T X, tiles (ti >= tj) and their mirror images, rounded to fp32
+// H[I,I]^-1 = X^T X, tiles (ti >= tj) and their mirror images, rounded to fp32.  The inverse is stored in
+// panels of 32 rows, contraction index major inside a panel: element (r, c) at
+// ((r / 32) BP + c) 32 + r % 32, so that what the block solve reads for one row tile and a range of
+// the contraction index c is one contiguous stretch of memory (128 bytes per c), not 64-byte pieces
+// 4 BP bytes apart.
+__device__ __forceinline__ int64_t hinv_at(int r, int c, int BP) { return ((int64_t)(r >> 5) * BP + c) * 32 + (r & 31); }
 __global__ __launch_bounds__(256) void ap_lauum_kernel(const fac_t* __restrict__ W, int BP, float* __restrict__ Hinv) {
   __shared__ Tile TA, TB;
   if (blockIdx.x > blockIdx.y) return;
@@ -485,8 +491,8 @@ __global__ __launch_bounds__(256) void ap_lauum_kernel(const fac_t* __restrict__
     for (int v = 0; v < 4; ++v) {
       const int r = ti * TS + acc_row(v), c = tj * TS + acc_col(cb);
       const float val = (float)acc.b[cb][v];
-      Hb[(int64_t)r * BP + c] = val;
-      Hb[(int64_t)c * BP + r] = val;
+      Hb[hinv_at(r, c, BP)] = val;
+      Hb[hinv_at(c, r, BP)] = val;
     }
 }
 
@@ -537,155 +543,247 @@ __global__ __launch_bounds__(256) void ap_init_kernel(const float* __restrict__ 
   }
 }
 
-// d = H[I,I]^-1 R[I,:] in two launches.  First, partial products over SOLVE_KSPLIT ranges of the
-// contraction index m: the inverse is symmetric, so row i of it is read as column i, lane = row, one
-// coalesced load per m, while the R values of a wave's 16 columns are the same for all its lanes
-// (scalar loads).  Grid (BP / 64 row tiles, SOLVE_KSPLIT, ceil(t / 256)); a workgroup has one wave per
-// 16 columns, up to 16 waves.  A wave whose 16 columns would run past t moves its window left (the
-// overlap is computed twice and stored once); t < 16 takes the guarded loop.
-__global__ __launch_bounds__(1024) void ap_solve_partial_kernel(const float* __restrict__ Hinv, int BP, int bs,
-                                                                const float* __restrict__ R, int64_t j0, int t,
-                                                                int kper, float* __restrict__ part) {
+// d = H[I,I]^-1 R[I,:], columns no longer updated set to 0, written to rows j0 .. j0 + bs - 1 of D, and
+// the columns' largest |d| to colmax (zero on entry).  One workgroup per 16 x 16 tile of d, on the fp32
+// matrix cores (v_mfma_f32_16x16x4_f32: A operand lane l holds A[l % 16][l / 16], B operand
+// B[l / 16][l % 16], result register v of lane l is D[4 (l / 16) + v][l % 16]).  The inverse is
+// symmetric and stored in 32-row panels (see ap_lauum_kernel): the A operand of contraction index m is
+// 16 consecutive floats, and consecutive m are 128 bytes apart.  The contraction index is cut into SOLVE_WAVES ranges, one per
+// wave of the workgroup, whose partial tiles are added in a fixed order through LDS; nothing is
+// exchanged between workgroups.  Every operand load is unconditional (out-of-range indices are
+// clamped and the value replaced by zero when it is used), so that a wave keeps two batches of
+// SOLVE_U operand pairs in flight and waits only for the older one.
+// Workgroups are numbered so that the 2 ceil(t / 16) tiles that read the same 128-byte lines of the
+// inverse (two neighbouring row tiles, all column tiles) follow each other on one XCD (workgroup w
+// runs on XCD w % 8): the 4 BP^2 bytes of the inverse then come from memory once, not once per XCD.
+typedef float f4 __attribute__((ext_vector_type(4)));
+constexpr int SOLVE_WAVES = 8;
+constexpr int SOLVE_U = 16;         // matrix instructions per batch of operand loads
+constexpr int XCDS = 8;
+
+__global__ __launch_bounds__(64 * SOLVE_WAVES) void ap_block_solve_kernel(const float* __restrict__ Hinv, int BP, int bs,
+                                                                         const float* __restrict__ R, int64_t j0,
+                                                                         int t, const int* __restrict__ frozen,
+                                                                         float* __restrict__ D,
+                                                                         unsigned* __restrict__ colmax) {
+  __shared__ f4 red[SOLVE_WAVES][64];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int i = blockIdx.x * 64 + lane;
-  const int c_first = blockIdx.z * 256 + wave * 16;      // first column this wave has to deliver
-  if (c_first >= t) return;
-  const int c0 = (t >= 16 && c_first + 16 > t) ? t - 16 : c_first;   // first column it computes
-  const int skip = c_first - c0;
-  const int ncol = t - c0 < 16 ? t - c0 : 16;
-  const int m0 = blockIdx.y * kper;
-  const int m1 = m0 + kper < bs ? m0 + kper : bs;
-  float acc[16];
+  const int lo = lane & 15, hi = lane >> 4;
+  const int CT = (t + 15) / 16, RT = (bs + 15) / 16;
+  const int g = blockIdx.x / XCDS;
+  const int pair = (g / (2 * CT)) * XCDS + blockIdx.x % XCDS;
+  const int member = g % (2 * CT);
+  const int rt = 2 * pair + (member & 1);
+  if (rt >= RT) return;
+  const int row0 = 16 * rt;
+  const int c = 16 * (member >> 1) + lo;
+  const bool cok = c < t;
+  const bool live = cok && !frozen[c];
+  float* Drow = D + (j0 + row0 + 4 * hi) * t + c;      // this lane's first output element
+  if (!__any(live)) {                                  // every column of the tile has converged
+    if (wave == 0 && cok) {
 #pragma unroll
-  for (int q = 0; q < 16; ++q) acc[q] = 0.0f;
-  const float* hp = Hinv + (int64_t)m0 * BP + i;
-  const float* rp = R + (j0 + m0) * t + c0;
-  if (ncol == 16) {
-#pragma unroll 4
-    for (int m = m0; m < m1; ++m) {
-      const float h = *hp;
-#pragma unroll
-      for (int q = 0; q < 16; ++q) acc[q] = fmaf(h, rp[q], acc[q]);
-      hp += BP;
-      rp += t;
+      for (int v = 0; v < 4; ++v)
+        if (row0 + 4 * hi + v < bs) Drow[(int64_t)v * t] = 0.0f;
     }
-  } else {
-    for (int m = m0; m < m1; ++m) {
-      const float h = *hp;
+    return;
+  }
+  const int kw = ((bs + SOLVE_WAVES - 1) / SOLVE_WAVES + 3) & ~3;   // contraction indices per wave, a multiple of 4
+  const int mb = wave * kw;
+  const int me = mb + kw < bs ? mb + kw : bs;
+  const float* ap = Hinv + hinv_at(row0 + lo, 0, BP);   // + 32 m
+  const float* bp = R + j0 * t + (cok ? c : 0);
+  f4 acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (mb < me) {
+    float a0[SOLVE_U], b0[SOLVE_U], a1[SOLVE_U], b1[SOLVE_U];
+    auto fetch = [&](float (&a)[SOLVE_U], float (&b)[SOLVE_U], int ms) {
 #pragma unroll
-      for (int q = 0; q < 16; ++q)
-        if (q < ncol) acc[q] = fmaf(h, rp[q], acc[q]);
-      hp += BP;
-      rp += t;
+      for (int u = 0; u < SOLVE_U; ++u) {
+        const int m = ms + 4 * u + hi;
+        const int mc = m < me ? m : me - 1;
+        a[u] = ap[32 * mc];
+        b[u] = bp[(int64_t)mc * t];
+      }
+    };
+    auto mac = [&](const float (&a)[SOLVE_U], const float (&b)[SOLVE_U], int ms) {
+#pragma unroll
+      for (int u = 0; u < SOLVE_U; u += 2) {
+        const bool ok0 = ms + 4 * u + hi < me, ok1 = ms + 4 * (u + 1) + hi < me;
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(ok0 ? a[u] : 0.0f, (ok0 && cok) ? b[u] : 0.0f, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(ok1 ? a[u + 1] : 0.0f, (ok1 && cok) ? b[u + 1] : 0.0f, acc1, 0, 0, 0);
+      }
+    };
+    fetch(a0, b0, mb);
+    for (int ms = mb; ms < me; ms += 8 * SOLVE_U) {
+      fetch(a1, b1, ms + 4 * SOLVE_U);
+      mac(a0, b0, ms);
+      fetch(a0, b0, ms + 8 * SOLVE_U);
+      mac(a1, b1, ms + 4 * SOLVE_U);
     }
   }
-  if (i < bs) {
-    float* out = part + ((int64_t)blockIdx.y * bs + i) * t + c0;
-#pragma unroll
-    for (int q = 0; q < 16; ++q)
-      if (q >= skip && q < ncol) out[q] = acc[q];
-  }
-}
-
-// Second, the partials summed in a fixed order, columns no longer updated set to 0, the result written
-// to rows j0 .. j0 + bs - 1 of D, and the columns' largest |d| to colmax (zero on entry).
-__global__ __launch_bounds__(256) void ap_solve_reduce_kernel(const float* __restrict__ part, int ksplit, int bs, int t,
-                                                              const int* __restrict__ frozen, int64_t j0,
-                                                              float* __restrict__ D, unsigned* __restrict__ colmax) {
-  __shared__ unsigned smax[GP_MAX_T];
-  for (int c = threadIdx.x; c < t; c += 256) smax[c] = 0u;
+  red[wave][lane] = acc0 + acc1;
   __syncthreads();
-  const int64_t total = (int64_t)bs * t;
-  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-    const int c = (int)(e % t);
-    float v0 = 0.0f, v1 = 0.0f, v2 = 0.0f, v3 = 0.0f;     // four chains so that the loads overlap
-    int k = 0;
-    for (; k + 3 < ksplit; k += 4) {
-      v0 += part[(int64_t)k * total + e];
-      v1 += part[(int64_t)(k + 1) * total + e];
-      v2 += part[(int64_t)(k + 2) * total + e];
-      v3 += part[(int64_t)(k + 3) * total + e];
+  if (wave != 0) return;
+  f4 sum = red[0][lane];
+#pragma unroll
+  for (int w = 1; w < SOLVE_WAVES; ++w) sum += red[w][lane];
+  float big = 0.0f;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const float val = live ? sum[v] : 0.0f;
+    if (cok && row0 + 4 * hi + v < bs) {
+      Drow[(int64_t)v * t] = val;
+      big = fmaxf(big, fabsf(val));
     }
-    for (; k < ksplit; ++k) v0 += part[(int64_t)k * total + e];
-    float v = (v0 + v1) + (v2 + v3);
-    if (frozen[c]) v = 0.0f;
-    D[j0 * t + e] = v;
-    atomicMax(&smax[c], __float_as_uint(fabsf(v)));
   }
-  __syncthreads();
-  for (int c = threadIdx.x; c < t; c += 256)
-    if (smax[c]) atomicMax(&colmax[c], smax[c]);
+  big = fmaxf(big, __shfl_xor(big, 16, 64));
+  big = fmaxf(big, __shfl_xor(big, 32, 64));
+  if (hi == 0 && big > 0.0f) atomicMax(&colmax[c], __float_as_uint(big));
 }
 
 // R -= H[:,I] d (the product's result, column-split partials summed here when JS > 1, plus sigma^2 d
-// on the block's own rows), V[I,:] += d, D[I,:] <- 0, squared residual norms per block slice.
-__global__ __launch_bounds__(256) void ap_update_kernel(float* __restrict__ R, float* __restrict__ V,
-                                                        float* __restrict__ D, const float* __restrict__ OUT,
-                                                        const float* __restrict__ part, int64_t stride, int JS,
-                                                        int64_t n, int t, int block, int S, int64_t j0, int64_t j1,
-                                                        float sigma2, double* __restrict__ norms) {
-  __shared__ float red[256];
-  int64_t r0, r1;
-  slice_rows(n, block, S, &r0, &r1);
-  const ColMap m = col_map(t);
-  for (int cg = 0; cg < t; cg += m.tw) {
-    const int c = cg + m.cl;
-    const bool valid = c < t && m.rl < m.lanes;
-    float acc = 0.0f;
-    if (valid) {
-      for (int64_t i = r0 + m.rl; i < r1; i += m.lanes) {
-        const int64_t e = i * t + c;
-        float hx;
-        if (JS > 1) {
-          hx = 0.0f;
-          for (int q = 0; q < JS; ++q) hx += part[(int64_t)q * stride + e];
-        } else {
-          hx = OUT[e];
-        }
-        if (i >= j0 && i < j1) {
-          const float dl = D[e];
-          hx = fmaf(sigma2, dl, hx);
-          V[e] += dl;
-          D[e] = 0.0f;
-        }
-        const float r = R[e] - hx;
-        R[e] = r;
-        acc = fmaf(r, r, acc);
-      }
+// on the block's own rows), V[I,:] += d, D[I,:] <- 0, squared residual norms per block slice.  A
+// workgroup streams its slice (whole rows, contiguous in memory) as a flat array; the squares go to
+// LDS, where one thread per column adds them up row by row.  All loads of a pass (UPD_U elements per
+// thread, every array) are unconditional and issued before the first use, so a workgroup waits for
+// memory once per pass; a slice lies inside one block, so "own rows" is a property of the workgroup.
+constexpr int UPD_E = 4096;   // elements of a slice between two column-sum passes
+constexpr int UPD_U = 8;
+
+template <int JSC, bool OWN>   // JSC: number of partial images (0: JS of them, any number)
+__device__ __forceinline__ void ap_update_pass(float* __restrict__ R, float* __restrict__ V, float* __restrict__ D,
+                                               const float* __restrict__ src, int64_t stride, int JS, int64_t base,
+                                               int E, int f0, float sigma2, float* sq) {
+  const int tid = threadIdx.x;
+  int64_t e[UPD_U];
+  float hp[JSC > 0 ? JSC : 1][UPD_U], rv[UPD_U], dl[UPD_U], vv[UPD_U];
+#pragma unroll
+  for (int u = 0; u < UPD_U; ++u) {
+    const int f = f0 + tid + 256 * u;
+    e[u] = base + (f < E ? f : E - 1);
+  }
+  if (JSC > 0) {
+#pragma unroll
+    for (int q = 0; q < JSC; ++q)
+#pragma unroll
+      for (int u = 0; u < UPD_U; ++u) hp[q][u] = src[(int64_t)q * stride + e[u]];
+  } else {
+#pragma unroll
+    for (int u = 0; u < UPD_U; ++u) hp[0][u] = 0.0f;
+    for (int q = 0; q < JS; ++q)
+#pragma unroll
+      for (int u = 0; u < UPD_U; ++u) hp[0][u] += src[(int64_t)q * stride + e[u]];
+  }
+#pragma unroll
+  for (int u = 0; u < UPD_U; ++u) {
+    rv[u] = R[e[u]];
+    if (OWN) {
+      dl[u] = D[e[u]];
+      vv[u] = V[e[u]];
     }
-    store_column_sums(m, valid, acc, cg, t, red, norms + (int64_t)blockIdx.x * t);
+  }
+#pragma unroll
+  for (int u = 0; u < UPD_U; ++u) {
+    const int f = f0 + tid + 256 * u;
+    float h = hp[0][u];
+    if (JSC > 1) {
+      h = 0.0f;
+#pragma unroll
+      for (int q = 0; q < JSC; ++q) h += hp[q][u];      // same order as the running sum of the general case
+    }
+    if (OWN) h = fmaf(sigma2, dl[u], h);
+    const float r = rv[u] - h;
+    if (f < E) {
+      if (OWN) {
+        V[e[u]] = vv[u] + dl[u];
+        D[e[u]] = 0.0f;
+      }
+      R[e[u]] = r;
+      sq[f] = r * r;
+    }
   }
 }
 
-// Stopping test per column, choice of the next block, post to the host.  One workgroup of 1024.
-// The slice partials are first summed per (block, column) into bnorm, then per column over the blocks
-// (in 1024 / t segments, combined in a fixed order), so that no thread walks all the partials alone.
-__device__ void ap_column_totals(const double* __restrict__ src, double* bnorm, int nb, int S, int t, double* spart,
-                                 double* scol) {
+template <int JSC>
+__global__ __launch_bounds__(256) void ap_update_kernel(float* __restrict__ R, float* __restrict__ V,
+                                                        float* __restrict__ D, const float* __restrict__ src,
+                                                        int64_t stride, int JS, int64_t n, int t, int block, int S,
+                                                        int ksel, float sigma2, double* __restrict__ norms) {
+  __shared__ float sq[UPD_E];
+  int64_t r0, r1;
+  slice_rows(n, block, S, &r0, &r1);
+  const bool own = (int)(blockIdx.x / S) == ksel;
   const int tid = threadIdx.x;
-  for (int idx = tid; idx < nb * t; idx += 1024) {
-    const int k = idx / t, c = idx - k * t;
-    const double* sp = src + (int64_t)k * S * t + c;
-    double v0 = 0.0, v1 = 0.0, v2 = 0.0, v3 = 0.0;      // four chains so that the loads overlap
-    int q = 0;
-    for (; q + 3 < S; q += 4) {
-      v0 += sp[(int64_t)q * t];
-      v1 += sp[(int64_t)(q + 1) * t];
-      v2 += sp[(int64_t)(q + 2) * t];
-      v3 += sp[(int64_t)(q + 3) * t];
+  constexpr int CG = (GP_MAX_T + 255) / 256;
+  double cs[CG];
+#pragma unroll
+  for (int g = 0; g < CG; ++g) cs[g] = 0.0;
+  const int rows_sub = UPD_E / t;
+  for (int64_t rs = r0; rs < r1; rs += rows_sub) {
+    const int nrow = (int)(rs + rows_sub < r1 ? rows_sub : r1 - rs);
+    const int E = nrow * t;
+    for (int f0 = 0; f0 < E; f0 += 256 * UPD_U) {
+      if (own) ap_update_pass<JSC, true>(R, V, D, src, stride, JS, rs * t, E, f0, sigma2, sq);
+      else ap_update_pass<JSC, false>(R, V, D, src, stride, JS, rs * t, E, f0, sigma2, sq);
     }
-    for (; q < S; ++q) v0 += sp[(int64_t)q * t];
-    bnorm[idx] = (v0 + v1) + (v2 + v3);
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < CG; ++g) {
+      const int c = tid + 256 * g;
+      if (c < t)
+        for (int row = 0; row < nrow; ++row) cs[g] += (double)sq[row * t + c];
+    }
+    __syncthreads();
   }
-  __threadfence();
-  __syncthreads();
-  const int nseg = 1024 / t;                 // t <= 1024
+#pragma unroll
+  for (int g = 0; g < CG; ++g) {
+    const int c = tid + 256 * g;
+    if (c < t) norms[(int64_t)blockIdx.x * t + c] = cs[g];
+  }
+}
+
+// Stopping test per column, choice of the next block, post to the host.  Workgroups of 1024.
+// First every workgroup turns the slice partials of its blocks (k = blockIdx.x, blockIdx.x + gridDim.x,
+// ..) into per-block squared norms bnorm[k][c]: min(S, 1024 / t) threads per column take every so-many-th
+// slice each, and their sums are combined in a fixed order through LDS.  One workgroup alone would have
+// to pull all nb S t partials through a single compute unit.  The workgroup that arrives last at the
+// ticket counter (release fence before the ticket, acquire fence after it; nobody waits for anybody)
+// then sums the blocks per column, applies the stopping rule and picks the next block.
+__device__ void ap_block_sums(const double* __restrict__ src, double* __restrict__ bnorm, int nb, int S, int t,
+                              double* spart) {
+  const int tid = threadIdx.x;
+  int CH = 1024 / t;                       // t <= 1024
+  if (CH > S) CH = S;
+  const int ch = tid / t, c = tid - ch * t;
+  for (int k = blockIdx.x; k < nb; k += gridDim.x) {
+    if (ch < CH) {
+      const double* sp = src + (int64_t)k * S * t + c;
+      double v = 0.0;
+#pragma unroll 4
+      for (int q = ch; q < S; q += CH) v += sp[(int64_t)q * t];
+      spart[ch * t + c] = v;
+    }
+    __syncthreads();
+    if (tid < t) {
+      double v = 0.0;
+      for (int h = 0; h < CH; ++h) v += spart[h * t + tid];
+      bnorm[(int64_t)k * t + tid] = v;
+    }
+    __syncthreads();
+  }
+}
+
+// per-column totals over the blocks, in 1024 / t segments combined in a fixed order
+__device__ void ap_column_totals(const double* bnorm, int nb, int t, double* spart, double* scol) {
+  const int tid = threadIdx.x;
+  const int nseg = 1024 / t;
   const int per = (nb + nseg - 1) / nseg;
   const int seg = tid / t, c = tid - seg * t;
   if (seg < nseg) {
     double v = 0.0;
     const int k1 = (seg + 1) * per < nb ? (seg + 1) * per : nb;
+#pragma unroll 4
     for (int k = seg * per; k < k1; ++k) v += bnorm[(int64_t)k * t + c];
     spart[seg * t + c] = v;
   }
@@ -704,25 +802,33 @@ __global__ __launch_bounds__(1024) void ap_finalise_kernel(ApDev s, int nb, int 
   __shared__ double scol[GP_MAX_T];
   __shared__ int sidx[1024];
   __shared__ int sfrozen[GP_MAX_T];
-  __shared__ int s_any, s_bad;
+  __shared__ int s_any, s_bad, s_last;
   const int tid = threadIdx.x;
+  if (init) ap_block_sums(s.normsB, s.bnormB, nb, S, t, sscore);
+  ap_block_sums(s.norms, s.bnorm, nb, S, t, sscore);
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) s_last = atomicAdd(s.ticket, 1u) == gridDim.x - 1 ? 1 : 0;
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
   if (tid == 0) {
+    *s.ticket = 0u;
     s_any = 0;
     s_bad = *fac_breakdown ? 1 : 0;
   }
   if (init) {
-    ap_column_totals(s.normsB, s.bnorm, nb, S, t, sscore, scol);
+    ap_column_totals(s.bnormB, nb, t, sscore, scol);
     if (tid < t) {
       s.bn2[tid] = scol[tid];
       s.zero_rhs[tid] = (scol[tid] == 0.0) ? 1 : 0;
     }
-    __threadfence();
     __syncthreads();
   }
-  ap_column_totals(s.norms, s.bnorm, nb, S, t, sscore, scol);
+  ap_column_totals(s.bnorm, nb, t, sscore, scol);
   if (tid < t) {
     const int c = tid;
-    const double bn2 = s.bn2[c];
+    const double bn2 = s.bn2[c];          // written by this same thread when init
     const int zero = s.zero_rhs[c];
     int fr = init ? zero : s.frozen[c];
     if (init && zero) s.relres[c] = 0.0f;
@@ -803,7 +909,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct ApLayout {
   int nb, BP, batch, win_chunks, S;
-  size_t off_hinv, off_A, off_W, off_T, off_DI, off_V, off_R, off_D, off_HP, off_SP, off_norms, off_normsB, off_bnorm, off_state, off_kmv, total;
+  size_t off_hinv, off_A, off_W, off_T, off_DI, off_V, off_R, off_D, off_HP, off_norms, off_normsB, off_bnorm, off_bnormB, off_state, off_kmv, total;
   size_t kmv_bytes;
 };
 
@@ -832,10 +938,10 @@ ApLayout ap_layout(const gp_ctx* ctx, int t, int block) {
   L.off_R = o; o += arr;
   L.off_D = o; o += arr;
   L.off_HP = o; o += arr;
-  L.off_SP = o; o += align_up((size_t)SOLVE_KSPLIT * L.BP * t * sizeof(float), 256);
   L.off_norms = o; o += nrm;
   L.off_normsB = o; o += nrm;
   L.off_bnorm = o; o += align_up((size_t)L.nb * t * sizeof(double), 256);
+  L.off_bnormB = o; o += align_up((size_t)L.nb * t * sizeof(double), 256);
   L.off_state = o; o += align_up(sizeof(ApFlags) + 64 + (size_t)t * (sizeof(double) + 2 * sizeof(float) + 3 * sizeof(int)) + 256, 256);
   L.off_kmv = o;
   size_t kb = gp_kmv_scratch_bytes(ctx, t);
@@ -869,13 +975,13 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
   float* R = (float*)(w + L.off_R);
   float* D = (float*)(w + L.off_D);
   float* HP = (float*)(w + L.off_HP);
-  float* SP = (float*)(w + L.off_SP);
   ApDev s;
   int* fac_breakdown;
   {
     char* q = w + L.off_state;
     s.flags = (ApFlags*)q; q += sizeof(ApFlags);
-    fac_breakdown = (int*)q; q += 64;
+    fac_breakdown = (int*)q; q += 32;
+    s.ticket = (unsigned*)q; q += 32;
     s.bn2 = (double*)q; q += sizeof(double) * t;
     s.tol = (float*)q; q += sizeof(float) * t;
     s.relres = (float*)q; q += sizeof(float) * t;
@@ -886,6 +992,7 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
   s.norms = (double*)(w + L.off_norms);
   s.normsB = (double*)(w + L.off_normsB);
   s.bnorm = (double*)(w + L.off_bnorm);
+  s.bnormB = (double*)(w + L.off_bnormB);
   void* kmv_scratch = w + L.off_kmv;
 
   const size_t need_pinned = sizeof(ApFlags) + sizeof(float) * t * 2;
@@ -952,9 +1059,10 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     ++kmv_count;
   }
   const dim3 sgrid(L.nb * L.S), sblock(256);
+  const int fgrid = L.nb < 64 ? L.nb : 64;     // workgroups of the finalise kernel
   hipLaunchKernelGGL(ap_init_kernel, sgrid, sblock, 0, st, dB, ldb, dX0, ldv, (const float*)HP, n, t, block, L.S, V, R, D,
                      s.norms, s.normsB);
-  hipLaunchKernelGGL(ap_finalise_kernel, dim3(1), dim3(1024), 0, st, s, L.nb, L.S, t, 1, (const int*)fac_breakdown);
+  hipLaunchKernelGGL(ap_finalise_kernel, dim3(fgrid), dim3(1024), 0, st, s, L.nb, L.S, t, 1, (const int*)fac_breakdown);
   GP_HIP(ctx, hipGetLastError());
   {
     const int rc = wait_seq(1);
@@ -971,14 +1079,12 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     const int64_t j1 = j0 + block < n ? j0 + block : n;
     const int bs = (int)(j1 - j0);
     {
-      const int kper = (bs + SOLVE_KSPLIT - 1) / SOLVE_KSPLIT;
-      hipLaunchKernelGGL(ap_solve_partial_kernel, dim3((bs + 63) / 64, SOLVE_KSPLIT, (t + 255) / 256),
-                         dim3(64 * (((t < 256 ? t : 256) + 15) / 16)), 0, st,
-                         (const float*)(Hinv + (size_t)k * BP * BP), BP, bs, (const float*)R, j0, t, kper, SP);
-      int rblocks = (int)(((int64_t)bs * t + 255) / 256);
-      if (rblocks > 2 * ctx->num_cu) rblocks = 2 * ctx->num_cu;
-      hipLaunchKernelGGL(ap_solve_reduce_kernel, dim3(rblocks), dim3(256), 0, st, (const float*)SP, SOLVE_KSPLIT, bs, t,
-                         (const int*)s.frozen, j0, D, s.colmax);
+      const int CT = (t + 15) / 16, RT = (bs + 15) / 16;
+      const int pairs = (RT + 1) / 2;
+      const int groups = (pairs + XCDS - 1) / XCDS;      // pairs of row tiles per XCD
+      hipLaunchKernelGGL(ap_block_solve_kernel, dim3(XCDS * groups * 2 * CT), dim3(64 * SOLVE_WAVES), 0, st,
+                         (const float*)(Hinv + (size_t)k * BP * BP), BP, bs, (const float*)R, j0, t, (const int*)s.frozen,
+                         D, s.colmax);
       GP_HIP(ctx, hipGetLastError());
     }
     KmvWindow win;
@@ -987,9 +1093,13 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     KmvDeferred df = {nullptr, 0, 1};
     const int rc = gp_kmv_launch(ctx, D, t, t, HP, t, 0, kmv_scratch, L.kmv_bytes, s.colmax, nullptr, &df, &win);
     if (rc < 0) return rc;
-    hipLaunchKernelGGL(ap_update_kernel, sgrid, sblock, 0, st, R, V, D, (const float*)HP, df.part, df.stride, df.JS, n, t,
-                       block, L.S, j0, j1, sigma2, s.norms);
-    hipLaunchKernelGGL(ap_finalise_kernel, dim3(1), dim3(1024), 0, st, s, L.nb, L.S, t, 0, (const int*)fac_breakdown);
+    {
+      const float* src = df.JS > 1 ? df.part : (const float*)HP;
+      auto upd = df.JS == 1 ? ap_update_kernel<1> : df.JS == 2 ? ap_update_kernel<2> : df.JS == 3 ? ap_update_kernel<3>
+                 : df.JS == 4 ? ap_update_kernel<4> : ap_update_kernel<0>;
+      hipLaunchKernelGGL(upd, sgrid, sblock, 0, st, R, V, D, src, df.stride, df.JS, n, t, block, L.S, k, sigma2, s.norms);
+    }
+    hipLaunchKernelGGL(ap_finalise_kernel, dim3(fgrid), dim3(1024), 0, st, s, L.nb, L.S, t, 0, (const int*)fac_breakdown);
     GP_HIP(ctx, hipGetLastError());
     const int rc2 = wait_seq(it + 2);
     if (rc2 < 0) return rc2;
