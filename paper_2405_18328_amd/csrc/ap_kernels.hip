@@ -464,11 +464,14 @@ __global__ __launch_bounds__(256) void ap_trinv_merge_kernel(const fac_t* __rest
 }
 
 // H[I,I]^-1 = X^T X, tiles (ti >= tj) and their mirror images, rounded to fp32.  The inverse is stored in
-// panels of 32 rows, contraction index major inside a panel: element (r, c) at
-// ((r / 32) BP + c) 32 + r % 32, so that what the block solve reads for one row tile and a range of
-// the contraction index c is one contiguous stretch of memory (128 bytes per c), not 64-byte pieces
-// 4 BP bytes apart.
-__device__ __forceinline__ int64_t hinv_at(int r, int c, int BP) { return ((int64_t)(r >> 5) * BP + c) * 32 + (r & 31); }
+// panels of 16 rows and, inside a panel, in groups of 4 contraction indices: element (r, c) at
+// ((r / 16) (BP / 4) + c / 4) 64 + (r % 16) 4 + c % 4.  What one wave of the block solve reads for its
+// row tile and 16 consecutive contraction indices (lane = (row, 4 of them), 16 bytes each) is then one
+// contiguous kilobyte, and the next 16 indices are the next kilobyte.
+__device__ __forceinline__ int64_t hinv_at(int r, int c, int BP) {
+  return ((int64_t)(r >> 4) * (BP >> 2) + (c >> 2)) * 64 + (r & 15) * 4 + (c & 3);
+}
+__device__ __forceinline__ constexpr int hinv_step() { return 64; }   // floats between c and c + 4 at fixed r
 __global__ __launch_bounds__(256) void ap_lauum_kernel(const fac_t* __restrict__ W, int BP, float* __restrict__ Hinv) {
   __shared__ Tile TA, TB;
   if (blockIdx.x > blockIdx.y) return;
@@ -544,96 +547,135 @@ __global__ __launch_bounds__(256) void ap_init_kernel(const float* __restrict__ 
 }
 
 // d = H[I,I]^-1 R[I,:], columns no longer updated set to 0, written to rows j0 .. j0 + bs - 1 of D, and
-// the columns' largest |d| to colmax (zero on entry).  One workgroup per 16 x 16 tile of d, on the fp32
-// matrix cores (v_mfma_f32_16x16x4_f32: A operand lane l holds A[l % 16][l / 16], B operand
-// B[l / 16][l % 16], result register v of lane l is D[4 (l / 16) + v][l % 16]).  The inverse is
-// symmetric and stored in 32-row panels (see ap_lauum_kernel): the A operand of contraction index m is
-// 16 consecutive floats, and consecutive m are 128 bytes apart.  The contraction index is cut into SOLVE_WAVES ranges, one per
-// wave of the workgroup, whose partial tiles are added in a fixed order through LDS; nothing is
-// exchanged between workgroups.  Every operand load is unconditional (out-of-range indices are
-// clamped and the value replaced by zero when it is used), so that a wave keeps two batches of
-// SOLVE_U operand pairs in flight and waits only for the older one.
-// Workgroups are numbered so that the 2 ceil(t / 16) tiles that read the same 128-byte lines of the
-// inverse (two neighbouring row tiles, all column tiles) follow each other on one XCD (workgroup w
-// runs on XCD w % 8): the 4 BP^2 bytes of the inverse then come from memory once, not once per XCD.
+// the columns' largest |d| to colmax (zero on entry).  One workgroup per 16 rows and 64 columns of d, on
+// the fp32 matrix cores (v_mfma_f32_16x16x4_f32: A operand lane l holds A[l % 16][l / 16], B operand
+// B[l / 16][l % 16], result register v of lane l is D[4 (l / 16) + v][l % 16]).
+//   - Every operand load is 16 bytes per lane (the memory pipeline of a compute unit spends the same
+//     time on a 4-byte-per-lane load).  A: the inverse is symmetric and stored so that lane l's four
+//     floats are Hinv[row0 + l % 16][m0 + 4 (l / 16) + j], j = 0..3 (see hinv_at).  B: lane l loads
+//     R[m][4 (l % 16) .. + 3] for the four m = m0 + 4 (l / 16) + j.  Matrix instruction (j, i) then
+//     contracts over the indices {m0 + 4 h + j} and produces the 16 columns {4 c + i}: the 64 columns
+//     of the workgroup are four interleaved tiles.  One A load and four B loads feed 16 instructions.
+//   - The contraction index is cut into SOLVE_WAVES ranges, one per wave, whose partial tiles are
+//     added in a fixed order through LDS; nothing is exchanged between workgroups.
+//   - Loads are unconditional (indices clamped, values replaced by zero when used), so a wave keeps
+//     two batches in flight and waits only for the older one.  Reading four floats at the end of a
+//     row of R runs into the next row (never past the array D that follows R in the workspace).
 typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
 constexpr int SOLVE_WAVES = 8;
-constexpr int SOLVE_U = 16;         // matrix instructions per batch of operand loads
-constexpr int XCDS = 8;
+constexpr int SOLVE_G = 2;          // groups of 16 contraction indices per batch of loads
 
 __global__ __launch_bounds__(64 * SOLVE_WAVES) void ap_block_solve_kernel(const float* __restrict__ Hinv, int BP, int bs,
                                                                          const float* __restrict__ R, int64_t j0,
                                                                          int t, const int* __restrict__ frozen,
                                                                          float* __restrict__ D,
                                                                          unsigned* __restrict__ colmax) {
-  __shared__ f4 red[SOLVE_WAVES][64];
+  __shared__ f4 red[SOLVE_WAVES][4][64];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lo = lane & 15, hi = lane >> 4;
-  const int CT = (t + 15) / 16, RT = (bs + 15) / 16;
-  const int g = blockIdx.x / XCDS;
-  const int pair = (g / (2 * CT)) * XCDS + blockIdx.x % XCDS;
-  const int member = g % (2 * CT);
-  const int rt = 2 * pair + (member & 1);
-  if (rt >= RT) return;
-  const int row0 = 16 * rt;
-  const int c = 16 * (member >> 1) + lo;
-  const bool cok = c < t;
-  const bool live = cok && !frozen[c];
-  float* Drow = D + (j0 + row0 + 4 * hi) * t + c;      // this lane's first output element
-  if (!__any(live)) {                                  // every column of the tile has converged
-    if (wave == 0 && cok) {
+  const int row0 = 16 * blockIdx.x;
+  const int cbase = 64 * blockIdx.y + 4 * lo;          // this lane's four columns: cbase + i
+  bool cok[4], live[4];
+  bool any_live = false;
 #pragma unroll
-      for (int v = 0; v < 4; ++v)
-        if (row0 + 4 * hi + v < bs) Drow[(int64_t)v * t] = 0.0f;
+  for (int i = 0; i < 4; ++i) {
+    cok[i] = cbase + i < t;
+    live[i] = frozen[cok[i] ? cbase + i : 0] == 0;     // unconditional loads, all four in flight together
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    live[i] = live[i] && cok[i];
+    any_live = any_live || live[i];
+  }
+  if (!__any(any_live)) {                              // every column of the workgroup has converged
+    if (wave == 0) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int c = 64 * blockIdx.y + 4 * lo + i;  // tile i, lane column lo
+          if (c < t && row0 + 4 * hi + v < bs) D[(j0 + row0 + 4 * hi + v) * t + c] = 0.0f;
+        }
     }
     return;
   }
-  const int kw = ((bs + SOLVE_WAVES - 1) / SOLVE_WAVES + 3) & ~3;   // contraction indices per wave, a multiple of 4
+  // tiles whose columns all lie past t are skipped (wave-uniform)
+  int ntile = t - 64 * (int)blockIdx.y;
+  ntile = ntile >= 4 ? 4 : ntile;                      // tile i holds the columns 64 cg + 4 c + i: present iff i < t - 64 cg
+  const int kw = ((bs + SOLVE_WAVES - 1) / SOLVE_WAVES + 15) & ~15;   // contraction indices per wave, a multiple of 16
   const int mb = wave * kw;
   const int me = mb + kw < bs ? mb + kw : bs;
-  const float* ap = Hinv + hinv_at(row0 + lo, 0, BP);   // + 32 m
-  const float* bp = R + j0 * t + (cok ? c : 0);
-  f4 acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
+  const float* ap = Hinv + hinv_at(row0 + lo, 4 * hi, BP);            // + hinv_step() floats per 4 contraction indices
+  const int bcol = cok[0] ? cbase : 0;
+  const float* bp = R + j0 * t + bcol;
+  f4 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) acc[i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
   if (mb < me) {
-    float a0[SOLVE_U], b0[SOLVE_U], a1[SOLVE_U], b1[SOLVE_U];
-    auto fetch = [&](float (&a)[SOLVE_U], float (&b)[SOLVE_U], int ms) {
+    struct Batch {
+      f4 a[SOLVE_G];
+      f4 b[SOLVE_G][4];
+    };
+    Batch b0, b1;
+    const int mlast = me - 1;
+    auto fetch = [&](Batch& q, int ms) {
 #pragma unroll
-      for (int u = 0; u < SOLVE_U; ++u) {
-        const int m = ms + 4 * u + hi;
-        const int mc = m < me ? m : me - 1;
-        a[u] = ap[32 * mc];
-        b[u] = bp[(int64_t)mc * t];
+      for (int g = 0; g < SOLVE_G; ++g) {
+        const int m0 = ms + 16 * g;                    // group of 16 contraction indices
+        const int mq = m0 < me ? m0 : (mlast & ~15);   // a group that starts inside the range (its tail is masked)
+        q.a[g] = *reinterpret_cast<const f4*>(ap + hinv_step() * (mq >> 2));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int m = mq + 4 * hi + j;
+          const int mc = m < me ? m : mlast;
+          q.b[g][j] = *reinterpret_cast<const f4u*>(bp + (int64_t)mc * t);
+        }
       }
     };
-    auto mac = [&](const float (&a)[SOLVE_U], const float (&b)[SOLVE_U], int ms) {
+    auto mac = [&](const Batch& q, int ms) {
 #pragma unroll
-      for (int u = 0; u < SOLVE_U; u += 2) {
-        const bool ok0 = ms + 4 * u + hi < me, ok1 = ms + 4 * (u + 1) + hi < me;
-        acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(ok0 ? a[u] : 0.0f, (ok0 && cok) ? b[u] : 0.0f, acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(ok1 ? a[u + 1] : 0.0f, (ok1 && cok) ? b[u + 1] : 0.0f, acc1, 0, 0, 0);
+      for (int g = 0; g < SOLVE_G; ++g) {
+        const int m0 = ms + 16 * g;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const bool ok = m0 + 4 * hi + j < me;
+          const float av = ok ? q.a[g][j] : 0.0f;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            if (i < ntile)
+              acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, (ok && cok[i]) ? q.b[g][j][i] : 0.0f, acc[i], 0, 0, 0);
+          }
+        }
       }
     };
-    fetch(a0, b0, mb);
-    for (int ms = mb; ms < me; ms += 8 * SOLVE_U) {
-      fetch(a1, b1, ms + 4 * SOLVE_U);
-      mac(a0, b0, ms);
-      fetch(a0, b0, ms + 8 * SOLVE_U);
-      mac(a1, b1, ms + 4 * SOLVE_U);
+    fetch(b0, mb);
+    for (int ms = mb; ms < me; ms += 32 * SOLVE_G) {
+      fetch(b1, ms + 16 * SOLVE_G);
+      mac(b0, ms);
+      fetch(b0, ms + 32 * SOLVE_G);
+      mac(b1, ms + 16 * SOLVE_G);
     }
   }
-  red[wave][lane] = acc0 + acc1;
-  __syncthreads();
-  if (wave != 0) return;
-  f4 sum = red[0][lane];
 #pragma unroll
-  for (int w = 1; w < SOLVE_WAVES; ++w) sum += red[w][lane];
+  for (int i = 0; i < 4; ++i) red[wave][i][lane] = acc[i];
+  __syncthreads();
+  if (wave >= 4 || wave >= ntile) return;
+  // wave i finishes tile i: columns 64 cg + 4 c + i for lane column c = lo
+  const int i = wave;
+  f4 sum = red[0][i][lane];
+#pragma unroll
+  for (int w = 1; w < SOLVE_WAVES; ++w) sum += red[w][i][lane];
+  const int c = 64 * blockIdx.y + 4 * lo + i;
+  const bool c_ok = c < t;
+  const bool c_live = c_ok && !frozen[c];
   float big = 0.0f;
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
-    const float val = live ? sum[v] : 0.0f;
-    if (cok && row0 + 4 * hi + v < bs) {
-      Drow[(int64_t)v * t] = val;
+    const float val = c_live ? sum[v] : 0.0f;
+    if (c_ok && row0 + 4 * hi + v < bs) {
+      D[(j0 + row0 + 4 * hi + v) * t + c] = val;
       big = fmaxf(big, fabsf(val));
     }
   }
@@ -1078,15 +1120,10 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     const int64_t j0 = (int64_t)k * block;
     const int64_t j1 = j0 + block < n ? j0 + block : n;
     const int bs = (int)(j1 - j0);
-    {
-      const int CT = (t + 15) / 16, RT = (bs + 15) / 16;
-      const int pairs = (RT + 1) / 2;
-      const int groups = (pairs + XCDS - 1) / XCDS;      // pairs of row tiles per XCD
-      hipLaunchKernelGGL(ap_block_solve_kernel, dim3(XCDS * groups * 2 * CT), dim3(64 * SOLVE_WAVES), 0, st,
-                         (const float*)(Hinv + (size_t)k * BP * BP), BP, bs, (const float*)R, j0, t, (const int*)s.frozen,
-                         D, s.colmax);
-      GP_HIP(ctx, hipGetLastError());
-    }
+    hipLaunchKernelGGL(ap_block_solve_kernel, dim3((bs + 15) / 16, (t + 63) / 64), dim3(64 * SOLVE_WAVES), 0, st,
+                       (const float*)(Hinv + (size_t)k * BP * BP), BP, bs, (const float*)R, j0, t, (const int*)s.frozen, D,
+                       s.colmax);
+    GP_HIP(ctx, hipGetLastError());
     KmvWindow win;
     win.chunk0 = (int)(j0 / 32);
     win.nchunks = (int)((j1 + 31) / 32) - win.chunk0;
