@@ -55,52 +55,75 @@ struct ApDev {
 };
 
 // ---- 64 x 64 tile products on the fp64 matrix cores ---------------------------------------------
-// Operands sit in LDS contraction-index-major: out[r][c] += sum_m TA[m][r] * TB[m][c].  A workgroup is
+// out[r][c] += sum_m A(r, m) B(m, c) over slabs of KD contraction indices staged in LDS.  A workgroup is
 // 4 waves; wave w owns rows 16 w .. 16 w + 15 of the output tile and all 64 columns, as four
 // 16 x 16 blocks of v_mfma_f64_16x16x4_f64 (A operand: lane l holds A[l % 16][l / 16]; B operand:
 // B[l / 16][l % 16]; result register v of lane l: D[4 v + l / 16][l % 16]).
+//
+// An operand slab is kept in LDS the way it lies in memory, so that it is fetched with 16-byte loads
+// and stored with 16-byte LDS writes, never transposed on the way:
+//   - "k-major": memory rows are contraction indices, slab element (m, x) at base[m * ld + x], x = the
+//     operand's row (A) or column (B) inside the tile; LDS word m * 64 + (x ^ 16 (m & 1));
+//   - "x-major": memory rows are the operand's own rows/columns, element (x, m) at base[x * ld + m];
+//     LDS word x * KD + (m ^ 2 (x & 15)).
+// The exclusive-ors make the matrix instructions' operand reads (16 values of x for each of 4
+// consecutive m per wave) hit every LDS bank once, without padding.
 typedef double d4 __attribute__((ext_vector_type(4)));
+typedef double d2 __attribute__((ext_vector_type(2)));
 
-constexpr int KD = 32;   // contraction depth held in LDS at a time: two 32 x 64 operand slabs = 33 KB per
+constexpr int KD = 32;   // contraction depth held in LDS at a time: two 32 x 64 operand slabs = 32 KB per
                          // workgroup, so that four workgroups share a compute unit and their loads, LDS
                          // traffic and matrix-core work overlap
 
-struct Tile {
-  fac_t v[KD][TS + 1];
+struct alignas(16) Tile {
+  fac_t v[KD * TS];
 };
 
 struct Acc {
   d4 b[4];   // column block cb: rows 16 w + 4 v + l / 16, column 16 cb + l % 16
 };
 
-// One 64 x 64 operand tile in memory: element (row, col) = base[row * ld + col].  by_col = false: the rows
-// are the contraction index (slab h = rows 32 h .. 32 h + 31, T[row][col]); by_col = true: the columns
-// are (slab h = columns 32 h .., stored transposed, T[col][row]).
+// One 64 x 64 operand tile in memory (see above); `xmajor` is fixed per call site (template argument
+// of tile_chain), `base` and `ld` are not.  Slab h of a tile = contraction indices 32 h .. 32 h + 31.
 struct Operand {
   const fac_t* base;
   int64_t ld;
-  bool by_col;
 };
 
 struct SlabRegs {
-  fac_t v[8];
+  d2 v[4];
 };
-// all 8 loads of a thread are issued before anything waits on them
+// all 4 loads of a thread are issued before anything waits on them
+template <bool XMAJOR>
 __device__ __forceinline__ void fetch_slab(SlabRegs& g, const Operand& o, int h) {
 #pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    const int e = threadIdx.x + 256 * q;
-    g.v[q] = o.by_col ? o.base[(int64_t)(e / KD) * o.ld + KD * h + (e % KD)]
-                      : o.base[(int64_t)(KD * h + e / TS) * o.ld + (e % TS)];
+  for (int q = 0; q < 4; ++q) {
+    const int e = threadIdx.x + 256 * q;            // pair of doubles e of the slab
+    const fac_t* src = XMAJOR ? o.base + (int64_t)(e / (KD / 2)) * o.ld + KD * h + 2 * (e % (KD / 2))
+                              : o.base + (int64_t)(KD * h + e / (TS / 2)) * o.ld + 2 * (e % (TS / 2));
+    g.v[q] = *reinterpret_cast<const d2*>(src);
   }
 }
-__device__ __forceinline__ void stash_slab(Tile& T, const SlabRegs& g, bool by_col) {
+template <bool XMAJOR>
+__device__ __forceinline__ void stash_slab(Tile& T, const SlabRegs& g) {
 #pragma unroll
-  for (int q = 0; q < 8; ++q) {
+  for (int q = 0; q < 4; ++q) {
     const int e = threadIdx.x + 256 * q;
-    if (by_col) T.v[e % KD][e / KD] = g.v[q];
-    else T.v[e / TS][e % TS] = g.v[q];
+    int word;
+    if (XMAJOR) {
+      const int x = e / (KD / 2), m = 2 * (e % (KD / 2));
+      word = x * KD + (m ^ (2 * (x & 15)));
+    } else {
+      const int m = e / (TS / 2), x = 2 * (e % (TS / 2));
+      word = m * TS + (x ^ (16 * (m & 1)));
+    }
+    *reinterpret_cast<d2*>(&T.v[word]) = g.v[q];     // the exclusive-ors are even: a pair stays a pair
   }
+}
+// operand value (x, m) of a staged slab
+template <bool XMAJOR>
+__device__ __forceinline__ fac_t slab_at(const Tile& T, int x, int m) {
+  return XMAJOR ? T.v[x * KD + (m ^ (2 * (x & 15)))] : T.v[m * TS + (x ^ (16 * (m & 1)))];
 }
 
 __device__ __forceinline__ void clear_acc(Acc& acc) {
@@ -108,41 +131,42 @@ __device__ __forceinline__ void clear_acc(Acc& acc) {
   for (int cb = 0; cb < 4; ++cb) acc.b[cb] = d4{0.0, 0.0, 0.0, 0.0};
 }
 
+template <bool AX, bool BX>
 __device__ __forceinline__ void mac_slab(const Tile& TA, const Tile& TB, Acc& acc) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int lo = lane & 15, hi = lane >> 4;
 #pragma unroll 4
   for (int m0 = 0; m0 < KD; m0 += 4) {
-    const fac_t a = TA.v[m0 + hi][16 * w + lo];
+    const fac_t a = slab_at<AX>(TA, 16 * w + lo, m0 + hi);
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb)
-      acc.b[cb] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, TB.v[m0 + hi][16 * cb + lo], acc.b[cb], 0, 0, 0);
+      acc.b[cb] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, slab_at<BX>(TB, 16 * cb + lo, m0 + hi), acc.b[cb], 0, 0, 0);
   }
 }
 
 // acc += sum over the tiles m = m_lo .. m_hi of A_m B_m, where opA(m) / opB(m) name the two 64 x 64
-// operand tiles of step m.  Slabs of 32 are staged through LDS; the next slab's loads are in flight
-// while the matrix cores work on the current one.
-template <typename FA, typename FB>
+// operand tiles of step m (AX / BX: x-major in memory).  The next slab's loads are in flight while the
+// matrix cores work on the current one.
+template <bool AX, bool BX, typename FA, typename FB>
 __device__ __forceinline__ void tile_chain(Tile& TA, Tile& TB, Acc& acc, int m_lo, int m_hi, FA opA, FB opB) {
   if (m_lo > m_hi) return;
   const int steps = 2 * (m_hi - m_lo + 1);
   SlabRegs ga, gb;
   Operand oa = opA(m_lo), ob = opB(m_lo);
-  fetch_slab(ga, oa, 0);
-  fetch_slab(gb, ob, 0);
+  fetch_slab<AX>(ga, oa, 0);
+  fetch_slab<BX>(gb, ob, 0);
   for (int q = 0; q < steps; ++q) {
-    stash_slab(TA, ga, oa.by_col);
-    stash_slab(TB, gb, ob.by_col);
+    stash_slab<AX>(TA, ga);
+    stash_slab<BX>(TB, gb);
     __syncthreads();
     if (q + 1 < steps) {
       const int m = m_lo + (q + 1) / 2;
       oa = opA(m);
       ob = opB(m);
-      fetch_slab(ga, oa, (q + 1) & 1);
-      fetch_slab(gb, ob, (q + 1) & 1);
+      fetch_slab<AX>(ga, oa, (q + 1) & 1);
+      fetch_slab<BX>(gb, ob, (q + 1) & 1);
     }
-    mac_slab(TA, TB, acc);
+    mac_slab<AX, BX>(TA, TB, acc);
     __syncthreads();
   }
 }
@@ -383,9 +407,9 @@ __global__ __launch_bounds__(256) void ap_chol_panel_kernel(fac_t* __restrict__ 
   Acc acc;
   clear_acc(acc);
   const int64_t ldA = BP;
-  tile_chain(TA, TB, acc, 0, 0,
-             [=](int) { return Operand{Aik, ldA, true}; },      // A_ik(r, m)
-             [=](int) { return Operand{DIb, TS, true}; });      // L_kk^-1(c, m)
+  tile_chain<true, true>(TA, TB, acc, 0, 0,
+                         [=](int) { return Operand{Aik, ldA}; },      // A_ik(r, m)
+                         [=](int) { return Operand{DIb, TS}; });      // L_kk^-1(c, m)
 #pragma unroll
   for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
@@ -403,15 +427,36 @@ __global__ __launch_bounds__(256) void ap_chol_update_kernel(fac_t* __restrict__
   const fac_t* LI = Ab + (int64_t)I * TS * BP + k * TS;
   const fac_t* LJ = Ab + (int64_t)J * TS * BP + k * TS;
   const int64_t ldA = BP;
-  tile_chain(TA, TB, acc, 0, 0,
-             [=](int) { return Operand{LI, ldA, true}; },       // L_Ik(r, m)
-             [=](int) { return Operand{LJ, ldA, true}; });      // L_Jk(c, m)
+  tile_chain<true, true>(TA, TB, acc, 0, 0,
+                         [=](int) { return Operand{LI, ldA}; },       // L_Ik(r, m)
+                         [=](int) { return Operand{LJ, ldA}; });      // L_Jk(c, m)
   fac_t* Aij = Ab + (int64_t)I * TS * BP + J * TS;
 #pragma unroll
   for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
     for (int v = 0; v < 4; ++v) Aij[(int64_t)acc_row(v) * BP + acc_col(cb)] -= acc.b[cb][v];
 }
+
+// Workgroup numbering of X^T X, the kernel with the longest tile-product chains: the output tiles are
+// grouped into super-blocks of SB x SB tiles, and the workgroups of a super-block follow each other on
+// one XCD (workgroup w of a launch runs on XCD w % XCDS), so that the operand tiles they share are
+// fetched into that XCD's L2 once.  Numbered row by row over the whole grid, every XCD pulled all of X
+// through its own L2 several times, and the kernel waited for memory 70 % of the time (1.25 ms against
+// 0.62 ms for nine blocks of 2048).  The triangular inverse's merges gained nothing from the same
+// numbering (fewer, shorter chains per launch) and keep the plain grid.
+constexpr int XCDS = 8;
+constexpr int SB = 8;         // super-block edge of X^T X (90 super-blocks for nine blocks of 2048: 11 or 12 per XCD)
+struct SbIndex {
+  int sb;        // super-block
+  int di, dj;    // tile inside it
+};
+__device__ __forceinline__ SbIndex sb_decode(int edge) {      // edge = tiles per super-block edge
+  const int per = edge * edge;
+  const int slot = blockIdx.x / XCDS;
+  const int within = slot % per;
+  return SbIndex{(slot / per) * XCDS + (int)(blockIdx.x % XCDS), within / edge, within % edge};
+}
+inline int sb_grid(int superblocks, int edge) { return XCDS * ((superblocks + XCDS - 1) / XCDS) * edge * edge; }
 
 // X = L^-1 by merging diagonal blocks pairwise, level by level (s = 1, 2, 4, .. tiles): for the pair
 // [[L11, 0], [L21, L22]] whose halves X11 = L11^-1 and X22 = L22^-1 are complete,
@@ -451,9 +496,9 @@ __global__ __launch_bounds__(256) void ap_trinv_merge_kernel(const fac_t* __rest
     const fac_t* Pt = P + (int64_t)ti * TS * BP;
     const fac_t* Qt = Q + (int64_t)tj * TS;
     const int64_t ld = BP;
-    tile_chain(TA, TB, acc, mlo, mhi,
-               [=](int m) { return Operand{Pt + (int64_t)m * TS, ld, true}; },          // P(r, q): the source column is the contraction index
-               [=](int m) { return Operand{Qt + (int64_t)m * TS * ld, ld, false}; });   // Q(q, c)
+    tile_chain<true, false>(TA, TB, acc, mlo, mhi,
+                            [=](int m) { return Operand{Pt + (int64_t)m * TS, ld}; },          // P(r, q): the source column is the contraction index
+                            [=](int m) { return Operand{Qt + (int64_t)m * TS * ld, ld}; });    // Q(q, c)
   }
   fac_t* out = (step == 0 ? T : X) + zo + (int64_t)(o2 + ti) * TS * BP + (o1 + tj) * TS;
   const fac_t sign = step == 0 ? 1.0 : -1.0;
@@ -472,22 +517,39 @@ __device__ __forceinline__ int64_t hinv_at(int r, int c, int BP) {
   return ((int64_t)(r >> 4) * (BP >> 2) + (c >> 2)) * 64 + (r & 15) * 4 + (c & 3);
 }
 __device__ __forceinline__ constexpr int hinv_step() { return 64; }   // floats between c and c + 4 at fixed r
-__global__ __launch_bounds__(256) void ap_lauum_kernel(const fac_t* __restrict__ W, int BP, float* __restrict__ Hinv) {
+// Workgroups are numbered by super-block (see sb_decode) and walk the contraction index downwards from
+// the same starting tile row, so that the 2 SB tile columns of X a super-block shares stay in its
+// XCD's L2 while they are in use.
+__host__ __device__ inline int lauum_superblocks(int nt) {
+  const int ns = (nt + SB - 1) / SB;
+  return ns * (ns + 1) / 2;
+}
+__global__ __launch_bounds__(256) void ap_lauum_kernel(const fac_t* __restrict__ W, int BP, int cnt,
+                                                       float* __restrict__ Hinv) {
   __shared__ Tile TA, TB;
-  if (blockIdx.x > blockIdx.y) return;
-  const int ti = blockIdx.y, tj = blockIdx.x, nt = BP / TS;
-  const fac_t* Wb = W + (int64_t)blockIdx.z * BP * BP;
+  const int nt = BP / TS;
+  const int nsb = lauum_superblocks(nt);
+  const SbIndex w = sb_decode(SB);
+  if (w.sb >= cnt * nsb) return;
+  const int z = w.sb / nsb, p = w.sb % nsb;
+  int I = 0;
+  while ((I + 1) * (I + 2) / 2 <= p) ++I;                             // p = I (I + 1) / 2 + J, J <= I
+  const int J = p - I * (I + 1) / 2;
+  const int ti = SB * I + w.di, tj = SB * J + w.dj;
+  if (ti >= nt || tj > ti) return;
+  const fac_t* Wb = W + (int64_t)z * BP * BP;
   Acc acc;
   clear_acc(acc);
   {
     const fac_t* Wi = Wb + (int64_t)ti * TS;
     const fac_t* Wj = Wb + (int64_t)tj * TS;
     const int64_t ld = BP;
-    tile_chain(TA, TB, acc, ti, nt - 1,
-               [=](int m) { return Operand{Wi + (int64_t)m * TS * ld, ld, false}; },    // X_m,ti(q, r)
-               [=](int m) { return Operand{Wj + (int64_t)m * TS * ld, ld, false}; });   // X_m,tj(q, c)
+    const int top = nt - 1 + ti;                                      // step m of the chain reads tile row top - m
+    tile_chain<false, false>(TA, TB, acc, ti, nt - 1,
+                             [=](int m) { return Operand{Wi + (int64_t)(top - m) * TS * ld, ld}; },    // X_m,ti(q, r)
+                             [=](int m) { return Operand{Wj + (int64_t)(top - m) * TS * ld, ld}; });   // X_m,tj(q, c)
   }
-  float* Hb = Hinv + (int64_t)blockIdx.z * BP * BP;
+  float* Hb = Hinv + (int64_t)z * BP * BP;
 #pragma unroll
   for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
@@ -1088,8 +1150,11 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
         hipLaunchKernelGGL(ap_trinv_merge_kernel, dim3(sz, sz, pairs * cnt), dim3(256), 0, st, (const fac_t*)A, W, TT, BP, sz,
                            pairs, step);
     }
-    hipLaunchKernelGGL(ap_lauum_kernel, dim3(nt, nt, cnt), dim3(256), 0, st, (const fac_t*)W, BP,
-                       Hinv + (size_t)blk0 * BP * BP);
+    {
+      const int sbs = cnt * lauum_superblocks(nt);
+      hipLaunchKernelGGL(ap_lauum_kernel, dim3(sb_grid(sbs, SB)), dim3(256), 0, st,
+                         (const fac_t*)W, BP, cnt, Hinv + (size_t)blk0 * BP * BP);
+    }
     GP_HIP(ctx, hipGetLastError());
   }
 
