@@ -166,7 +166,7 @@ struct KmvPlan {
 KmvPlan gp_plan_kmv(const gp_ctx* ctx, int64_t rows, int64_t col_chunks = 0);   // col_chunks = 0: all of the context's
 size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t);   // square product, worst case over the paths gp_set_theta may choose
 size_t gp_kmv_rect_scratch_bytes(const gp_ctx* ctx, int t, int64_t rows);
-size_t gp_kmv_window_scratch_bytes(const gp_ctx* ctx, int t, int col_chunks);   // product over a column window of that many chunks
+size_t gp_kmv_window_scratch_bytes(const gp_ctx* ctx, int t, int col_chunks);   // product over any column window of at most that many chunks
 // OUT = K V (+ sigma^2 V).  colmax: optional device array of t bit patterns of max_i |V_ic| that the
 // caller already holds (the split-fp16 path then skips its own reduction over V); NULL otherwise.
 // rows: NULL, or the row side of a rectangular product (add_noise must then be 0).

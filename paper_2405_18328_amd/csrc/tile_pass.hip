@@ -316,11 +316,19 @@ size_t gp_kmv_rect_scratch_bytes(const gp_ctx* ctx, int t, int64_t rows) {
 
 size_t gp_kmv_scratch_bytes(const gp_ctx* ctx, int t) { return gp_kmv_rect_scratch_bytes(ctx, t, ctx->n); }
 
+// Scratch for a product over any column window of at most col_chunks chunks.  The number of column
+// splits is not monotone in the window's length (65 chunks are cut into 13 ranges of 5, 64 chunks into
+// 16 ranges of 4), so every length is planned.
 size_t gp_kmv_window_scratch_bytes(const gp_ctx* ctx, int t, int col_chunks) {
-  KmvPlan pl = gp_plan_kmv(ctx, ctx->n, col_chunks);
-  const size_t fp32_bytes = pl.JS <= 1 ? 0 : (size_t)pl.JS * (size_t)ctx->n * (size_t)t * sizeof(float);
-  const size_t f16_bytes = gp_kmv_f16_scratch_bytes(ctx, t, ctx->n, col_chunks);
-  return fp32_bytes > f16_bytes ? fp32_bytes : f16_bytes;
+  size_t need = 0;
+  for (int c = 1; c <= col_chunks; ++c) {
+    const KmvPlan pl = gp_plan_kmv(ctx, ctx->n, c);
+    const size_t fp32_bytes = pl.JS <= 1 ? 0 : (size_t)pl.JS * (size_t)ctx->n * (size_t)t * sizeof(float);
+    const size_t f16_bytes = gp_kmv_f16_scratch_bytes(ctx, t, ctx->n, c);
+    if (fp32_bytes > need) need = fp32_bytes;
+    if (f16_bytes > need) need = f16_bytes;
+  }
+  return need;
 }
 
 int gp_kmv_launch(gp_ctx* ctx, const float* dV, int64_t ldv, int t, float* dOut, int64_t ldo,

@@ -336,3 +336,41 @@ def test_ap_random_small_shapes():
                 np.testing.assert_allclose(rr, rro, rtol=2e-3, atol=2e-5)   # a single-block solve leaves an fp32 rounding-level residual
         finally:
             dv.close()
+
+
+def test_ap_shapes_at_the_solve_kernels_tile_boundaries():
+    """Right-hand-side counts around the block solve's 64-column workgroups and 4-column lanes (63..66, 128,
+    129), block sizes around its 16-row tiles and the factorisation's 64-row tiles (16, 17, 127..129, 500),
+    and the largest blocks the library takes (2047, 2048): three steps against the oracle."""
+    rng = np.random.default_rng(77)
+    cases = [(300, 63, 100), (300, 64, 128), (300, 65, 129), (300, 66, 16), (300, 128, 17), (260, 129, 127),
+             (1100, 65, 500), (4200, 65, 2047), (4300, 9, 2048)]
+    for case, (n, t, block) in enumerate(cases):
+        d = 5
+        kind = "se" if case % 2 else "matern32"
+        X = rng.standard_normal((n, d)).astype(np.float32)
+        ell = rng.uniform(0.8, 2.5, size=d) * np.sqrt(d)
+        a, sigma = float(rng.uniform(0.5, 1.5)), float(rng.uniform(0.4, 1.0))
+        # rows growing in size keep the blocks' residual norms apart, so that the greedy order is unambiguous
+        B = (rng.standard_normal((n, t)) * (1.0 + np.arange(n)[:, None] / n)).astype(np.float32)
+        print(f"[ap-shape] case {case}: n={n} t={t} block={block} {kind}", flush=True)
+        H = orc.coefficient_matrix(X, ell, a, sigma, kind)
+        Bf = B.astype(np.float64)
+        dv = Dev(X, kind, ell, a, sigma)
+        try:
+            k = 3
+            Vo, ito, rro, pko = orc.ap_batched(H, Bf, tol=1e-12, block=block, max_iters=k)
+            Vs, safe = np.zeros_like(Bf), True
+            for _ in range(ito):
+                safe = safe and _margin_ok(H, Bf, Vs, block, np.ones(t, bool))
+                Vs, _, _, _ = orc.ap_batched(H, Bf, X0=Vs, tol=1e-12, block=block, max_iters=1)
+            rc, it, _, rr, pk, Vd = dv.ap_solve(B, 1e-12, block, max_iters=ito, picks=True)
+            assert it == ito
+            if safe:
+                assert list(pk) == pko
+                assert (_colrel(Vd.cpu().numpy(), Vo) <= STEP_TOL).all(), (case, _colrel(Vd.cpu().numpy(), Vo).max())
+                np.testing.assert_allclose(rr, rro, rtol=2e-3, atol=2e-5)
+            else:
+                print(f"[ap-shape] case {case}: block margins too narrow for a step-by-step comparison", flush=True)
+        finally:
+            dv.close()
