@@ -28,6 +28,10 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
 # by (workload, n); the JSON line repeats the source next to the number.
 TRAFFIC = {("config2", 16384): 43.4e6, ("config5", 2000000): 742e9}
 TRAFFIC_SOURCE = "profiles/kmv_tile_f16_hbm_traffic_pmc.md (rocprofv3 --pmc runs, not this run)"
+# Engine clock under the tile kernel (GRBM_GUI_ACTIVE over the kernel's duration), likewise from separate
+# counter runs: the published peaks assume 2.4 GHz, the chip holds less under this kernel's load.
+ENGINE_CLOCK_GHZ = {"config2": 1.98, "config5": 1.74}
+ENGINE_CLOCK_SOURCE = "profiles/kmv_tile_f16_engine_clock_under_load.md (rocprofv3 --pmc runs, not this run; peak assumes 2.4 GHz)"
 
 
 def kmv_flops(n, d, t, kind):
@@ -130,7 +134,9 @@ def config5_leg(cap=4, outer_steps=3, timed_products=3):
                       "value_tflops": F * timed_products / wall / 1e12,
                       "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                                    "frac": achieved / peak, "traffic": TRAFFIC.get(("config5", n)),
-                                   "traffic_source": TRAFFIC_SOURCE, "kernel": "kmv_tile_kernel" if path == 0 else "kmv_tile_f16_kernel",
+                                   "traffic_source": TRAFFIC_SOURCE, "engine_clock_ghz": ENGINE_CLOCK_GHZ["config5"],
+                                   "engine_clock_source": ENGINE_CLOCK_SOURCE,
+                                   "kernel": "kmv_tile_kernel" if path == 0 else "kmv_tile_f16_kernel",
                                    "product_path": PATH_NAMES[path], "peak_dtype": "fp32" if path == 0 else "fp16",
                                    "launches": int(launches), "avg_launch_ms": avg_s * 1e3, "flops_per_launch": F_launch,
                                    "executed_mfma_tflops": executed, "executed_mfma_frac_of_peak": executed / peak,
@@ -426,6 +432,8 @@ def main():
                          # counter-based bytes exist for the square product only (the CG path's launches)
                          "traffic": TRAFFIC.get((args.workload, n)) if args.solver == "cg" and not args.predict else None,
                          "traffic_source": TRAFFIC_SOURCE if args.solver == "cg" and not args.predict and (args.workload, n) in TRAFFIC else None,
+                         "engine_clock_ghz": ENGINE_CLOCK_GHZ.get(args.workload) if (args.workload, n) in TRAFFIC else None,
+                         "engine_clock_source": ENGINE_CLOCK_SOURCE if (args.workload, n) in TRAFFIC else None,
                          "kernel": "kmv_tile_kernel" if path == 0 else "kmv_tile_f16_kernel",
                          "product_path": PATH_NAMES[path], "peak_dtype": "fp32" if path == 0 else "fp16",
                          "launches": int(launches), "avg_launch_ms": avg_kern_s * 1e3,
