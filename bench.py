@@ -397,6 +397,20 @@ def main():
                                  "iters": cold_it, "max_relres": cold_rel, "not_converged_steps": int(cold_nc),
                                  "note": "zero initialisation + resampled Gaussian probes, same theta sequence"}
                 extra["warm_vs_cold_cg_speedup"] = extra["cold"]["cg_ms_per_step"] / warm_stats["cg_ms_per_step"]
+                # second cold arm: zero initialisation but the warm arm's own fixed probes, which isolates what
+                # the initial guess alone buys (the arm above also changes the right-hand sides every step)
+                fx_ms, fx_it = [], []
+                for r in timed:
+                    th = r.theta
+                    gp.gp_set_theta(opt.ctx, th[:d], th[d], th[d + 1])
+                    torch.cuda.synchronize()
+                    c0 = time.perf_counter()
+                    rc, it, _, rel = solve(opt.B, None, Vc)
+                    fx_ms.append((time.perf_counter() - c0) * 1e3)
+                    fx_it.append(it)
+                extra["cold_fixed_probes"] = {"cg_ms_per_step": float(np.mean(fx_ms)), "iters_per_step": float(np.mean(fx_it)),
+                                              "iters": fx_it, "note": "zero initialisation, same fixed probes as the warm arm, "
+                                                                      "same theta sequence"}
                 if warm_stats["not_converged_steps"] or cold_nc:
                     # iteration cap reached: the comparison is the residual reached with the same budget per
                     # step (the warm arm keeps the progress of earlier steps, paper Section 3)
