@@ -9,13 +9,14 @@
 //   - set-up (once per solve, i.e. once per theta): every H[I,I] is built, factorised (Cholesky, fp64,
 //     64 x 64 tiles, many blocks side by side in one launch), and turned into its explicit inverse
 //     (triangular inverse, then L^-T L^-1), stored in fp32.  The block solve of every later step is
-//     then one dense product H[I,I]^-1 R[I,:] spread over all compute units instead of two
-//     triangular solves that a few workgroups would have to walk through row tile by row tile;
+//     then one dense product H[I,I]^-1 R[I,:] on the fp32 matrix cores spread over the chip instead of
+//     two triangular solves that a few workgroups would have to walk through row tile by row tile;
 //   - H[:,I] d is the matrix-free tile pass restricted to the block's columns (KmvWindow);
-//   - one streaming kernel applies the update and leaves per-block squared residual norms, one small
+//   - one streaming kernel applies the update and leaves per-slice squared residual norms, one small
 //     kernel turns those into the stopping test and the next block, and posts both to pinned host
 //     memory for the host loop (as the CG loop does).
-// All reductions have a fixed order; the only atomics are integer maxima.
+// All floating-point reductions have a fixed order; the atomics are integer maxima (column maxima) and
+// one integer ticket counter (which workgroup of the finalise kernel finishes last).
 #include <math.h>
 #include <stdint.h>
 
