@@ -625,61 +625,71 @@ __global__ __launch_bounds__(256) void ap_init_kernel(const float* __restrict__ 
 //     two batches in flight and waits only for the older one.  Reading four floats at the end of a
 //     row of R runs into the next row (never past the array D that follows R in the workspace).
 typedef float f4 __attribute__((ext_vector_type(4)));
-typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
 constexpr int SOLVE_WAVES = 8;
-constexpr int SOLVE_G = 2;          // groups of 16 contraction indices per batch of loads
 
+// NTL consecutive floats at a 4-byte-aligned address
+template <int NTL> struct RowVec;
+template <> struct RowVec<4> { typedef float type __attribute__((ext_vector_type(4), aligned(4))); };
+template <> struct RowVec<2> { typedef float type __attribute__((ext_vector_type(2), aligned(4))); };
+
+// NTL = interleaved column tiles per workgroup: 4 (64 columns, 16-byte loads of R) or 2 (32 columns,
+// 8-byte loads; twice as many workgroups, for products whose 16-row tiles alone do not fill the chip)
+template <int NTL>
 __global__ __launch_bounds__(64 * SOLVE_WAVES) void ap_block_solve_kernel(const float* __restrict__ Hinv, int BP, int bs,
                                                                          const float* __restrict__ R, int64_t j0,
                                                                          int t, const int* __restrict__ frozen,
                                                                          float* __restrict__ D,
                                                                          unsigned* __restrict__ colmax) {
-  __shared__ f4 red[SOLVE_WAVES][4][64];
+  typedef typename RowVec<NTL>::type rowvec;
+  constexpr int CW = 16 * NTL;                         // columns of a workgroup
+  constexpr int SOLVE_G = 2;                           // groups of 16 contraction indices per batch of loads
+  __shared__ f4 red[SOLVE_WAVES][NTL][64];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lo = lane & 15, hi = lane >> 4;
   const int row0 = 16 * blockIdx.x;
-  const int cbase = 64 * blockIdx.y + 4 * lo;          // this lane's four columns: cbase + i
-  bool cok[4], live[4];
+  const int cbase = CW * blockIdx.y + NTL * lo;        // this lane's B columns: cbase + i
+  bool cok[NTL], live[NTL];
   bool any_live = false;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < NTL; ++i) {
     cok[i] = cbase + i < t;
-    live[i] = frozen[cok[i] ? cbase + i : 0] == 0;     // unconditional loads, all four in flight together
+    live[i] = frozen[cok[i] ? cbase + i : 0] == 0;     // unconditional loads, all in flight together
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < NTL; ++i) {
     live[i] = live[i] && cok[i];
     any_live = any_live || live[i];
   }
   if (!__any(any_live)) {                              // every column of the workgroup has converged
     if (wave == 0) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < NTL; ++i)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          const int c = 64 * blockIdx.y + 4 * lo + i;  // tile i, lane column lo
+          const int c = cbase + i;                     // tile i, lane column lo
           if (c < t && row0 + 4 * hi + v < bs) D[(j0 + row0 + 4 * hi + v) * t + c] = 0.0f;
         }
     }
     return;
   }
-  // tiles whose columns all lie past t are skipped (wave-uniform)
-  int ntile = t - 64 * (int)blockIdx.y;
-  ntile = ntile >= 4 ? 4 : ntile;                      // tile i holds the columns 64 cg + 4 c + i: present iff i < t - 64 cg
+  // tiles whose columns all lie past t are skipped (wave-uniform): tile i holds the columns
+  // CW cg + NTL c + i, present iff i < t - CW cg
+  int ntile = t - CW * (int)blockIdx.y;
+  ntile = ntile >= NTL ? NTL : ntile;
   const int kw = ((bs + SOLVE_WAVES - 1) / SOLVE_WAVES + 15) & ~15;   // contraction indices per wave, a multiple of 16
   const int mb = wave * kw;
   const int me = mb + kw < bs ? mb + kw : bs;
   const float* ap = Hinv + hinv_at(row0 + lo, 4 * hi, BP);            // + hinv_step() floats per 4 contraction indices
   const int bcol = cok[0] ? cbase : 0;
   const float* bp = R + j0 * t + bcol;
-  f4 acc[4];
+  f4 acc[NTL];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) acc[i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
+  for (int i = 0; i < NTL; ++i) acc[i] = f4{0.0f, 0.0f, 0.0f, 0.0f};
   if (mb < me) {
     struct Batch {
       f4 a[SOLVE_G];
-      f4 b[SOLVE_G][4];
+      rowvec b[SOLVE_G][4];
     };
     Batch b0, b1;
     const int mlast = me - 1;
@@ -693,7 +703,7 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void ap_block_solve_kernel(const 
         for (int j = 0; j < 4; ++j) {
           const int m = mq + 4 * hi + j;
           const int mc = m < me ? m : mlast;
-          q.b[g][j] = *reinterpret_cast<const f4u*>(bp + (int64_t)mc * t);
+          q.b[g][j] = *reinterpret_cast<const rowvec*>(bp + (int64_t)mc * t);
         }
       }
     };
@@ -706,7 +716,7 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void ap_block_solve_kernel(const 
           const bool ok = m0 + 4 * hi + j < me;
           const float av = ok ? q.a[g][j] : 0.0f;
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
+          for (int i = 0; i < NTL; ++i) {
             if (i < ntile)
               acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, (ok && cok[i]) ? q.b[g][j][i] : 0.0f, acc[i], 0, 0, 0);
           }
@@ -722,17 +732,17 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void ap_block_solve_kernel(const 
     }
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) red[wave][i][lane] = acc[i];
+  for (int i = 0; i < NTL; ++i) red[wave][i][lane] = acc[i];
   __syncthreads();
-  if (wave >= 4 || wave >= ntile) return;
-  // wave i finishes tile i: columns 64 cg + 4 c + i for lane column c = lo
+  if (wave >= NTL || wave >= ntile) return;
+  // wave i finishes tile i: columns CW cg + NTL c + i for lane column c = lo
   const int i = wave;
   f4 sum = red[0][i][lane];
 #pragma unroll
   for (int w = 1; w < SOLVE_WAVES; ++w) sum += red[w][i][lane];
-  const int c = 64 * blockIdx.y + 4 * lo + i;
+  const int c = CW * blockIdx.y + NTL * lo + i;
   const bool c_ok = c < t;
-  const bool c_live = c_ok && !frozen[c];
+  const bool c_live = c_ok && !frozen[c_ok ? c : 0];
   float big = 0.0f;
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
@@ -1186,10 +1196,20 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     const int64_t j0 = (int64_t)k * block;
     const int64_t j1 = j0 + block < n ? j0 + block : n;
     const int bs = (int)(j1 - j0);
-    hipLaunchKernelGGL(ap_block_solve_kernel, dim3((bs + 15) / 16, (t + 63) / 64), dim3(64 * SOLVE_WAVES), 0, st,
-                       (const float*)(Hinv + (size_t)k * BP * BP), BP, bs, (const float*)R, j0, t, (const int*)s.frozen, D,
-                       s.colmax);
-    GP_HIP(ctx, hipGetLastError());
+    {
+      // 64 columns per workgroup read R with 16-byte loads; 32 columns double the workgroups when those
+      // would not reach one per compute unit (a block of 2000 has 125 row tiles)
+      const int rt = (bs + 15) / 16;
+      if (rt * ((t + 63) / 64) >= ctx->num_cu)
+        hipLaunchKernelGGL(ap_block_solve_kernel<4>, dim3(rt, (t + 63) / 64), dim3(64 * SOLVE_WAVES), 0, st,
+                           (const float*)(Hinv + (size_t)k * BP * BP), BP, bs, (const float*)R, j0, t, (const int*)s.frozen,
+                           D, s.colmax);
+      else
+        hipLaunchKernelGGL(ap_block_solve_kernel<2>, dim3(rt, (t + 31) / 32), dim3(64 * SOLVE_WAVES), 0, st,
+                           (const float*)(Hinv + (size_t)k * BP * BP), BP, bs, (const float*)R, j0, t, (const int*)s.frozen,
+                           D, s.colmax);
+      GP_HIP(ctx, hipGetLastError());
+    }
     KmvWindow win;
     win.chunk0 = (int)(j0 / 32);
     win.nchunks = (int)((j1 + 31) / 32) - win.chunk0;
