@@ -634,10 +634,15 @@ template <> struct RowVec<2> { typedef float type __attribute__((ext_vector_type
 
 // NTL = interleaved column tiles per workgroup: 4 (64 columns, 16-byte loads of R) or 2 (32 columns,
 // 8-byte loads; twice as many workgroups, for products whose 16-row tiles alone do not fill the chip)
+// The block is the one the last finalise step chose (flags->sel, read here on the device), so the host
+// can queue this kernel right behind that step without waiting to learn the choice; it does nothing once
+// the solve is over.  The grid covers a full block; workgroups past a short last block leave at once.
 template <int NTL>
-__global__ __launch_bounds__(64 * SOLVE_WAVES) void ap_block_solve_kernel(const float* __restrict__ Hinv, int BP, int bs,
-                                                                         const float* __restrict__ R, int64_t j0,
-                                                                         int t, const int* __restrict__ frozen,
+__global__ __launch_bounds__(64 * SOLVE_WAVES) void ap_block_solve_kernel(const float* __restrict__ Hinv_all, int BP,
+                                                                         int block, int64_t n,
+                                                                         const float* __restrict__ R, int t,
+                                                                         const ApFlags* __restrict__ flags,
+                                                                         const int* __restrict__ frozen,
                                                                          float* __restrict__ D,
                                                                          unsigned* __restrict__ colmax) {
   typedef typename RowVec<NTL>::type rowvec;
@@ -648,6 +653,12 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void ap_block_solve_kernel(const 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lo = lane & 15, hi = lane >> 4;
   const int row0 = 16 * blockIdx.x;
+  const int done = flags->all_done, k = flags->sel;
+  if (done) return;
+  const int64_t j0 = (int64_t)k * block;
+  const int bs = (int)(n - j0 < block ? n - j0 : block);
+  if (row0 >= bs) return;
+  const float* Hinv = Hinv_all + (int64_t)k * BP * BP;
   const int cbase = CW * blockIdx.y + NTL * lo;        // this lane's B columns: cbase + i
   bool cok[NTL], live[NTL];
   bool any_live = false;
@@ -1188,28 +1199,31 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
   }
 
   const float sigma2 = (float)(ctx->sigma * ctx->sigma);
+  // The block solve of a step takes the block choice from the device, so it is queued behind the
+  // previous step's finalise kernel before the host has seen that step's outcome: the host's poll and its
+  // next launches then run while the block solve does.
+  auto launch_solve = [&]() {
+    const int full = (int)(n < block ? n : block);
+    const int rt = (full + 15) / 16;
+    // 64 columns per workgroup read R with 16-byte loads; 32 columns double the workgroups when those
+    // would not reach one per compute unit (a block of 2000 has 125 row tiles)
+    if (rt * ((t + 63) / 64) >= ctx->num_cu)
+      hipLaunchKernelGGL(ap_block_solve_kernel<4>, dim3(rt, (t + 63) / 64), dim3(64 * SOLVE_WAVES), 0, st,
+                         (const float*)Hinv, BP, block, n, (const float*)R, t, (const ApFlags*)s.flags,
+                         (const int*)s.frozen, D, s.colmax);
+    else
+      hipLaunchKernelGGL(ap_block_solve_kernel<2>, dim3(rt, (t + 31) / 32), dim3(64 * SOLVE_WAVES), 0, st,
+                         (const float*)Hinv, BP, block, n, (const float*)R, t, (const ApFlags*)s.flags,
+                         (const int*)s.frozen, D, s.colmax);
+  };
   int it = 0;
+  if (!hpost->all_done && max_iters > 0) launch_solve();
   while (!hpost->all_done && it < max_iters) {
     const int k = hpost->sel;
     if (k < 0 || k >= L.nb) return gp_fail(ctx, GP_ERR_HIP, "gp_ap_solve: block choice %d out of range", k);
     if (h_picks) h_picks[it] = k;
     const int64_t j0 = (int64_t)k * block;
     const int64_t j1 = j0 + block < n ? j0 + block : n;
-    const int bs = (int)(j1 - j0);
-    {
-      // 64 columns per workgroup read R with 16-byte loads; 32 columns double the workgroups when those
-      // would not reach one per compute unit (a block of 2000 has 125 row tiles)
-      const int rt = (bs + 15) / 16;
-      if (rt * ((t + 63) / 64) >= ctx->num_cu)
-        hipLaunchKernelGGL(ap_block_solve_kernel<4>, dim3(rt, (t + 63) / 64), dim3(64 * SOLVE_WAVES), 0, st,
-                           (const float*)(Hinv + (size_t)k * BP * BP), BP, bs, (const float*)R, j0, t, (const int*)s.frozen,
-                           D, s.colmax);
-      else
-        hipLaunchKernelGGL(ap_block_solve_kernel<2>, dim3(rt, (t + 31) / 32), dim3(64 * SOLVE_WAVES), 0, st,
-                           (const float*)(Hinv + (size_t)k * BP * BP), BP, bs, (const float*)R, j0, t, (const int*)s.frozen,
-                           D, s.colmax);
-      GP_HIP(ctx, hipGetLastError());
-    }
     KmvWindow win;
     win.chunk0 = (int)(j0 / 32);
     win.nchunks = (int)((j1 + 31) / 32) - win.chunk0;
@@ -1223,6 +1237,7 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
       hipLaunchKernelGGL(upd, sgrid, sblock, 0, st, R, V, D, src, df.stride, df.JS, n, t, block, L.S, k, sigma2, s.norms);
     }
     hipLaunchKernelGGL(ap_finalise_kernel, dim3(fgrid), dim3(1024), 0, st, s, L.nb, L.S, t, 0, (const int*)fac_breakdown);
+    if (it + 1 < max_iters) launch_solve();      // the next step's, should there be one
     GP_HIP(ctx, hipGetLastError());
     const int rc2 = wait_seq(it + 2);
     if (rc2 < 0) return rc2;
