@@ -417,20 +417,26 @@ __global__ __launch_bounds__(256) void ap_chol_panel_kernel(fac_t* __restrict__ 
     for (int v = 0; v < 4; ++v) Aik[(int64_t)acc_row(v) * BP + acc_col(cb)] = acc.b[cb][v];
 }
 
-// trailing update A_IJ -= L_Ik L_Jk^T for the tiles I >= J > k (I = k + 1 + blockIdx.y, J = k + 1 + blockIdx.x)
-__global__ __launch_bounds__(256) void ap_chol_update_kernel(fac_t* __restrict__ A, int BP, int k) {
+// trailing update A_IJ -= sum_{m = k0}^{k0 + klen - 1} L_Im L_Jm^T for the tiles I >= J, J = j0 + blockIdx.x
+// (blockIdx.x < gridDim.x), I = j0 + blockIdx.y.  The factorisation works in rounds of CHOL_ROUND tile
+// columns: inside a round the earlier columns are applied to the next column alone (one tile column),
+// and once the round is factorised all its columns are applied to the rest of the matrix together,
+// which reads and writes the trailing matrix once per round instead of once per column -- that traffic,
+// not the arithmetic, is what bounds the update.
+constexpr int CHOL_ROUND = 2;   // 4 measured no better: the one-column updates inside a round are few workgroups with longer chains
+__global__ __launch_bounds__(256) void ap_chol_update_kernel(fac_t* __restrict__ A, int BP, int k0, int klen, int j0) {
   __shared__ Tile TA, TB;
   if (blockIdx.x > blockIdx.y) return;
-  const int I = k + 1 + blockIdx.y, J = k + 1 + blockIdx.x;
+  const int I = j0 + blockIdx.y, J = j0 + blockIdx.x;
   fac_t* Ab = A + (int64_t)blockIdx.z * BP * BP;
   Acc acc;
   clear_acc(acc);
-  const fac_t* LI = Ab + (int64_t)I * TS * BP + k * TS;
-  const fac_t* LJ = Ab + (int64_t)J * TS * BP + k * TS;
+  const fac_t* LI = Ab + (int64_t)I * TS * BP;
+  const fac_t* LJ = Ab + (int64_t)J * TS * BP;
   const int64_t ldA = BP;
-  tile_chain<true, true>(TA, TB, acc, 0, 0,
-                         [=](int) { return Operand{LI, ldA}; },       // L_Ik(r, m)
-                         [=](int) { return Operand{LJ, ldA}; });      // L_Jk(c, m)
+  tile_chain<true, true>(TA, TB, acc, k0, k0 + klen - 1,
+                         [=](int m) { return Operand{LI + m * TS, ldA}; },       // L_Im(r, q)
+                         [=](int m) { return Operand{LJ + m * TS, ldA}; });      // L_Jm(c, q)
   fac_t* Aij = Ab + (int64_t)I * TS * BP + J * TS;
 #pragma unroll
   for (int cb = 0; cb < 4; ++cb)
@@ -1158,13 +1164,18 @@ int gp_ap_run(gp_ctx* ctx, const float* dB, int64_t ldb, const float* dX0, float
     const int cnt = L.nb - blk0 < L.batch ? L.nb - blk0 : L.batch;
     hipLaunchKernelGGL(ap_build_kernel, dim3(nt, nt, cnt), dim3(256), 2 * TS * (ctx->d + 1) * sizeof(float), st, ctx->dX,
                        ctx->d, n, (const double*)ctx->dTheta, ctx->kernel, block, BP, blk0, A);
-    for (int k = 0; k < nt; ++k) {
-      hipLaunchKernelGGL(ap_chol_diag_kernel, dim3(cnt), dim3(256), 0, st, A, BP, k, DI, W, fac_breakdown);
-      const int below = nt - k - 1;
-      if (below > 0) {
-        hipLaunchKernelGGL(ap_chol_panel_kernel, dim3(below, cnt), dim3(256), 0, st, A, BP, k, (const fac_t*)DI);
-        hipLaunchKernelGGL(ap_chol_update_kernel, dim3(below, below, cnt), dim3(256), 0, st, A, BP, k);
+    for (int k0 = 0; k0 < nt; k0 += CHOL_ROUND) {
+      const int k1 = k0 + CHOL_ROUND < nt ? k0 + CHOL_ROUND : nt;
+      for (int c = k0; c < k1; ++c) {
+        // the round's earlier columns applied to column c (tiles (I, c), I >= c)
+        if (c > k0) hipLaunchKernelGGL(ap_chol_update_kernel, dim3(1, nt - c, cnt), dim3(256), 0, st, A, BP, k0, c - k0, c);
+        hipLaunchKernelGGL(ap_chol_diag_kernel, dim3(cnt), dim3(256), 0, st, A, BP, c, DI, W, fac_breakdown);
+        if (nt - c - 1 > 0)
+          hipLaunchKernelGGL(ap_chol_panel_kernel, dim3(nt - c - 1, cnt), dim3(256), 0, st, A, BP, c, (const fac_t*)DI);
       }
+      // the whole round applied to everything past it
+      const int rest = nt - k1;
+      if (rest > 0) hipLaunchKernelGGL(ap_chol_update_kernel, dim3(rest, rest, cnt), dim3(256), 0, st, A, BP, k0, k1 - k0, k1);
     }
     for (int sz = 1; sz < nt; sz *= 2) {
       const int pairs = (nt + 2 * sz - 1) / (2 * sz);
