@@ -480,7 +480,11 @@ __global__ __launch_bounds__(256) void ap_trinv_merge_kernel(const fac_t* __rest
   const int pr = blockIdx.z % pairs, z = blockIdx.z / pairs;
   const int o1 = 2 * s * pr, o2 = o1 + s;
   const int s2 = nt - o2 < s ? nt - o2 : s;         // tiles in the second half (may be short or empty)
-  const int ti = blockIdx.y, tj = blockIdx.x;
+  // workgroups are dispatched x first, then y: the slow index is the one the chain length depends on,
+  // longest chains first (step 0: s - tj products, step 1: ti + 1), so that the launch does not end
+  // on a few long chains that started last
+  const int ti = step == 0 ? blockIdx.x : s - 1 - (int)blockIdx.y;
+  const int tj = step == 0 ? blockIdx.y : blockIdx.x;
   if (ti >= s2) return;
   const int64_t zo = (int64_t)z * BP * BP;
   const fac_t* P;      // left factor, tile (ti, m) at P + (ti * TS * BP + m * TS)
